@@ -1,0 +1,174 @@
+"""ctypes front end of the CPU checker in ``es_oracle.c``: TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg import this
+package.  Nothing here touches the HIP library, and the HIP package never
+imports this one.  Arrays are numpy; the noise matrix is dense ``[rows, D]``
+float32 (values already rounded to bf16 when the workload stores bf16 noise).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = [_HERE / "es_oracle.c", _HERE / "rollout_body.inc"]
+_LIB = _HERE / "liboracle.so"
+
+
+class OrcConfig(C.Structure):
+    _fields_ = [
+        ("pop", C.c_uint32), ("envs", C.c_uint32), ("horizon", C.c_uint32),
+        ("obs", C.c_uint32), ("hid", C.c_uint32), ("act", C.c_uint32),
+        ("dtype", C.c_uint32), ("noise_dtype", C.c_uint32),
+        ("antithetic", C.c_uint32), ("out_tanh", C.c_uint32),
+        ("sigma", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+        ("adam_eps", C.c_float), ("weight_decay", C.c_float),
+        ("done_thresh", C.c_float), ("act_cost", C.c_float),
+        ("seed", C.c_uint64),
+    ]
+
+
+def build(force: bool = False) -> Path:
+    """Compile the checker with gcc (contraction off so the binary32 sequences are exact)."""
+    stale = (not _LIB.exists()) or any(p.stat().st_mtime > _LIB.stat().st_mtime for p in _SRC)
+    if force or stale:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+                               "-o", str(tmp), str(_SRC[0]), "-lm"], cwd=str(_HERE))
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(str(build()))
+        _lib.orc_param_count.restype = C.c_size_t
+        _lib.orc_bf16_round.restype = C.c_float
+        _lib.orc_bf16_round.argtypes = [C.c_float]
+        _lib.orc_max_threads.restype = C.c_int
+    return _lib
+
+
+def config(w) -> OrcConfig:
+    """Build the checker's config from a workload description (any object with these fields)."""
+    c = OrcConfig()
+    for name, _ in OrcConfig._fields_:
+        setattr(c, name, getattr(w, name))
+    return c
+
+
+def _p(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def max_threads() -> int:
+    return int(lib().orc_max_threads())
+
+
+def param_count(w) -> int:
+    c = config(w)
+    return int(lib().orc_param_count(C.byref(c)))
+
+
+def philox4x32_10(ctr, key):
+    c = (C.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    out = (C.c_uint32 * 4)()
+    lib().orc_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def gauss_pair(xa: int, xb: int):
+    z = (C.c_float * 2)()
+    lib().orc_gauss_pair(C.c_uint32(xa), C.c_uint32(xb), z)
+    return float(z[0]), float(z[1])
+
+
+def bf16_round(x):
+    a = np.asarray(x, dtype=np.float32)
+    out = np.empty_like(a)
+    f = lib().orc_bf16_round
+    flat_in, flat_out = a.ravel(), out.ravel()
+    for i in range(flat_in.size):
+        flat_out[i] = f(float(flat_in[i]))
+    return out
+
+
+def sample_population(w, gen: int, rows=None) -> np.ndarray:
+    """Noise rows ``rows=(j0, j1)`` (default: all) of generation ``gen``: float32 ``[j1-j0, D]``."""
+    c = config(w)
+    d = param_count(w)
+    j0, j1 = (0, w.noise_rows) if rows is None else rows
+    out = np.empty((j1 - j0, d), dtype=np.float32)
+    lib().orc_sample_rows(C.byref(c), C.c_uint64(gen), C.c_uint32(j0), C.c_uint32(j1), _p(out, C.c_float))
+    return out
+
+
+def perturb(w, theta, noise, i: int) -> np.ndarray:
+    c = config(w)
+    theta, noise = _f32(theta), _f32(noise)
+    out = np.empty(param_count(w), dtype=np.float32)
+    lib().orc_perturb(C.byref(c), _p(theta, C.c_float), _p(noise, C.c_float), C.c_uint32(i), _p(out, C.c_float))
+    return out
+
+
+def reset(w, gen: int, e: int) -> np.ndarray:
+    c = config(w)
+    out = np.empty(w.obs, dtype=np.float32)
+    lib().orc_reset(C.byref(c), C.c_uint64(gen), C.c_uint32(e), _p(out, C.c_float))
+    return out
+
+
+def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: int = 0):
+    """Evaluate individuals ``(i0, i1)`` (default all).  ``noise`` is the FULL dense matrix.
+
+    Returns ``(returns [n,E] f32, ep_len [n,E] i32, fitness [n] f32, margin [n,E] f32)``.
+    """
+    c = config(w)
+    theta, noise, a_mat, b_mat = _f32(theta), _f32(noise), _f32(a_mat), _f32(b_mat)
+    assert noise.shape == (w.noise_rows, param_count(w))
+    i0, i1 = (0, w.pop) if individuals is None else individuals
+    n = i1 - i0
+    ret = np.empty((n, w.envs), dtype=np.float32)
+    ln = np.empty((n, w.envs), dtype=np.int32)
+    fit = np.empty(n, dtype=np.float32)
+    mar = np.empty((n, w.envs), dtype=np.float32)
+    lib().orc_rollout(C.byref(c), C.c_uint64(gen), _p(theta, C.c_float), _p(noise, C.c_float),
+                      _p(a_mat, C.c_float), _p(b_mat, C.c_float), C.c_uint32(i0), C.c_uint32(i1),
+                      C.c_int(arith), _p(ret, C.c_float), _p(ln, C.c_int32), _p(fit, C.c_float),
+                      _p(mar, C.c_float))
+    return ret, ln, fit, mar
+
+
+def rank(fitness):
+    f = _f32(fitness)
+    n = f.size
+    r = np.empty(n, dtype=np.int32)
+    u = np.empty(n, dtype=np.float32)
+    lib().orc_rank(C.c_uint32(n), _p(f, C.c_float), _p(r, C.c_int32), _p(u, C.c_float))
+    return r, u
+
+
+def update(w, adam_step: int, noise, shaped, theta, m, v):
+    """One gradient-estimate + Adam step.  Returns new ``(theta, m, v, g)`` (inputs untouched)."""
+    c = config(w)
+    noise, shaped = _f32(noise), _f32(shaped)
+    assert noise.shape == (w.noise_rows, param_count(w)) and shaped.size == w.pop
+    th, mm, vv = (np.array(x, dtype=np.float32, copy=True) for x in (theta, m, v))
+    g = np.empty(param_count(w), dtype=np.float32)
+    lib().orc_update(C.byref(c), C.c_uint64(adam_step), _p(noise, C.c_float), _p(shaped, C.c_float),
+                     _p(th, C.c_float), _p(mm, C.c_float), _p(vv, C.c_float), _p(g, C.c_float))
+    return th, mm, vv, g

@@ -1,0 +1,110 @@
+"""Seeded synthetic workloads: the five benchmark shapes and their input arrays.
+
+This module only *draws inputs* (environment matrices, the initial parameter
+vector, zeroed optimiser moments).  It contains none of the method's arithmetic
+(no noise stream, no perturbation, no rollout, no ranking, no optimiser) so
+that the HIP path and the CPU checker can both be fed from it without sharing
+any code of the method itself.
+
+The environment is a stand-in for the locomotion simulators the paper times
+on (Sec. 5.1, fixed-length episodes of 1000 steps; Sec. 5.2 population size and
+[256,256] networks): a state vector of locomotion-task width, a dense policy
+MLP, a per-step reward and an early-termination rule.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+import math
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    """Static description of one OpenES generation (paper Sec. 3.3, 5.1, App. B Table 5b)."""
+    name: str
+    pop: int            # N, population size
+    envs: int           # E, environment copies (episodes) per individual
+    horizon: int        # T, maximum episode length
+    obs: int            # n_o
+    hid: int            # n_h (two hidden layers)
+    act: int            # n_a
+    dtype: int          # 0: fp32 ; 1: bf16 contraction operands, fp32 accumulate
+    noise_dtype: int    # 0: fp32 noise matrix ; 1: bf16 noise matrix
+    seed: int
+    sigma: float = 0.02
+    lr: float = 0.01
+    beta1: float = 0.9
+    beta2: float = 0.999
+    adam_eps: float = 1e-8
+    weight_decay: float = 0.005
+    done_thresh: float = 0.95
+    act_cost: float = 0.01
+    antithetic: int = 1
+    out_tanh: int = 1
+
+    @property
+    def n_params(self) -> int:
+        o, h, a = self.obs, self.hid, self.act
+        return (o + 1) * h + (h + 1) * h + (h + 1) * a
+
+    @property
+    def noise_rows(self) -> int:
+        return self.pop // 2 if self.antithetic else self.pop
+
+    @property
+    def env_steps(self) -> int:
+        return self.pop * self.envs * self.horizon
+
+    def fixed_length(self) -> "Workload":
+        """Same workload with the termination rule switched off (every episode runs T steps)."""
+        return replace(self, name=self.name + "-fixedlen", done_thresh=math.inf)
+
+
+CONFIGS = (
+    Workload("cfg0", pop=8, envs=4, horizon=100, obs=11, hid=32, act=3, dtype=0, noise_dtype=0, seed=0),
+    Workload("cfg1", pop=16, envs=16, horizon=1000, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=1),
+    Workload("cfg2", pop=256, envs=1, horizon=1000, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=2),
+    Workload("cfg3", pop=1024, envs=16, horizon=1000, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=3),
+    Workload("cfg4", pop=4096, envs=4, horizon=1000, obs=244, hid=256, act=17, dtype=1, noise_dtype=1, seed=4),
+)
+
+
+def layer_shapes(w: Workload):
+    """(rows, cols) of W1, b1, W2, b2, W3, b3 in flat-parameter order; matrices are [out, in] row-major."""
+    o, h, a = w.obs, w.hid, w.act
+    return ((h, o), (h,), (h, h), (h,), (a, h), (a,))
+
+
+def make_inputs(w: Workload):
+    """Draw A [n_o,n_o], B [n_o,n_a], theta0 [D] (float32) for a workload, from its seed.
+
+    A: i.i.d. N(0,1) rescaled to spectral radius 0.9.  B: i.i.d. N(0, 1/3).
+    theta0: every weight matrix N(0, 2/(fan_in+fan_out)), biases zero.
+    """
+    rng = np.random.default_rng([int(w.seed), 0x45534D49])
+    g = rng.standard_normal((w.obs, w.obs))
+    rho = float(np.max(np.abs(np.linalg.eigvals(g))))
+    a_mat = (0.9 / rho) * g
+    b_mat = rng.standard_normal((w.obs, w.act)) * math.sqrt(1.0 / 3.0)
+    parts = []
+    for shp in layer_shapes(w):
+        if len(shp) == 2:
+            fan_out, fan_in = shp
+            parts.append((rng.standard_normal(shp) * math.sqrt(2.0 / (fan_in + fan_out))).ravel())
+        else:
+            parts.append(np.zeros(shp))
+    theta0 = np.concatenate(parts)
+    assert theta0.size == w.n_params
+    return (np.ascontiguousarray(a_mat, dtype=np.float32),
+            np.ascontiguousarray(b_mat, dtype=np.float32),
+            np.ascontiguousarray(theta0, dtype=np.float32))
+
+
+def random_fitness(n: int, seed: int, ties: bool = False) -> np.ndarray:
+    """A seeded fitness vector for exercising the ranking / update stages on their own."""
+    rng = np.random.default_rng([seed, 0x46495421])
+    f = rng.standard_normal(n).astype(np.float32) * 100.0
+    if ties and n >= 4:
+        f[rng.integers(0, n, size=n // 4)] = f[0]
+    return f

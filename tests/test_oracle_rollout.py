@@ -1,0 +1,210 @@
+"""Pins for the CPU checker's rollout: closed forms, special cases, a library-based
+one-step evaluation and a pure-Python enumeration on tiny inputs."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2501_15129_amd.workloads import Workload, make_inputs, layer_shapes
+
+W = Workload("tiny", pop=6, envs=3, horizon=7, obs=5, hid=8, act=2, dtype=0, noise_dtype=0, seed=21)
+
+
+def _unpack(w, theta):
+    out, off = [], 0
+    for shp in layer_shapes(w):
+        n = int(np.prod(shp))
+        out.append(np.asarray(theta[off:off + n], dtype=np.float64).reshape(shp))
+        off += n
+    return out
+
+
+def _policy_torch(w, theta, s):
+    w1, b1, w2, b2, w3, b3 = (torch.from_numpy(x) for x in _unpack(w, theta))
+    x = torch.from_numpy(np.asarray(s, dtype=np.float64))
+    h1 = torch.tanh(F.linear(x, w1, b1))
+    h2 = torch.tanh(F.linear(h1, w2, b2))
+    a = F.linear(h2, w3, b3)
+    return (torch.tanh(a) if w.out_tanh else a).numpy()
+
+
+def test_sigma_zero_gives_identical_fitness():
+    a_mat, b_mat, theta = make_inputs(W)
+    w0 = replace(W, sigma=0.0)
+    eps = oracle.sample_population(w0, 0)
+    ret, ln, fit, _ = oracle.rollout(w0, 0, theta, eps, a_mat, b_mat)
+    assert np.all(fit.view(np.uint32) == fit.view(np.uint32)[0])
+    assert np.all(ret == ret[0]) and np.all(ln == ln[0])
+    # ... and with sigma > 0 they differ
+    eps = oracle.sample_population(W, 0)
+    _, _, fit, _ = oracle.rollout(W, 0, theta, eps, a_mat, b_mat)
+    assert len(set(fit.tolist())) == W.pop
+
+
+def test_one_step_return_against_library_forward():
+    for out_tanh in (1, 0):
+        w = replace(W, horizon=1, out_tanh=out_tanh)
+        a_mat, b_mat, theta = make_inputs(w)
+        eps = oracle.sample_population(w, 4)
+        ret, ln, fit, _ = oracle.rollout(w, 4, theta, eps, a_mat, b_mat)
+        for i in range(w.pop):
+            th = oracle.perturb(w, theta, eps, i)
+            for e in range(w.envs):
+                s0 = oracle.reset(w, 4, e).astype(np.float64)
+                act = _policy_torch(w, th, s0)
+                want = 1.0 - np.dot(s0, s0) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+                assert abs(ret[i, e] - want) < 1e-6
+                assert ln[i, e] == 1
+        assert np.allclose(fit, ret.astype(np.float64).mean(axis=1), rtol=1e-6)
+
+
+def test_multi_step_against_library_forward():
+    w = replace(W, horizon=6, done_thresh=math.inf)
+    a_mat, b_mat, theta = make_inputs(w)
+    eps = oracle.sample_population(w, 1)
+    ret, ln, _, _ = oracle.rollout(w, 1, theta, eps, a_mat, b_mat)
+    a64, b64 = a_mat.astype(np.float64), b_mat.astype(np.float64)
+    for i in (0, 3):
+        th = oracle.perturb(w, theta, eps, i)
+        for e in range(w.envs):
+            s = oracle.reset(w, 1, e).astype(np.float64)
+            total = 0.0
+            for _ in range(w.horizon):
+                act = _policy_torch(w, th, s)
+                total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+                s = np.tanh(a64 @ s + b64 @ act)
+            assert abs(ret[i, e] - total) < 1e-5 and ln[i, e] == w.horizon
+
+
+def test_zero_policy_closed_forms():
+    w = replace(W, horizon=9, sigma=0.0, done_thresh=math.inf)
+    a_mat, b_mat, _ = make_inputs(w)
+    theta = np.zeros(w.n_params, dtype=np.float32)
+    eps = oracle.sample_population(w, 0)
+    # zero weights: action 0, s' = tanh(A s): R = sum_t (1 - |s_t|^2 / n_o)
+    ret, ln, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+    for e in range(w.envs):
+        s = oracle.reset(w, 0, e).astype(np.float64)
+        total = 0.0
+        for _ in range(w.horizon):
+            total += 1.0 - np.dot(s, s) / w.obs
+            s = np.tanh(a_mat.astype(np.float64) @ s)
+        assert abs(ret[0, e] - total) < 1e-5
+    # A = 0 too: the state is 0 from step 1 on, so R = r_0 + (T - 1)
+    ret, ln, _, _ = oracle.rollout(w, 0, theta, eps, np.zeros_like(a_mat), b_mat)
+    for e in range(w.envs):
+        s0 = oracle.reset(w, 0, e).astype(np.float64)
+        assert abs(ret[0, e] - ((1.0 - np.dot(s0, s0) / w.obs) + (w.horizon - 1))) < 1e-5
+    assert np.all(ln == w.horizon)
+    # only the last bias set: a = tanh(b3) constant, A = 0: s_t = tanh(B a) for t >= 1
+    theta_b = theta.copy()
+    theta_b[-w.act:] = np.array([0.7, -1.3], dtype=np.float32)
+    ret, _, _, _ = oracle.rollout(w, 0, theta_b, eps, np.zeros_like(a_mat), b_mat)
+    act = np.tanh(theta_b[-w.act:].astype(np.float64))
+    s1 = np.tanh(b_mat.astype(np.float64) @ act)
+    cost = float(np.float32(w.act_cost)) * np.dot(act, act)
+    for e in range(w.envs):
+        s0 = oracle.reset(w, 0, e).astype(np.float64)
+        want = (1.0 - np.dot(s0, s0) / w.obs - cost) + (w.horizon - 1) * (1.0 - np.dot(s1, s1) / w.obs - cost)
+        assert abs(ret[0, e] - want) < 1e-5
+
+
+def test_termination_rule_and_indexing():
+    a_mat, b_mat, theta = make_inputs(W)
+    eps = oracle.sample_population(W, 0)
+    # a threshold below every reachable |s| ends each episode after its first step,
+    # and that step's reward counts
+    w = replace(W, done_thresh=1e-6)
+    ret, ln, _, mar = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+    ret1, _, _, _ = oracle.rollout(replace(W, horizon=1), 0, theta, eps, a_mat, b_mat)
+    assert np.all(ln == 1) and np.array_equal(ret, ret1)
+    # threshold never reached (|tanh| < 1): full length
+    w = replace(W, done_thresh=1.0)
+    _, ln, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+    assert np.all(ln == W.horizon)
+    # the test is on s_{t+1}: with A = c*I, zero policy, |s| grows as tanh(c s) and the
+    # episode length is the first t with max|s_t| > thresh, counted from s_1
+    theta0 = np.zeros_like(theta)
+    big = (3.0 * np.eye(W.obs)).astype(np.float32)
+    w = replace(W, sigma=0.0, horizon=50, done_thresh=0.9)
+    ret, ln, _, mar = oracle.rollout(w, 0, theta0, eps, big, b_mat)
+    for e in range(w.envs):
+        s = oracle.reset(w, 0, e).astype(np.float64)
+        t, total = 0, 0.0
+        while True:
+            total += 1.0 - np.dot(s, s) / w.obs
+            t += 1
+            s = np.tanh(3.0 * s)
+            if np.max(np.abs(s)) > np.float32(0.9) or t == w.horizon:
+                break
+        assert ln[0, e] == t and abs(ret[0, e] - total) < 1e-5
+        assert mar[0, e] > 0
+
+
+def test_two_individual_enumeration_pure_python():
+    """N = 2 (one mirrored pair), E = 1, T in {1, 2}: everything recomputed with scalar Python."""
+    for horizon in (1, 2):
+        w = Workload("enum", pop=2, envs=1, horizon=horizon, obs=2, hid=2, act=1, dtype=0, noise_dtype=0,
+                     seed=5, done_thresh=math.inf)
+        a_mat, b_mat, theta = make_inputs(w)
+        eps = oracle.sample_population(w, 0)
+        ret, ln, fit, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+        s_init = [float(x) for x in oracle.reset(w, 0, 0)]
+        sig = float(np.float32(w.sigma))
+        for i, sign in ((0, 1.0), (1, -1.0)):
+            th = [float(np.float32(float(theta[d]) + sign * sig * float(eps[0, d]))) for d in range(w.n_params)]
+            w1 = [th[0:2], th[2:4]]; b1 = th[4:6]
+            w2 = [th[6:8], th[8:10]]; b2 = th[10:12]
+            w3 = th[12:14]; b3 = th[14]
+            s = list(s_init)
+            total = 0.0
+            for _ in range(horizon):
+                h1 = [math.tanh(w1[u][0] * s[0] + w1[u][1] * s[1] + b1[u]) for u in range(2)]
+                h2 = [math.tanh(w2[u][0] * h1[0] + w2[u][1] * h1[1] + b2[u]) for u in range(2)]
+                act = math.tanh(w3[0] * h2[0] + w3[1] * h2[1] + b3)
+                total += 1.0 - (s[0] ** 2 + s[1] ** 2) / 2.0 - float(np.float32(0.01)) * act * act
+                s = [math.tanh(float(a_mat[k, 0]) * s[0] + float(a_mat[k, 1]) * s[1] + float(b_mat[k, 0]) * act)
+                     for k in range(2)]
+            assert abs(ret[i, 0] - total) < 1e-6
+            assert abs(fit[i] - total) < 1e-6
+
+
+def test_bf16_mode_one_step_against_library_rounding():
+    w = replace(W, dtype=1, noise_dtype=1, horizon=2, done_thresh=math.inf)
+    a_mat, b_mat, theta = make_inputs(w)
+    eps = oracle.sample_population(w, 0)
+    ret, _, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+
+    def q(x):   # value -> binary32 -> bf16, by the library's own conversion
+        return torch.from_numpy(np.asarray(x, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+    aq, bq = q(a_mat), q(b_mat)
+    for i in (0, 5):
+        th = oracle.perturb(w, theta, eps, i)          # already bf16 values
+        assert np.array_equal(th, q(th).astype(np.float32))
+        w1, b1, w2, b2, w3, b3 = _unpack(w, th)
+        for e in range(w.envs):
+            s = oracle.reset(w, 0, e).astype(np.float64)
+            total = 0.0
+            for _ in range(w.horizon):
+                x = q(s)
+                h1 = q(np.tanh(w1 @ x + b1))
+                h2 = q(np.tanh(w2 @ h1 + b2))
+                act = np.tanh(w3 @ h2 + b3)
+                total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+                s = np.tanh(aq @ x + bq @ q(act))
+            assert abs(ret[i, e] - total) < 1e-6
+
+
+def test_subrange_and_binary32_probe():
+    a_mat, b_mat, theta = make_inputs(W)
+    eps = oracle.sample_population(W, 2)
+    full = oracle.rollout(W, 2, theta, eps, a_mat, b_mat)
+    part = oracle.rollout(W, 2, theta, eps, a_mat, b_mat, individuals=(2, 5))
+    for x, y in zip(full, part):
+        assert np.array_equal(x[2:5], y)
+    probe = oracle.rollout(W, 2, theta, eps, a_mat, b_mat, arith=1)
+    assert np.allclose(probe[0], full[0], rtol=1e-5) and np.array_equal(probe[1], full[1])
