@@ -1,0 +1,140 @@
+/*
+ * es.h - C boundary of the MI355X (gfx950) OpenES hot path.
+ *
+ * One generation of the evolutionary policy search of arXiv 2501.15129 is four
+ * enqueues on one HIP stream, with no host synchronisation in between (the paper's
+ * Workflow.step() runs as one device program: Sec. 3.1, Sec. 3.3):
+ *
+ *     es_sample_population -> es_rollout -> es_rank -> es_update
+ *
+ * Conventions
+ *   - Every pointer whose name ends in _d is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or retains device memory; the buffers must stay
+ *     valid until the work enqueued on `stream` has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every hot
+ *     call only enqueues kernels; none of them synchronises or reads back.
+ *   - Return value: ES_OK (0) or a negative es_status.  Nothing throws or aborts;
+ *     es_strerror() names the code and es_last_error() gives the detail of the last
+ *     failure on that context.  Arguments are validated on the host BEFORE any launch,
+ *     so a failing call enqueues nothing.
+ *   - Determinism: no floating-point atomics; the same inputs give bit-identical
+ *     outputs on every run.
+ *   - N = pop, E = envs_per_ind, T = horizon, D = es_param_count().
+ *
+ * Flat parameter vector theta[D] (binary32): W1[hid,obs], b1[hid], W2[hid,hid], b2[hid],
+ * W3[act,hid], b3[act], in this order, each matrix row-major [out,in].
+ *
+ * Noise matrix: es_noise_rows() rows (N/2 with mirrored sampling, else N), row stride
+ * es_noise_ld() ELEMENTS (D rounded up so that every row starts 1 KiB-aligned), element
+ * type binary32 (noise_dtype 0) or bf16 bit patterns (noise_dtype 1).  Columns
+ * D <= d < ld are written as zero by es_sample_population and must be zero if the caller
+ * fills the matrix itself.
+ */
+#ifndef ES_H_
+#define ES_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum es_status {
+  ES_OK = 0,
+  ES_EINVAL = -1,       /* null pointer, zero dimension, odd pop with mirrored sampling, ... */
+  ES_EUNSUPPORTED = -2, /* a shape or mode no kernel of this build can place on chip        */
+  ES_EHIP = -3          /* the HIP runtime reported an error (text in es_last_error)        */
+} es_status;
+
+typedef struct es_config {
+  uint32_t pop;          /* N; must be even when antithetic = 1                              */
+  uint32_t envs_per_ind; /* E: environment copies = episodes per fitness evaluation          */
+  uint32_t horizon;      /* T: maximum episode length                                        */
+  uint32_t obs_dim, hid_dim, act_dim; /* policy MLP obs -> hid -> hid -> act                 */
+  uint32_t dtype;        /* 0: binary32 everywhere.  1: every operand of a matrix product
+                            (perturbed weights and biases, env matrices A and B, the state,
+                            hidden activations and action as inputs of the next product) is
+                            rounded to bf16; accumulation, tanh, reward, return are binary32 */
+  uint32_t noise_dtype;  /* 0: binary32 noise matrix ; 1: bf16 noise matrix                  */
+  uint32_t antithetic;   /* 1: individuals 2j and 2j+1 use +eps_j and -eps_j                 */
+  uint32_t out_tanh;     /* 1: tanh on the action layer as well                              */
+  float sigma;           /* noise std (paper App. B Table 5b: 0.02)                          */
+  float lr, beta1, beta2, adam_eps; /* Adam (Table 5b: lr 0.01)                              */
+  float weight_decay;    /* L2 coefficient added to the gradient (Table 5b: 0.005)           */
+  float done_thresh;     /* episode ends after the step whose new state has max|s| > this;
+                            +inf = fixed-length episodes (the paper's timing protocol, Sec. 5.1) */
+  float act_cost;        /* reward = 1 - |s|^2/obs_dim - act_cost |a|^2                      */
+  uint64_t seed;         /* key of the counter-based noise / reset streams                   */
+} es_config;
+
+typedef struct es_ctx es_ctx; /* opaque, host-side: validated config + kernel choice */
+
+/* Validate `cfg` and build a context.  Allocates host memory only.  Must be called with the
+ * target GPU current; the kernel choice depends on that device's LDS size. */
+int es_create(const es_config* cfg, es_ctx** out);
+int es_destroy(es_ctx* ctx);
+
+size_t es_param_count(const es_ctx* ctx);      /* D                                           */
+size_t es_noise_rows(const es_ctx* ctx);       /* N/2 (mirrored) or N                         */
+size_t es_noise_ld(const es_ctx* ctx);         /* row stride of the noise matrix, in elements */
+size_t es_noise_bytes(const es_ctx* ctx);      /* rows * ld * sizeof(element)                 */
+size_t es_workspace_bytes(const es_ctx* ctx);  /* scratch for es_rollout / es_update (>= 256) */
+const char* es_rollout_kernel(const es_ctx* ctx); /* name of the rollout variant chosen       */
+const char* es_strerror(int status);
+const char* es_last_error(const es_ctx* ctx);
+
+/*
+ * Noise of generation `generation` (paper Sec. 5.1: perturbations are generated on the fly
+ * each generation, not read from a pre-built table).  noise[j, d] for j < rows, d < D is
+ * variate (d mod 4) of the Philox4x32-10 block with counter (d / 4, j, generation, 1) and
+ * key (seed low, seed high), mapped to N(0,1) by a fixed binary32 Box-Muller sequence, then
+ * rounded to bf16 (nearest-even) when noise_dtype = 1.  generation < 2^32.
+ * Writes rows * ld elements to noise_d.
+ */
+int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream);
+
+/*
+ * Population x environment evaluation (paper Sec. 3.3: all individuals at once, each on E
+ * parallel environment copies; Sec. 5.2: deterministic MLP policy, fitness = mean
+ * undiscounted episodic return).  For individual i (noise row j = i/2, sign +/- when
+ * mirrored, else j = i, +):
+ *     theta_i = fma(sign * sigma, noise[j, :], theta)        (binary32; bf16-rounded if dtype 1)
+ *     s_0[e]  = uniform[-0.1, 0.1) from Philox counter (k / 4, e, generation, 2), the same for all i
+ *     per step: h1 = tanh(W1 s + b1), h2 = tanh(W2 h1 + b2), a = tanh(W3 h2 + b3),
+ *               r = 1 - |s|^2/obs_dim - act_cost |a|^2,  R += r,  L += 1,
+ *               s <- tanh(A s + B a),  stop after this step if max|s| > done_thresh.
+ * In:  theta_d [D] f32, noise_d (layout above), A_d [obs,obs] f32, B_d [obs,act] f32 (row-major).
+ * Out: returns_d [N,E] f32, ep_len_d [N,E] i32, fitness_d [N] f32 (mean over E).
+ * workspace_d: es_workspace_bytes() bytes, contents irrelevant on entry.
+ */
+int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const void* noise_d,
+               const float* A_d, const float* B_d, float* returns_d, int32_t* ep_len_d,
+               float* fitness_d, void* workspace_d, void* stream);
+
+/*
+ * Centred-rank fitness shaping (the OpenES of the paper's Sec. 4.2, after Salimans et al.):
+ * rank_i = position of individual i in ascending fitness order, ties broken by index
+ * (-0 equals +0; NaNs sort by bit pattern, no error); shaped_i = rank_i / (N-1) - 1/2.
+ * In: fitness_d [N] f32.  Out: rank_d [N] i32, shaped_d [N] f32.
+ */
+int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_d, void* stream);
+
+/*
+ * Search-gradient estimate and Adam step (paper App. B Table 5b: Adam, lr 0.01, weight decay 0.005):
+ *     g[d]  = 1/(N sigma) * sum_i shaped_i * sign_i * noise[row(i), d]
+ *     grad  = -g + weight_decay * theta ;  m, v = Adam moments ;  k = adam_step >= 1
+ *     theta <- theta - lr * (m / (1 - beta1^k)) / (sqrt(v / (1 - beta2^k)) + adam_eps)
+ * The noise matrix is streamed exactly once; sums are taken in binary64 in a fixed order.
+ * In: noise_d, shaped_d [N] f32.  In/out: theta_d, m_d, v_d [D] f32.
+ * Out (optional, may be NULL): grad_d [D] f32 receives g.
+ * workspace_d: es_workspace_bytes() bytes.  sigma must be > 0.
+ */
+int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d,
+              float* theta_d, float* m_d, float* v_d, float* grad_d, void* workspace_d,
+              void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ES_H_ */

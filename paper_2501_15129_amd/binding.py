@@ -1,0 +1,163 @@
+"""Thin ctypes binding of the C boundary in ``include/es.h``.
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels of
+``libes_hip.so``.  PyTorch supplies device memory (``tensor.data_ptr()``) and the stream.
+There is no CPU fallback: if the library is missing, importing fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libes_hip.so"
+
+ES_OK, ES_EINVAL, ES_EUNSUPPORTED, ES_EHIP = 0, -1, -2, -3
+
+
+class EsConfig(C.Structure):
+    """Mirror of ``struct es_config``."""
+    _fields_ = [
+        ("pop", C.c_uint32), ("envs_per_ind", C.c_uint32), ("horizon", C.c_uint32),
+        ("obs_dim", C.c_uint32), ("hid_dim", C.c_uint32), ("act_dim", C.c_uint32),
+        ("dtype", C.c_uint32), ("noise_dtype", C.c_uint32),
+        ("antithetic", C.c_uint32), ("out_tanh", C.c_uint32),
+        ("sigma", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+        ("adam_eps", C.c_float), ("weight_decay", C.c_float),
+        ("done_thresh", C.c_float), ("act_cost", C.c_float),
+        ("seed", C.c_uint64),
+    ]
+
+
+class EsError(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__(f"{name} ({detail})" if detail else name)
+        self.status = status
+
+
+def load_library() -> C.CDLL:
+    if not _LIB_PATH.exists():
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2501_15129_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(str(_LIB_PATH))
+    vp, u64, sz = C.c_void_p, C.c_uint64, C.c_size_t
+    lib.es_create.argtypes = [C.POINTER(EsConfig), C.POINTER(vp)]
+    lib.es_destroy.argtypes = [vp]
+    for fn in ("es_param_count", "es_noise_rows", "es_noise_ld", "es_noise_bytes", "es_workspace_bytes"):
+        getattr(lib, fn).argtypes = [vp]
+        getattr(lib, fn).restype = sz
+    lib.es_rollout_kernel.argtypes = [vp]
+    lib.es_rollout_kernel.restype = C.c_char_p
+    lib.es_strerror.argtypes = [C.c_int]
+    lib.es_strerror.restype = C.c_char_p
+    lib.es_last_error.argtypes = [vp]
+    lib.es_last_error.restype = C.c_char_p
+    lib.es_sample_population.argtypes = [vp, u64, vp, vp]
+    lib.es_rollout.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.es_rank.argtypes = [vp, vp, vp, vp, vp]
+    lib.es_update.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp]
+    return lib
+
+
+_lib = load_library()
+
+
+def make_config(w) -> EsConfig:
+    """Build an ``es_config`` from a workload description (fields of ``workloads.Workload``)."""
+    return EsConfig(pop=w.pop, envs_per_ind=w.envs, horizon=w.horizon, obs_dim=w.obs, hid_dim=w.hid,
+                    act_dim=w.act, dtype=w.dtype, noise_dtype=w.noise_dtype, antithetic=w.antithetic,
+                    out_tanh=w.out_tanh, sigma=w.sigma, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
+                    adam_eps=w.adam_eps, weight_decay=w.weight_decay, done_thresh=w.done_thresh,
+                    act_cost=w.act_cost, seed=w.seed)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t, dtype, numel, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: needs {numel} elements, got {t.numel()}")
+    return t.data_ptr()
+
+
+class EsContext:
+    """Owns one ``es_ctx``.  Method names and argument order follow ``include/es.h``."""
+
+    def __init__(self, cfg):
+        self.cfg = cfg if isinstance(cfg, EsConfig) else make_config(cfg)
+        h = C.c_void_p()
+        rc = _lib.es_create(C.byref(self.cfg), C.byref(h))
+        if rc != ES_OK:
+            raise EsError(rc, _lib.es_strerror(rc).decode(), _lib.es_last_error(None).decode())
+        self._h = h
+        self.param_count = int(_lib.es_param_count(h))
+        self.noise_rows = int(_lib.es_noise_rows(h))
+        self.noise_ld = int(_lib.es_noise_ld(h))
+        self.noise_bytes = int(_lib.es_noise_bytes(h))
+        self.workspace_bytes = int(_lib.es_workspace_bytes(h))
+        self.rollout_kernel = _lib.es_rollout_kernel(h).decode()
+        self.noise_torch_dtype = torch.bfloat16 if self.cfg.noise_dtype == 1 else torch.float32
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.es_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def _check(self, rc):
+        if rc != ES_OK:
+            raise EsError(rc, _lib.es_strerror(rc).decode(), _lib.es_last_error(self._h).decode())
+
+    # -- buffers (plumbing: torch owns the memory) --------------------------------
+    def alloc_noise(self, device="cuda"):
+        return torch.empty((self.noise_rows, self.noise_ld), dtype=self.noise_torch_dtype, device=device)
+
+    def alloc_workspace(self, device="cuda"):
+        return torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+
+    # -- the four hot calls ---------------------------------------------------------
+    def sample_population(self, generation: int, noise):
+        n = self.noise_rows * self.noise_ld
+        self._check(_lib.es_sample_population(self._h, generation, _ptr(noise, self.noise_torch_dtype, n, "noise"),
+                                              _stream()))
+
+    def rollout(self, generation: int, theta, noise, a_mat, b_mat, returns, ep_len, fitness, workspace):
+        c = self.cfg
+        f32, n = torch.float32, self.noise_rows * self.noise_ld
+        self._check(_lib.es_rollout(
+            self._h, generation, _ptr(theta, f32, self.param_count, "theta"),
+            _ptr(noise, self.noise_torch_dtype, n, "noise"),
+            _ptr(a_mat, f32, c.obs_dim * c.obs_dim, "A"), _ptr(b_mat, f32, c.obs_dim * c.act_dim, "B"),
+            _ptr(returns, f32, c.pop * c.envs_per_ind, "returns"),
+            _ptr(ep_len, torch.int32, c.pop * c.envs_per_ind, "ep_len"),
+            _ptr(fitness, f32, c.pop, "fitness"),
+            _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
+
+    def rank(self, fitness, rank, shaped):
+        n = self.cfg.pop
+        self._check(_lib.es_rank(self._h, _ptr(fitness, torch.float32, n, "fitness"),
+                                 _ptr(rank, torch.int32, n, "rank"), _ptr(shaped, torch.float32, n, "shaped"),
+                                 _stream()))
+
+    def update(self, adam_step: int, noise, shaped, theta, m, v, grad, workspace):
+        f32, d, n = torch.float32, self.param_count, self.noise_rows * self.noise_ld
+        self._check(_lib.es_update(
+            self._h, adam_step, _ptr(noise, self.noise_torch_dtype, n, "noise"),
+            _ptr(shaped, f32, self.cfg.pop, "shaped"), _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"),
+            _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"),
+            _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
+
+
+def raw_library() -> C.CDLL:
+    """The loaded ``libes_hip.so`` (for tests that exercise the C boundary's error paths)."""
+    return _lib

@@ -1,0 +1,156 @@
+// Host side of the C boundary: validation, context, dispatch.  See include/es.h for the
+// contract of every entry point.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "es_internal.hpp"
+
+namespace es {
+
+uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16);
+
+int fail(es_ctx* ctx, int code, const std::string& what) {
+  if (ctx) ctx->last_error = what;
+  return code;
+}
+
+int check_launch(es_ctx* ctx, const char* what) {
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return fail(ctx, ES_EHIP, std::string(what) + ": " + hipGetErrorString(err));
+  return ES_OK;
+}
+
+static thread_local std::string g_create_error;
+
+}  // namespace es
+
+using namespace es;
+
+extern "C" {
+
+const char* es_strerror(int status) {
+  switch (status) {
+    case ES_OK: return "ES_OK";
+    case ES_EINVAL: return "ES_EINVAL: invalid argument";
+    case ES_EUNSUPPORTED: return "ES_EUNSUPPORTED: no kernel of this build supports the requested shape or mode";
+    case ES_EHIP: return "ES_EHIP: HIP runtime error";
+    default: return "unknown es_status";
+  }
+}
+
+const char* es_last_error(const es_ctx* ctx) { return ctx ? ctx->last_error.c_str() : g_create_error.c_str(); }
+
+int es_create(const es_config* cfg, es_ctx** out) {
+  g_create_error.clear();
+  if (!cfg || !out) { g_create_error = "es_create: null argument"; return ES_EINVAL; }
+  *out = nullptr;
+  const es_config& c = *cfg;
+  auto bad = [&](const char* why) { g_create_error = std::string("es_create: ") + why; return (int)ES_EINVAL; };
+  if (c.pop == 0 || c.envs_per_ind == 0 || c.horizon == 0) return bad("pop, envs_per_ind and horizon must be positive");
+  if (c.obs_dim == 0 || c.hid_dim == 0 || c.act_dim == 0) return bad("layer widths must be positive");
+  if (c.dtype > 1 || c.noise_dtype > 1) return bad("dtype and noise_dtype must be 0 or 1");
+  if (c.antithetic > 1 || c.out_tanh > 1) return bad("antithetic and out_tanh must be 0 or 1");
+  if (c.antithetic && (c.pop & 1u)) return bad("pop must be even with mirrored sampling");
+  if (!(c.sigma >= 0.0f) || !std::isfinite(c.sigma)) return bad("sigma must be finite and >= 0");
+  if (std::isnan(c.done_thresh)) return bad("done_thresh is NaN");
+  if (!std::isfinite(c.lr) || !std::isfinite(c.weight_decay) || !std::isfinite(c.act_cost)) return bad("non-finite hyper-parameter");
+  if (!(c.beta1 >= 0.0f && c.beta1 < 1.0f) || !(c.beta2 >= 0.0f && c.beta2 < 1.0f)) return bad("betas must lie in [0, 1)");
+  if (!(c.adam_eps > 0.0f)) return bad("adam_eps must be positive");
+  const uint64_t o = c.obs_dim, h = c.hid_dim, a = c.act_dim;
+  const uint64_t D = (o + 1) * h + (h + 1) * h + (h + 1) * a;
+  if (D > (1ull << 30) || (uint64_t)c.pop * c.envs_per_ind > (1ull << 30) || c.obs_dim > 65535 || c.hid_dim > 65535)
+    return bad("shape too large");
+
+  es_ctx* ctx = new (std::nothrow) es_ctx();
+  if (!ctx) { g_create_error = "es_create: out of host memory"; return ES_EINVAL; }
+  ctx->cfg = c;
+  Shape& s = ctx->shp;
+  s.N = c.pop; s.E = c.envs_per_ind; s.T = c.horizon; s.no = c.obs_dim; s.nh = c.hid_dim; s.na = c.act_dim;
+  s.D = (uint32_t)D;
+  s.ld = (s.D + NOISE_LD_ALIGN - 1) / NOISE_LD_ALIGN * NOISE_LD_ALIGN;
+  s.rows = c.antithetic ? c.pop / 2 : c.pop;
+  s.oW1 = 0; s.ob1 = (uint32_t)(h * o); s.oW2 = s.ob1 + (uint32_t)h; s.ob2 = s.oW2 + (uint32_t)(h * h);
+  s.oW3 = s.ob2 + (uint32_t)h; s.ob3 = s.oW3 + (uint32_t)(a * h);
+
+  int dev = 0, lds = 65536;
+  if (hipGetDevice(&dev) == hipSuccess) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0) lds = v;
+  } else {
+    (void)hipGetLastError();   // no device here (host-only checks): keep the conservative default
+  }
+  ctx->lds_limit = lds;
+  ctx->lds_bytes_wave = wave_rollout_lds_bytes(c);
+  ctx->mfma_variant = mfma_variant_for(c);
+  if (ctx->mfma_variant >= 0) {
+    ctx->rollout_kind = ROLLOUT_MFMA_REG;
+    ctx->kernel_name = mfma_variant_name(ctx->mfma_variant);
+  } else {
+    ctx->rollout_kind = ROLLOUT_WAVE_LDS;
+    ctx->kernel_name = c.dtype == 1 ? "rollout_wave_lds_bf16" : "rollout_wave_lds_f32";
+  }
+  ctx->upd_chunks = update_chunks(s.rows, s.ld, c.noise_dtype == 1);
+  ctx->workspace_bytes = std::max<size_t>(256, (size_t)ctx->upd_chunks * s.ld * sizeof(double));
+  *out = ctx;
+  return ES_OK;
+}
+
+int es_destroy(es_ctx* ctx) {
+  delete ctx;
+  return ES_OK;
+}
+
+size_t es_param_count(const es_ctx* ctx) { return ctx ? ctx->shp.D : 0; }
+size_t es_noise_rows(const es_ctx* ctx) { return ctx ? ctx->shp.rows : 0; }
+size_t es_noise_ld(const es_ctx* ctx) { return ctx ? ctx->shp.ld : 0; }
+size_t es_noise_bytes(const es_ctx* ctx) {
+  return ctx ? (size_t)ctx->shp.rows * ctx->shp.ld * (ctx->cfg.noise_dtype == 1 ? 2 : 4) : 0;
+}
+size_t es_workspace_bytes(const es_ctx* ctx) { return ctx ? ctx->workspace_bytes : 0; }
+const char* es_rollout_kernel(const es_ctx* ctx) { return ctx ? ctx->kernel_name.c_str() : ""; }
+
+int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (!noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
+  if (generation >> 32) return fail(ctx, ES_EINVAL, "es_sample_population: generation must be < 2^32");
+  return launch_sample(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
+}
+
+int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const void* noise_d, const float* A_d,
+               const float* B_d, float* returns_d, int32_t* ep_len_d, float* fitness_d, void* workspace_d,
+               void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (!theta_d || !noise_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d)
+    return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
+  if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->rollout_kind == ROLLOUT_MFMA_REG)
+    return launch_rollout_mfma(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
+                               fitness_d, workspace_d, st);
+  if (ctx->lds_bytes_wave > (size_t)ctx->lds_limit)
+    return fail(ctx, ES_EUNSUPPORTED, "es_rollout: perturbed parameters of one individual (" +
+                                          std::to_string(ctx->lds_bytes_wave) + " B) exceed the LDS of a workgroup (" +
+                                          std::to_string(ctx->lds_limit) + " B) and no register-resident kernel is built for this shape");
+  return launch_rollout_wave(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
+                             fitness_d, workspace_d, st);
+}
+
+int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (!fitness_d || !rank_d || !shaped_d) return fail(ctx, ES_EINVAL, "es_rank: null device pointer");
+  return launch_rank(ctx, fitness_d, rank_d, shaped_d, static_cast<hipStream_t>(stream));
+}
+
+int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, float* theta_d,
+              float* m_d, float* v_d, float* grad_d, void* workspace_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (!noise_d || !shaped_d || !theta_d || !m_d || !v_d || !workspace_d)
+    return fail(ctx, ES_EINVAL, "es_update: null device pointer");
+  if (adam_step < 1) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
+  if (!(ctx->cfg.sigma > 0.0f)) return fail(ctx, ES_EINVAL, "es_update: sigma must be > 0");
+  return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, workspace_d,
+                       static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

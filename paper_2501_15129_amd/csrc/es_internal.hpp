@@ -1,0 +1,65 @@
+// Internal declarations shared by the host API and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "../../include/es.h"
+
+namespace es {
+
+enum RolloutKind : int {
+  ROLLOUT_WAVE_LDS = 0,   // one wavefront per (individual, env); weights in LDS
+  ROLLOUT_MFMA_REG = 1,   // one workgroup per individual; bf16 weights resident in registers, MFMA
+};
+
+struct Shape {
+  uint32_t N, E, T, no, nh, na;
+  uint32_t D;        // parameter count
+  uint32_t ld;       // noise row stride (elements)
+  uint32_t rows;     // noise rows
+  // flat offsets of W1,b1,W2,b2,W3,b3
+  uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
+};
+
+}  // namespace es
+
+struct es_ctx {
+  es_config cfg;
+  es::Shape shp;
+  int rollout_kind;
+  int mfma_variant;          // index of the instantiated register-resident kernel, or -1
+  size_t lds_bytes_wave;     // dynamic LDS of the wave/LDS rollout
+  uint32_t upd_chunks;       // row chunks of the update reduction
+  size_t workspace_bytes;
+  int lds_limit;             // LDS bytes per workgroup on the device seen at es_create
+  std::string kernel_name;
+  std::string last_error;
+};
+
+namespace es {
+
+constexpr uint32_t NOISE_LD_ALIGN = 512;   // elements
+constexpr uint32_t STREAM_NOISE = 1u;
+constexpr uint32_t STREAM_RESET = 2u;
+
+int fail(es_ctx* ctx, int code, const std::string& what);
+int check_launch(es_ctx* ctx, const char* what);
+
+// stage launchers (each validates nothing: the API layer has done so)
+int launch_sample(es_ctx* ctx, uint32_t gen, void* noise, hipStream_t st);
+int launch_rank(es_ctx* ctx, const float* fit, int32_t* rank, float* shaped, hipStream_t st);
+int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* shaped, float* theta,
+                  float* m, float* v, float* grad, void* ws, hipStream_t st);
+int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
+                        const float* A, const float* B, float* returns, int32_t* ep_len,
+                        float* fitness, void* ws, hipStream_t st);
+int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
+                        const float* A, const float* B, float* returns, int32_t* ep_len,
+                        float* fitness, void* ws, hipStream_t st);
+int mfma_variant_for(const es_config& cfg);       // -1 when no register-resident kernel fits
+const char* mfma_variant_name(int variant);
+size_t wave_rollout_lds_bytes(const es_config& cfg);
+
+}  // namespace es

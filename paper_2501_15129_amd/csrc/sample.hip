@@ -1,0 +1,51 @@
+// es_sample_population: the noise matrix of one generation, generated on the fly from a
+// counter-based stream (paper Sec. 5.1: perturbations are not read from a pre-built table).
+//
+// One thread turns one Philox block into four consecutive columns of one row.  The matrix
+// is written once, with full-width coalesced vector stores; columns past D are zero.
+// Bound: integer/fp ALU work (10 Philox rounds + two Box-Muller evaluations per 4 values),
+// then the HBM write of rows * ld elements.
+#include "es_device.hpp"
+#include "es_internal.hpp"
+
+namespace es {
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void sample_kernel(void* __restrict__ noise, uint32_t D, uint32_t ld,
+                                                     uint32_t gen, uint32_t k0, uint32_t k1) {
+  const uint32_t blk = blockIdx.x * 256u + threadIdx.x;   // 4-column block within the row
+  const uint32_t row = blockIdx.y;
+  if (blk * 4u >= ld) return;
+  const uint32_t d0 = blk * 4u;
+  float z0 = 0.f, z1 = 0.f, z2 = 0.f, z3 = 0.f;
+  if (d0 < D) {
+    const Words4 w = philox4x32_10(blk, row, gen, STREAM_NOISE, k0, k1);
+    gauss_pair(w.x, w.y, z0, z1);
+    gauss_pair(w.z, w.w, z2, z3);
+    if (d0 + 1 >= D) z1 = 0.f;
+    if (d0 + 2 >= D) z2 = 0.f;
+    if (d0 + 3 >= D) z3 = 0.f;
+  }
+  const size_t off = (size_t)row * ld + d0;
+  if (BF16) {
+    uint2 v;
+    v.x = bf16_bits(z0) | (bf16_bits(z1) << 16);
+    v.y = bf16_bits(z2) | (bf16_bits(z3) << 16);
+    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(noise) + off) = v;
+  } else {
+    *reinterpret_cast<float4*>(static_cast<float*>(noise) + off) = make_float4(z0, z1, z2, z3);
+  }
+}
+
+int launch_sample(es_ctx* ctx, uint32_t gen, void* noise, hipStream_t st) {
+  const Shape& s = ctx->shp;
+  const uint32_t k0 = (uint32_t)ctx->cfg.seed, k1 = (uint32_t)(ctx->cfg.seed >> 32);
+  dim3 grid((s.ld / 4 + 255) / 256, s.rows);
+  if (ctx->cfg.noise_dtype == 1)
+    hipLaunchKernelGGL(sample_kernel<true>, grid, dim3(256), 0, st, noise, s.D, s.ld, gen, k0, k1);
+  else
+    hipLaunchKernelGGL(sample_kernel<false>, grid, dim3(256), 0, st, noise, s.D, s.ld, gen, k0, k1);
+  return check_launch(ctx, "es_sample_population");
+}
+
+}  // namespace es

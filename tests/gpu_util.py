@@ -1,0 +1,83 @@
+"""Helpers shared by the GPU parity tests: marshal the checker's dense arrays into the
+layouts the C boundary expects, run stages, and compare under the stated tolerances."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+# Tolerances (the benchmark spec): episode returns within 1e-4 relative in fp32 and 2e-2 in bf16;
+# updated parameters within 1e-5 relative (+1e-7 absolute for parameters near zero).
+RET_RTOL = {0: 1e-4, 1: 2e-2}
+# |max|s| - done_thresh| below this at any executed step marks an episode whose termination
+# step may legitimately differ between binary64 and binary32 / bf16 evaluation.
+KNIFE_EDGE = {0: 1e-5, 1: 1e-2}
+PARAM_RTOL, PARAM_ATOL = 1e-5, 1e-7
+
+
+def noise_to_device(ctx, eps_dense: np.ndarray) -> torch.Tensor:
+    """Dense float32 [rows, D] (already bf16-valued when the workload stores bf16) -> padded device matrix."""
+    rows, d = eps_dense.shape
+    assert rows == ctx.noise_rows and d == ctx.param_count
+    pad = np.zeros((rows, ctx.noise_ld), dtype=np.float32)
+    pad[:, :d] = eps_dense
+    t = torch.from_numpy(pad)
+    if ctx.cfg.noise_dtype == 1:
+        bits = (pad.view(np.uint32) >> 16).astype(np.uint16)
+        assert np.array_equal((bits.astype(np.uint32) << 16).view(np.float32), pad), "noise is not bf16-valued"
+        t = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16)
+    return t.cuda()
+
+
+def noise_from_device(ctx, noise: torch.Tensor) -> np.ndarray:
+    """Device noise matrix -> float32 [rows, ld] on the host (exact widening for bf16)."""
+    return noise.detach().float().cpu().numpy()
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def run_rollout(ctx, w, gen, theta, noise_dev, a_mat, b_mat):
+    ret = torch.full((w.pop, w.envs), float("nan"), dtype=torch.float32, device="cuda")
+    ln = torch.full((w.pop, w.envs), -1, dtype=torch.int32, device="cuda")
+    fit = torch.full((w.pop,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = ctx.alloc_workspace()
+    ctx.rollout(gen, dev(theta), noise_dev, dev(a_mat), dev(b_mat), ret, ln, fit, ws)
+    torch.cuda.synchronize()
+    return ret.cpu().numpy(), ln.cpu().numpy(), fit.cpu().numpy()
+
+
+def compare_rollout(w, got, ref, label=""):
+    """got = (returns, ep_len, fitness) from the GPU; ref = (returns, ep_len, fitness, margin) from the checker.
+
+    Episode lengths must be identical except for episodes the checker flags as knife-edge;
+    returns are compared where the lengths agree; fitness where every episode of the
+    individual agrees.  Returns the number of flagged episodes."""
+    g_ret, g_len, g_fit = got
+    r_ret, r_len, r_fit, r_mar = ref
+    rtol = RET_RTOL[w.dtype]
+    edge = r_mar < KNIFE_EDGE[w.dtype]
+    same = g_len == r_len
+    assert np.all(same | edge), f"{label}: episode length differs away from the termination threshold: " \
+        f"{np.argwhere(~(same | edge))[:5].tolist()}"
+    assert np.mean(~same) <= 0.02 + 2.0 / same.size, f"{label}: too many knife-edge flips ({np.sum(~same)} of {same.size})"
+    err = np.abs(g_ret.astype(np.float64) - r_ret) / np.maximum(np.abs(r_ret), 1e-3)
+    worst = float(np.max(np.where(same, err, 0.0)))
+    assert worst <= rtol, f"{label}: return mismatch {worst:.3e} > {rtol}"
+    ind_ok = np.all(same, axis=1)
+    ferr = np.abs(g_fit.astype(np.float64) - r_fit) / np.maximum(np.abs(r_fit), 1e-3)
+    assert float(np.max(np.where(ind_ok, ferr, 0.0))) <= rtol, f"{label}: fitness mismatch"
+    # fitness is the mean of the returns the kernel itself produced
+    assert np.allclose(g_fit, g_ret.astype(np.float64).mean(axis=1), rtol=1e-5, atol=1e-5), f"{label}: fitness != mean"
+    return int(np.sum(~same)), worst
+
+
+def assert_params_close(got, ref, label=""):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    bad = np.abs(got - ref) > PARAM_RTOL * np.abs(ref) + PARAM_ATOL
+    assert not bad.any(), f"{label}: {int(bad.sum())} of {bad.size} elements off; worst " \
+        f"{float(np.max(np.abs(got - ref))):.3e}"

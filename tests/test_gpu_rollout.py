@@ -1,0 +1,108 @@
+"""GPU parity of es_rollout against the CPU checker, called through the C boundary.
+
+The checker's noise matrix is injected (stage-wise test), so the only differences are the
+rollout's own arithmetic: binary32 (or bf16 operands) on the GPU, binary64 in the checker.
+"""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs
+from gpu_util import compare_rollout, noise_to_device, run_rollout
+
+pytestmark = pytest.mark.gpu
+
+TINY = Workload("tiny", pop=6, envs=3, horizon=7, obs=5, hid=8, act=2, dtype=0, noise_dtype=0, seed=21)
+ODD = Workload("odd", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=22)
+WIDE = Workload("wide", pop=4, envs=2, horizon=40, obs=70, hid=100, act=9, dtype=0, noise_dtype=0, seed=23)
+
+
+@pytest.fixture(scope="module")
+def es():
+    import paper_2501_15129_amd as pkg
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return pkg
+
+
+def _case(es, w, gen=0, individuals=None, theta=None):
+    a_mat, b_mat, theta0 = make_inputs(w)
+    theta = theta0 if theta is None else theta
+    ctx = es.EsContext(w)
+    eps = oracle.sample_population(w, gen)
+    got = run_rollout(ctx, w, gen, theta, noise_to_device(ctx, eps), a_mat, b_mat)
+    ref = oracle.rollout(w, gen, theta, eps, a_mat, b_mat, individuals=individuals)
+    if individuals is not None:
+        i0, i1 = individuals
+        got = tuple(x[i0:i1] for x in got)
+    flips, worst = compare_rollout(w, got, ref, w.name)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst return rel err {worst:.2e}, knife-edge flips {flips}")
+    return got, ref
+
+
+@pytest.mark.parametrize("w", [
+    TINY, ODD, WIDE,
+    replace(TINY, name="tiny-T1", horizon=1),
+    replace(TINY, name="tiny-N2E1", pop=2, envs=1),
+    replace(ODD, name="odd-noanti", antithetic=0, pop=7),
+    replace(ODD, name="odd-linear-out", out_tanh=0),
+    replace(ODD, name="odd-fixedlen", done_thresh=math.inf),
+    replace(ODD, name="odd-bf16", dtype=1, noise_dtype=1),
+    replace(WIDE, name="wide-bf16", dtype=1, noise_dtype=1, done_thresh=math.inf),
+    replace(ODD, name="odd-f32noise-bf16ops", dtype=1, noise_dtype=0),
+], ids=lambda w: w.name)
+def test_rollout_small_shapes(es, w):
+    _case(es, w, gen=2)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_rollout_fp32_configs_full(es, idx):
+    """configs[0..2] at full size, every (individual, environment) pair compared."""
+    _case(es, CONFIGS[idx], gen=0)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_rollout_fp32_configs_fixed_length(es, idx):
+    """Same workloads under the paper's timing protocol (fixed-length episodes, Sec. 5.1)."""
+    w = CONFIGS[idx].fixed_length()
+    got, _ = _case(es, w, gen=1)
+    assert np.all(got[1] == w.horizon)
+
+
+def test_sigma_zero_identical_fitness(es):
+    w = replace(ODD, sigma=0.0)
+    got, _ = _case(es, w)
+    fit = got[2]
+    assert np.all(fit.view(np.uint32) == fit.view(np.uint32)[0])
+    assert np.all(got[0] == got[0][0]) and np.all(got[1] == got[1][0])
+
+
+def test_degenerate_rollouts(es):
+    # threshold below every reachable state: each episode is exactly one step long
+    got, _ = _case(es, replace(ODD, name="odd-len1", done_thresh=1e-6))
+    assert np.all(got[1] == 1)
+    # zero policy, zero dynamics: R = r_0 + (T - 1) exactly representable -> tight check
+    w = replace(TINY, name="tiny-zero", sigma=0.0, horizon=33, done_thresh=math.inf)
+    a_mat, b_mat, _ = make_inputs(w)
+    ctx = es.EsContext(w)
+    eps = oracle.sample_population(w, 0)
+    ret, ln, fit = run_rollout(ctx, w, 0, np.zeros(w.n_params, np.float32), noise_to_device(ctx, eps),
+                               np.zeros_like(a_mat), b_mat)
+    for e in range(w.envs):
+        s0 = oracle.reset(w, 0, e).astype(np.float64)
+        assert abs(ret[0, e] - (1.0 - np.dot(s0, s0) / w.obs + 32.0)) < 1e-4
+    assert np.all(ln == 33)
+
+
+def test_rollout_rerun_is_bit_identical(es):
+    w = CONFIGS[0]
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    nd = noise_to_device(ctx, oracle.sample_population(w, 0))
+    a = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
+    b = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
