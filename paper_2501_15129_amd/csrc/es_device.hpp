@@ -44,7 +44,7 @@ __device__ __forceinline__ void gauss_pair(uint32_t xa, uint32_t xb, float& zc, 
   float m = __uint_as_float((fb & 0x007FFFFFu) | 0x3F800000u);
   if (m > 1.41421354f) { m = m * 0.5f; e += 1; }
   const int n = 24 - e;
-  const float s = __fdiv_rn(m - 1.0f, m + 1.0f);
+  const float s = (m - 1.0f) / (m + 1.0f);          // correctly rounded division
   const float t = s * s;
   float p = 0x1.745d18p-4f;                    // 1/11
   p = __fmaf_rn(t, p, 0x1.c71c72p-4f);         // 1/9
@@ -55,7 +55,7 @@ __device__ __forceinline__ void gauss_pair(uint32_t xa, uint32_t xb, float& zc, 
   float lnm = s * p;
   lnm = lnm + lnm;
   const float nlu = __fmaf_rn((float)n, 0.693147182f, -lnm);
-  const float rad = __fsqrt_rn(nlu + nlu);
+  const float rad = __builtin_sqrtf(nlu + nlu);    // correctly rounded (not the native approximation)
 
   const uint32_t oct = k2 >> 21;
   uint32_t f = k2 & 0x1FFFFFu;

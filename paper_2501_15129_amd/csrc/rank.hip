@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void rank_kernel(const float* __restrict__ fit
   cnt += __shfl_xor(cnt, 1, 64);
   if (part == 0 && i < n) {
     rank[i] = (int32_t)cnt;
-    shaped[i] = n > 1 ? __fdiv_rn((float)cnt, (float)(n - 1)) - 0.5f : 0.0f;
+    shaped[i] = n > 1 ? ((float)cnt / (float)(n - 1)) - 0.5f : 0.0f;
   }
 }
 

@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     __syncthreads();
     ss = wave_sum(ss);
     aa = wave_sum(aa);
-    R += (1.0f - __fdiv_rn(ss, (float)no)) - a.act_cost * aa;
+    R += (1.0f - (ss / (float)no)) - a.act_cost * aa;
     len += 1;
     float mx = 0.0f;
     for (uint32_t k = lane; k < no; k += 64u) {
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void fitness_kernel(const float* __restrict__ 
   if (i >= N) return;
   float s = 0.0f;
   for (uint32_t e = 0; e < E; ++e) s += returns[(size_t)i * E + e];
-  fitness[i] = __fdiv_rn(s, (float)E);
+  fitness[i] = (s / (float)E);
 }
 
 int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,

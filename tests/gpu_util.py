@@ -50,29 +50,47 @@ def run_rollout(ctx, w, gen, theta, noise_dev, a_mat, b_mat):
     return ret.cpu().numpy(), ln.cpu().numpy(), fit.cpu().numpy()
 
 
-def compare_rollout(w, got, ref, label=""):
-    """got = (returns, ep_len, fitness) from the GPU; ref = (returns, ep_len, fitness, margin) from the checker.
+# A trajectory is called sensitive when the checker's OWN binary32 evaluation of it already
+# drifts from its binary64 evaluation by more than this fraction of the tolerance: a few
+# random policies make the closed loop chaotic, and there no binary32 kernel can track the
+# binary64 return to 1e-4.  Such episodes are listed and held to SENSITIVE_RTOL instead.
+SENSITIVE_FRACTION_OF_RTOL = 0.125
+SENSITIVE_RTOL = 5e-2
+MAX_SENSITIVE_SHARE = 0.03
+
+
+def compare_rollout(w, got, ref, label="", probe=None):
+    """got = (returns, ep_len, fitness) from the GPU; ref = (returns, ep_len, fitness, margin) from the
+    checker in binary64; probe = the checker's binary32 evaluation of the same episodes (optional).
 
     Episode lengths must be identical except for episodes the checker flags as knife-edge;
     returns are compared where the lengths agree; fitness where every episode of the
-    individual agrees.  Returns the number of flagged episodes."""
+    individual agrees.  Returns (knife-edge flips, worst error on regular episodes, sensitive count)."""
     g_ret, g_len, g_fit = got
     r_ret, r_len, r_fit, r_mar = ref
     rtol = RET_RTOL[w.dtype]
-    edge = r_mar < KNIFE_EDGE[w.dtype]
+    scale = np.maximum(np.abs(r_ret), 1e-3)
+    if probe is not None:
+        sens = (np.abs(probe[0].astype(np.float64) - r_ret) / scale > SENSITIVE_FRACTION_OF_RTOL * rtol) | (probe[1] != r_len)
+    else:
+        sens = np.zeros(r_ret.shape, dtype=bool)
+    edge = (r_mar < KNIFE_EDGE[w.dtype]) | sens
     same = g_len == r_len
     assert np.all(same | edge), f"{label}: episode length differs away from the termination threshold: " \
         f"{np.argwhere(~(same | edge))[:5].tolist()}"
     assert np.mean(~same) <= 0.02 + 2.0 / same.size, f"{label}: too many knife-edge flips ({np.sum(~same)} of {same.size})"
-    err = np.abs(g_ret.astype(np.float64) - r_ret) / np.maximum(np.abs(r_ret), 1e-3)
-    worst = float(np.max(np.where(same, err, 0.0)))
+    assert np.mean(sens) <= MAX_SENSITIVE_SHARE + 1.0 / same.size, f"{label}: {int(sens.sum())} sensitive episodes"
+    err = np.abs(g_ret.astype(np.float64) - r_ret) / scale
+    worst = float(np.max(np.where(same & ~sens, err, 0.0)))
     assert worst <= rtol, f"{label}: return mismatch {worst:.3e} > {rtol}"
-    ind_ok = np.all(same, axis=1)
+    worst_sens = float(np.max(np.where(same & sens, err, 0.0)))
+    assert worst_sens <= SENSITIVE_RTOL, f"{label}: return mismatch {worst_sens:.3e} on a sensitive episode"
+    ind_ok = np.all(same & ~sens, axis=1)
     ferr = np.abs(g_fit.astype(np.float64) - r_fit) / np.maximum(np.abs(r_fit), 1e-3)
     assert float(np.max(np.where(ind_ok, ferr, 0.0))) <= rtol, f"{label}: fitness mismatch"
     # fitness is the mean of the returns the kernel itself produced
     assert np.allclose(g_fit, g_ret.astype(np.float64).mean(axis=1), rtol=1e-5, atol=1e-5), f"{label}: fitness != mean"
-    return int(np.sum(~same)), worst
+    return int(np.sum(~same)), worst, int(sens.sum())
 
 
 def assert_params_close(got, ref, label=""):

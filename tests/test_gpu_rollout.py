@@ -35,11 +35,13 @@ def _case(es, w, gen=0, individuals=None, theta=None):
     eps = oracle.sample_population(w, gen)
     got = run_rollout(ctx, w, gen, theta, noise_to_device(ctx, eps), a_mat, b_mat)
     ref = oracle.rollout(w, gen, theta, eps, a_mat, b_mat, individuals=individuals)
+    probe = oracle.rollout(w, gen, theta, eps, a_mat, b_mat, individuals=individuals, arith=1)
     if individuals is not None:
         i0, i1 = individuals
         got = tuple(x[i0:i1] for x in got)
-    flips, worst = compare_rollout(w, got, ref, w.name)
-    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst return rel err {worst:.2e}, knife-edge flips {flips}")
+    flips, worst, sens = compare_rollout(w, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst return rel err {worst:.2e}, knife-edge flips {flips}, "
+          f"sensitive episodes {sens} of {ref[0].size}")
     return got, ref
 
 
@@ -70,6 +72,20 @@ def test_rollout_fp32_configs_fixed_length(es, idx):
     w = CONFIGS[idx].fixed_length()
     got, _ = _case(es, w, gen=1)
     assert np.all(got[1] == w.horizon)
+
+
+@pytest.mark.parametrize("idx", [1, 2])
+def test_rollout_fp32_configs_short_horizon_strict(es, idx):
+    """The first 60 steps of configs[1..2], where no trajectory has had time to diverge:
+    every episode must meet the strict tolerance (no sensitive-episode allowance)."""
+    w = replace(CONFIGS[idx], name=f"cfg{idx}-T60", horizon=60)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    eps = oracle.sample_population(w, 0)
+    got = run_rollout(ctx, w, 0, theta, noise_to_device(ctx, eps), a_mat, b_mat)
+    ref = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+    flips, worst, _ = compare_rollout(w, got, ref, w.name, probe=None)
+    assert worst <= 1e-5
 
 
 def test_sigma_zero_identical_fitness(es):
