@@ -8,8 +8,6 @@
 
 namespace es {
 
-uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16);
-
 int fail(es_ctx* ctx, int code, const std::string& what) {
   if (ctx) ctx->last_error = what;
   return code;
@@ -73,14 +71,16 @@ int es_create(const es_config* cfg, es_ctx** out) {
   s.oW1 = 0; s.ob1 = (uint32_t)(h * o); s.oW2 = s.ob1 + (uint32_t)h; s.ob2 = s.oW2 + (uint32_t)(h * h);
   s.oW3 = s.ob2 + (uint32_t)h; s.ob3 = s.oW3 + (uint32_t)(a * h);
 
-  int dev = 0, lds = 65536;
+  int dev = 0, lds = 65536, cus = 256;
   if (hipGetDevice(&dev) == hipSuccess) {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0) lds = v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
   } else {
     (void)hipGetLastError();   // no device here (host-only checks): keep the conservative default
   }
   ctx->lds_limit = lds;
+  ctx->num_cus = cus;
   ctx->lds_bytes_wave = wave_rollout_lds_bytes(c);
   ctx->mfma_variant = mfma_variant_for(c);
   if (ctx->mfma_variant >= 0) {

@@ -34,6 +34,7 @@ struct es_ctx {
   uint32_t upd_chunks;       // row chunks of the update reduction
   size_t workspace_bytes;
   int lds_limit;             // LDS bytes per workgroup on the device seen at es_create
+  int num_cus;               // compute units of that device
   std::string kernel_name;
   std::string last_error;
 };
@@ -61,5 +62,6 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
 int mfma_variant_for(const es_config& cfg);       // -1 when no register-resident kernel fits
 const char* mfma_variant_name(int variant);
 size_t wave_rollout_lds_bytes(const es_config& cfg);
+uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16);
 
 }  // namespace es

@@ -53,7 +53,8 @@ def run_rollout(ctx, w, gen, theta, noise_dev, a_mat, b_mat):
 # A trajectory is called sensitive when the checker's OWN binary32 evaluation of it already
 # drifts from its binary64 evaluation by more than this fraction of the tolerance: a few
 # random policies make the closed loop chaotic, and there no binary32 kernel can track the
-# binary64 return to 1e-4.  Such episodes are listed and held to SENSITIVE_RTOL instead.
+# binary64 return to 1e-4.  Such episodes are listed and held to SENSITIVE_RTOL instead; the
+# share of episodes that actually need the allowance is capped.
 SENSITIVE_FRACTION_OF_RTOL = 0.125
 SENSITIVE_RTOL = 5e-2
 MAX_SENSITIVE_SHARE = 0.03
@@ -65,7 +66,9 @@ def compare_rollout(w, got, ref, label="", probe=None):
 
     Episode lengths must be identical except for episodes the checker flags as knife-edge;
     returns are compared where the lengths agree; fitness where every episode of the
-    individual agrees.  Returns (knife-edge flips, worst error on regular episodes, sensitive count)."""
+    individual agrees.  Sensitive episodes (see above) are held to SENSITIVE_RTOL, and at most
+    MAX_SENSITIVE_SHARE of all episodes may need that allowance.
+    Returns (knife-edge flips, worst error on regular episodes, sensitive count)."""
     g_ret, g_len, g_fit = got
     r_ret, r_len, r_fit, r_mar = ref
     rtol = RET_RTOL[w.dtype]
@@ -78,13 +81,17 @@ def compare_rollout(w, got, ref, label="", probe=None):
     same = g_len == r_len
     assert np.all(same | edge), f"{label}: episode length differs away from the termination threshold: " \
         f"{np.argwhere(~(same | edge))[:5].tolist()}"
-    assert np.mean(~same) <= 0.02 + 2.0 / same.size, f"{label}: too many knife-edge flips ({np.sum(~same)} of {same.size})"
-    assert np.mean(sens) <= MAX_SENSITIVE_SHARE + 1.0 / same.size, f"{label}: {int(sens.sum())} sensitive episodes"
+    # a flagged episode flips only if the two evaluations differ by more than its margin at that step
+    assert np.sum(~same) <= 0.3 * np.sum(edge) + 2, \
+        f"{label}: too many knife-edge flips ({np.sum(~same)} of {int(np.sum(edge))} flagged, {same.size} episodes)"
     err = np.abs(g_ret.astype(np.float64) - r_ret) / scale
     worst = float(np.max(np.where(same & ~sens, err, 0.0)))
     assert worst <= rtol, f"{label}: return mismatch {worst:.3e} > {rtol}"
     worst_sens = float(np.max(np.where(same & sens, err, 0.0)))
     assert worst_sens <= SENSITIVE_RTOL, f"{label}: return mismatch {worst_sens:.3e} on a sensitive episode"
+    excused = same & sens & (err > rtol)
+    assert np.mean(excused) <= MAX_SENSITIVE_SHARE + 1.0 / same.size, \
+        f"{label}: {int(excused.sum())} sensitive episodes beyond the regular tolerance"
     ind_ok = np.all(same & ~sens, axis=1)
     ferr = np.abs(g_fit.astype(np.float64) - r_fit) / np.maximum(np.abs(r_fit), 1e-3)
     assert float(np.max(np.where(ind_ok, ferr, 0.0))) <= rtol, f"{label}: fitness mismatch"

@@ -122,3 +122,42 @@ def test_rollout_rerun_is_bit_identical(es):
     b = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
     for x, y in zip(a, b):
         assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
+# ---- register-resident MFMA variants (bf16, hidden width up to 256) ----
+MF = Workload("mfma", pop=6, envs=16, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=33)
+
+
+@pytest.mark.parametrize("w", [
+    MF,
+    replace(MF, name="mfma-E4-obs244", envs=4, obs=244, act=17, horizon=25),
+    replace(MF, name="mfma-fixedlen", done_thresh=math.inf, horizon=80),
+    replace(MF, name="mfma-obs244-fixedlen", envs=4, obs=244, act=17, horizon=40, done_thresh=math.inf),
+    replace(MF, name="mfma-E1", envs=1),
+    replace(MF, name="mfma-E21", envs=21, horizon=20),
+    replace(MF, name="mfma-obs60-hid200-act10", obs=60, hid=200, act=10),
+    replace(MF, name="mfma-obs100-hid160-act20", obs=100, hid=160, act=20, envs=5),
+    replace(MF, name="mfma-obs33-act17", obs=33, act=17, envs=3),
+    replace(MF, name="mfma-noanti-linear-f32noise", antithetic=0, pop=5, out_tanh=0, noise_dtype=0),
+    replace(MF, name="mfma-T1", horizon=1),
+    replace(MF, name="mfma-len1", done_thresh=1e-6),
+    replace(MF, name="mfma-N600", pop=600, envs=2, horizon=6),
+], ids=lambda w: w.name)
+def test_rollout_mfma_variants(es, w):
+    ctx = es.EsContext(w)
+    assert "mfma" in ctx.rollout_kernel
+    _case(es, w, gen=1)
+
+
+def test_rollout_mfma_sigma_zero_and_rerun(es):
+    w = replace(MF, sigma=0.0, horizon=30)
+    got, _ = _case(es, w)
+    assert np.all(got[2].view(np.uint32) == got[2].view(np.uint32)[0])
+    w = replace(MF, envs=4, obs=244, act=17, horizon=12)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    nd = noise_to_device(ctx, oracle.sample_population(w, 0))
+    a = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
+    b = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
