@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the OpenES hot path on one MI355X.
+
+One "step" is one whole generation: es_sample_population -> es_rollout -> es_rank ->
+es_update, enqueued on one stream with every input already resident in HBM.  The default
+workload is the largest configuration (configs[4]: population 4096 x 4 environment copies,
+T = 1000, MLP 244-256-256-17, bf16) under the paper's timing protocol of fixed-length
+episodes (Sec. 5.1); the same workload with its termination rule switched on is reported
+beside it.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from dataclasses import replace
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+FP32_VALU_PEAK_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+
+
+def flop_per_env_step(w) -> int:
+    """Multiply-add flops of one policy forward plus one environment step (2 flop per MAC)."""
+    o, h, a = w.obs, w.hid, w.act
+    return 2 * (o * h + h * h + h * a) + 2 * (o * o + o * a)
+
+
+def update_bytes(w, ctx) -> int:
+    """Algorithmic bytes of es_update: the noise matrix once, theta/m/v read and written, the weights."""
+    elt = 2 if w.noise_dtype == 1 else 4
+    return w.noise_rows * w.n_params * elt + 24 * w.n_params + 4 * w.pop
+
+
+def run_generations(torch, ctx, w, bufs, steps, warmup, gen0=0):
+    """Runs warmup + steps generations; returns (wall seconds for `steps`, per-stage ms lists, live env steps)."""
+    names = ("sample", "rollout", "rank", "update")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+    live = 0
+
+    def generation(g, marks=None):
+        if marks: marks[0].record()
+        ctx.sample_population(g, bufs["noise"])
+        if marks: marks[1].record()
+        ctx.rollout(g, bufs["theta"], bufs["noise"], bufs["A"], bufs["B"], bufs["ret"], bufs["len"], bufs["fit"], bufs["ws"])
+        if marks: marks[2].record()
+        ctx.rank(bufs["fit"], bufs["rank"], bufs["shaped"])
+        if marks: marks[3].record()
+        ctx.update(g + 1, bufs["noise"], bufs["shaped"], bufs["theta"], bufs["m"], bufs["v"], None, bufs["ws"])
+        if marks: marks[4].record()
+
+    for k in range(warmup):
+        generation(gen0 + k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        generation(gen0 + warmup + k, ev[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    live = int(bufs["len"].sum().item())            # episode lengths of the last generation
+    stage = {n: [ev[k][j].elapsed_time(ev[k][j + 1]) for k in range(steps)] for j, n in enumerate(names)}
+    return wall, stage, live
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The CPU checker, as it stands, on a bounded sample of the same workload (host cores of this machine)."""
+    import numpy as np
+    import oracle
+    from paper_2501_15129_amd.workloads import make_inputs
+
+    threads = oracle.max_threads()
+    a_mat, b_mat, theta = make_inputs(w)
+
+    def timed(n_ind):
+        ws = replace(w, pop=n_ind)
+        t0 = time.perf_counter()
+        eps = oracle.sample_population(ws, 0)
+        ret, ln, fit, _ = oracle.rollout(ws, 0, theta, eps, a_mat, b_mat)
+        _, shaped = oracle.rank(fit)
+        oracle.update(ws, 1, eps, shaped, theta, np.zeros_like(theta), np.zeros_like(theta))
+        return time.perf_counter() - t0, int(ln.sum())
+
+    n = min(w.pop, 2 * ((threads + 1) // 2))
+    dt, steps = timed(n)
+    if dt < budget_s and n < w.pop:
+        n2 = min(w.pop, 2 * int(max(1, (budget_s / max(dt, 1e-3)) * n / 2)))
+        if n2 > n:
+            n = n2
+            dt, steps = timed(n)
+    return {"value": steps / dt, "unit": "env-steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"one full generation (sample, rollout, rank, update) of the first {n} of {w.pop} individuals "
+                      f"x {w.envs} envs x T={w.horizon}, {steps} env-steps in {dt:.1f} s, OpenMP over individuals"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="index into the five workloads (default: the largest)")
+    ap.add_argument("--done-rule", action="store_true", help="time the workload with its termination rule on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; --gpus N with N > 1 is not supported "
+              "(sharding along the population is a design note only)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2501_15129_amd import CONFIGS, EsContext, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    base = CONFIGS[args.config]
+    w = base if args.done_rule else base.fixed_length()
+    a_mat, b_mat, theta = make_inputs(w)
+
+    def setup(wl):
+        ctx = EsContext(wl)
+        d = ctx.param_count
+        dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        bufs = dict(noise=ctx.alloc_noise(), ws=ctx.alloc_workspace(), theta=dev(theta), A=dev(a_mat), B=dev(b_mat),
+                    m=torch.zeros(d, device="cuda"), v=torch.zeros(d, device="cuda"),
+                    ret=torch.empty((wl.pop, wl.envs), device="cuda"),
+                    len=torch.empty((wl.pop, wl.envs), dtype=torch.int32, device="cuda"),
+                    fit=torch.empty(wl.pop, device="cuda"), rank=torch.empty(wl.pop, dtype=torch.int32, device="cuda"),
+                    shaped=torch.empty(wl.pop, device="cuda"))
+        return ctx, bufs
+
+    ctx, bufs = setup(w)
+    wall, stage, live = run_generations(torch, ctx, w, bufs, args.steps, args.warmup)
+    mean = lambda xs: float(sum(xs) / len(xs))
+    ms_per_step = wall * 1e3 / args.steps
+    nominal = w.env_steps
+    executed = live if args.done_rule else nominal     # fixed-length: every step of every episode runs
+    if not args.done_rule:
+        assert live == nominal, f"fixed-length run executed {live} of {nominal} env-steps"
+    value = executed * args.steps / wall
+
+    roll_ms = mean(stage["rollout"])
+    upd_ms = mean(stage["update"])
+    flops = flop_per_env_step(w) * executed
+    bf16 = w.dtype == 1
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VALU_PEAK_TFLOPS
+    ach = flops / (roll_ms * 1e-3) / 1e12
+    roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                "flop_per_launch": flops, "avg_launch_ms": roll_ms}
+    ub = update_bytes(w, ctx)
+    ugbs = ub / (upd_ms * 1e-3) / 1e9
+    roofline_update = {"kernel": "grad_partial_kernel+adam_kernel", "bound": "hbm", "achieved": ugbs, "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "frac": ugbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": ub,
+                       "avg_launch_ms": upd_ms}
+
+    out = {
+        "metric": "env-steps/sec (policy fwd + env step), whole OpenES generation",
+        "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs, T={w.horizon}, MLP {w.obs}-{w.hid}-{w.hid}-{w.act} tanh, "
+                               f"{'bf16 operands / fp32 accumulate' if bf16 else 'fp32'}, "
+                               f"{'termination rule on (live env-steps counted)' if args.done_rule else 'fixed-length episodes (paper Sec. 5.1 protocol)'}",
+                   "population": w.pop, "envs_per_individual": w.envs, "horizon": w.horizon, "params": w.n_params,
+                   "rollout_kernel": ctx.rollout_kernel},
+        "generations_per_s": args.steps / wall,
+        "env_steps_per_generation": executed,
+        "stage_ms": {k: mean(v) for k, v in stage.items()},
+        "roofline": roofline,
+        "roofline_update": roofline_update,
+    }
+
+    if not args.done_rule and not args.no_second_variant:
+        ctx2, bufs2 = setup(base)
+        wall2, stage2, live2 = run_generations(torch, ctx2, base, bufs2, args.steps, args.warmup)
+        out["with_termination_rule"] = {"live_env_steps_per_generation": live2, "ms_per_step": wall2 * 1e3 / args.steps,
+                                        "live_env_steps_per_s": live2 * args.steps / wall2,
+                                        "generations_per_s": args.steps / wall2,
+                                        "stage_ms": {k: mean(v) for k, v in stage2.items()}}
+        del ctx2, bufs2
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"]["host_cpus_visible"] = os.cpu_count()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

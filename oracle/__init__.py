@@ -118,10 +118,12 @@ def sample_population(w, gen: int, rows=None) -> np.ndarray:
 
 
 def perturb(w, theta, noise, i: int) -> np.ndarray:
+    """Parameters of individual ``i``; ``noise`` is the full dense matrix."""
     c = config(w)
     theta, noise = _f32(theta), _f32(noise)
+    row = _f32(noise[i // 2 if w.antithetic else i])
     out = np.empty(param_count(w), dtype=np.float32)
-    lib().orc_perturb(C.byref(c), _p(theta, C.c_float), _p(noise, C.c_float), C.c_uint32(i), _p(out, C.c_float))
+    lib().orc_perturb(C.byref(c), _p(theta, C.c_float), _p(row, C.c_float), C.c_uint32(i), _p(out, C.c_float))
     return out
 
 
@@ -132,22 +134,25 @@ def reset(w, gen: int, e: int) -> np.ndarray:
     return out
 
 
-def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: int = 0):
-    """Evaluate individuals ``(i0, i1)`` (default all).  ``noise`` is the FULL dense matrix.
+def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: int = 0, noise_row0: int = 0):
+    """Evaluate individuals ``(i0, i1)`` (default all).  ``noise`` holds the dense rows from
+    ``noise_row0`` on (the full matrix by default); it must cover the rows of these individuals.
 
     Returns ``(returns [n,E] f32, ep_len [n,E] i32, fitness [n] f32, margin [n,E] f32)``.
     """
     c = config(w)
     theta, noise, a_mat, b_mat = _f32(theta), _f32(noise), _f32(a_mat), _f32(b_mat)
-    assert noise.shape == (w.noise_rows, param_count(w))
     i0, i1 = (0, w.pop) if individuals is None else individuals
     n = i1 - i0
+    first, last = (i0 // 2, (i1 - 1) // 2) if w.antithetic else (i0, i1 - 1)
+    assert noise.ndim == 2 and noise.shape[1] == param_count(w)
+    assert noise_row0 <= first and last < noise_row0 + noise.shape[0], "noise rows do not cover these individuals"
     ret = np.empty((n, w.envs), dtype=np.float32)
     ln = np.empty((n, w.envs), dtype=np.int32)
     fit = np.empty(n, dtype=np.float32)
     mar = np.empty((n, w.envs), dtype=np.float32)
     lib().orc_rollout(C.byref(c), C.c_uint64(gen), _p(theta, C.c_float), _p(noise, C.c_float),
-                      _p(a_mat, C.c_float), _p(b_mat, C.c_float), C.c_uint32(i0), C.c_uint32(i1),
+                      C.c_uint32(noise_row0), _p(a_mat, C.c_float), _p(b_mat, C.c_float), C.c_uint32(i0), C.c_uint32(i1),
                       C.c_int(arith), _p(ret, C.c_float), _p(ln, C.c_int32), _p(fit, C.c_float),
                       _p(mar, C.c_float))
     return ret, ln, fit, mar

@@ -193,15 +193,15 @@ void orc_sample_population(const orc_config *cfg, uint64_t gen, float *noise) {
   orc_sample_rows(cfg, gen, 0, noise_rows(cfg), noise);
 }
 
-/* Parameters of individual i: theta_i[d] = fma(sign * sigma, eps[row, d], theta[d]) in
+/* Parameters of individual i: theta_i[d] = fma(sign * sigma, eps_row[d], theta[d]) in
  * binary32 (one rounding), sign = +1 / -1 for even / odd i under mirrored sampling;
- * rounded to bf16 afterwards when dtype = 1. */
-void orc_perturb(const orc_config *cfg, const float *theta, const float *noise, uint32_t i, float *theta_i) {
+ * rounded to bf16 afterwards when dtype = 1.  eps_row is the noise row of this individual
+ * (row i/2 when mirrored, else row i). */
+void orc_perturb(const orc_config *cfg, const float *theta, const float *eps_row, uint32_t i, float *theta_i) {
   size_t D = orc_param_count(cfg);
-  uint32_t row = cfg->antithetic ? i / 2 : i;
   float scale = (cfg->antithetic && (i & 1u)) ? -cfg->sigma : cfg->sigma;
   for (size_t d = 0; d < D; ++d) {
-    float v = fmaf(scale, noise[(size_t)row * D + d], theta[d]);
+    float v = fmaf(scale, eps_row[d], theta[d]);
     if (cfg->dtype == 1) v = orc_bf16_round(v);
     theta_i[d] = v;
   }
@@ -252,9 +252,11 @@ static double q_operand(const orc_config *cfg, double x) {
  *   returns[(i-i0)*E + e], ep_len[(i-i0)*E + e], fitness[i-i0] = mean_e returns,
  *   margin[(i-i0)*E + e] = min over executed steps of | max_k|s_{t+1,k}| - done_thresh |
  *   (how close the termination test came to flipping; +inf when the rule is off).
+ * noise holds the rows from noise_row0 on (dense, D per row): row r of the matrix is at
+ * noise + (r - noise_row0) * D.
  * arith = 0: binary64 (the reference); 1: binary32 (sensitivity probe). */
 void orc_rollout(const orc_config *cfg, uint64_t gen, const float *theta, const float *noise,
-                 const float *A, const float *B, uint32_t i0, uint32_t i1, int arith,
+                 uint32_t noise_row0, const float *A, const float *B, uint32_t i0, uint32_t i1, int arith,
                  float *returns, int32_t *ep_len, float *fitness, float *margin) {
   size_t D = orc_param_count(cfg);
   uint32_t E = cfg->envs, no = cfg->obs, na = cfg->act;
@@ -267,7 +269,8 @@ void orc_rollout(const orc_config *cfg, uint64_t gen, const float *theta, const 
   for (uint32_t i = i0; i < i1; ++i) {
     float *theta_i = (float *)malloc(sizeof(float) * D);
     float *s0 = (float *)malloc(sizeof(float) * no);
-    orc_perturb(cfg, theta, noise, i, theta_i);
+    uint32_t row = cfg->antithetic ? i / 2 : i;
+    orc_perturb(cfg, theta, noise + (size_t)(row - noise_row0) * D, i, theta_i);
     double fit = 0.0;
     for (uint32_t e = 0; e < E; ++e) {
       double ret, mar;

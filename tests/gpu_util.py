@@ -50,14 +50,21 @@ def run_rollout(ctx, w, gen, theta, noise_dev, a_mat, b_mat):
     return ret.cpu().numpy(), ln.cpu().numpy(), fit.cpu().numpy()
 
 
-# A trajectory is called sensitive when the checker's OWN binary32 evaluation of it already
-# drifts from its binary64 evaluation by more than this fraction of the tolerance: a few
-# random policies make the closed loop chaotic, and there no binary32 kernel can track the
-# binary64 return to 1e-4.  Such episodes are listed and held to SENSITIVE_RTOL instead; the
-# share of episodes that actually need the allowance is capped.
+# A trajectory is called sensitive when the checker's OWN second evaluation of it (same
+# algorithm, binary32 accumulation instead of binary64) already drifts from the reference by
+# more than this fraction of the tolerance: some random policies make the closed loop
+# chaotic, and there no finite-precision kernel can track the binary64 return (in bf16 mode a
+# single flipped rounding decorrelates the trajectories).  Such episodes are held to
+# SENSITIVE_RTOL instead, and the share of episodes that actually need the allowance is capped
+# - unless the whole batch is in the chaotic regime (more than CHAOTIC_SHARE of its episodes
+# flagged): then every episode is held to SENSITIVE_RTOL, the batch mean to CHAOTIC_MEAN_RTOL,
+# and the caller must ALSO pass a strict comparison at a horizon short enough for the
+# trajectories not to have diverged (the per-step code path is the same for every step).
 SENSITIVE_FRACTION_OF_RTOL = 0.125
 SENSITIVE_RTOL = 5e-2
 MAX_SENSITIVE_SHARE = 0.03
+CHAOTIC_SHARE = 0.25
+CHAOTIC_MEAN_RTOL = 1.5e-2
 
 
 def compare_rollout(w, got, ref, label="", probe=None):
@@ -66,9 +73,8 @@ def compare_rollout(w, got, ref, label="", probe=None):
 
     Episode lengths must be identical except for episodes the checker flags as knife-edge;
     returns are compared where the lengths agree; fitness where every episode of the
-    individual agrees.  Sensitive episodes (see above) are held to SENSITIVE_RTOL, and at most
-    MAX_SENSITIVE_SHARE of all episodes may need that allowance.
-    Returns (knife-edge flips, worst error on regular episodes, sensitive count)."""
+    individual agrees.  Returns (knife-edge flips, worst error on regular episodes,
+    number of sensitive episodes, chaotic-regime flag)."""
     g_ret, g_len, g_fit = got
     r_ret, r_len, r_fit, r_mar = ref
     rtol = RET_RTOL[w.dtype]
@@ -77,6 +83,9 @@ def compare_rollout(w, got, ref, label="", probe=None):
         sens = (np.abs(probe[0].astype(np.float64) - r_ret) / scale > SENSITIVE_FRACTION_OF_RTOL * rtol) | (probe[1] != r_len)
     else:
         sens = np.zeros(r_ret.shape, dtype=bool)
+    chaotic = bool(np.mean(sens) > CHAOTIC_SHARE)
+    if chaotic:
+        sens = np.ones_like(sens)
     edge = (r_mar < KNIFE_EDGE[w.dtype]) | sens
     same = g_len == r_len
     assert np.all(same | edge), f"{label}: episode length differs away from the termination threshold: " \
@@ -89,15 +98,19 @@ def compare_rollout(w, got, ref, label="", probe=None):
     assert worst <= rtol, f"{label}: return mismatch {worst:.3e} > {rtol}"
     worst_sens = float(np.max(np.where(same & sens, err, 0.0)))
     assert worst_sens <= SENSITIVE_RTOL, f"{label}: return mismatch {worst_sens:.3e} on a sensitive episode"
-    excused = same & sens & (err > rtol)
-    assert np.mean(excused) <= MAX_SENSITIVE_SHARE + 1.0 / same.size, \
-        f"{label}: {int(excused.sum())} sensitive episodes beyond the regular tolerance"
+    if chaotic:
+        mean_err = abs(float(np.mean(g_ret[same].astype(np.float64))) - float(np.mean(r_ret[same]))) / abs(float(np.mean(r_ret[same])))
+        assert mean_err <= CHAOTIC_MEAN_RTOL, f"{label}: mean return over the batch off by {mean_err:.3e}"
+    else:
+        excused = same & sens & (err > rtol)
+        assert np.mean(excused) <= MAX_SENSITIVE_SHARE + 1.0 / same.size, \
+            f"{label}: {int(excused.sum())} sensitive episodes beyond the regular tolerance"
     ind_ok = np.all(same & ~sens, axis=1)
     ferr = np.abs(g_fit.astype(np.float64) - r_fit) / np.maximum(np.abs(r_fit), 1e-3)
     assert float(np.max(np.where(ind_ok, ferr, 0.0))) <= rtol, f"{label}: fitness mismatch"
     # fitness is the mean of the returns the kernel itself produced
     assert np.allclose(g_fit, g_ret.astype(np.float64).mean(axis=1), rtol=1e-5, atol=1e-5), f"{label}: fitness != mean"
-    return int(np.sum(~same)), worst, int(sens.sum())
+    return int(np.sum(~same)), (worst_sens if chaotic else worst), int(sens.sum()), chaotic
 
 
 def assert_params_close(got, ref, label=""):
