@@ -17,13 +17,17 @@ FLAGS = [
     "-fhip-fp32-correctly-rounded-divide-sqrt",
     # packed-FP32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators in architectural VGPRs: the accumulation-register half of the file is
+    # reserved for the register-resident policy weights of the rollout kernel
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 
 
 def _compile(src: str) -> Path:
     obj = CSRC / (Path(src).stem + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
+    extra = os.environ.get("ES_EXTRA_HIPCC_FLAGS", "").split()      # tuning experiments only
+    cmd = [HIPCC, *FLAGS, *extra, "-c", str(CSRC / src), "-o", str(obj)]
     subprocess.check_call(cmd, cwd=str(CSRC))
     return obj
 

@@ -50,14 +50,15 @@ constexpr int KS3 = KT_H / 4;     // K tiles of the action layer per wavefront
 constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activation row
 
 #ifndef ES_V256_KTAR
-#define ES_V256_KTAR 2
+#define ES_V256_KTAR 4
 #endif
 
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
-template <int KT1_, int MT3_, int MTE_, int KTAR_>
+template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_>
 struct Variant {
+  static constexpr int NC = NC_;              // environment copies per pass: 16, or 4 with column compaction
   static constexpr int KT1 = KT1_;            // K tiles over the (padded) observation width
   static constexpr int MT3 = MT3_;            // 16-row tiles of the action layer
   static constexpr int MTE = MTE_;            // 16-row tiles of the next-state vector per wavefront
@@ -71,10 +72,10 @@ struct Variant {
   static constexpr int PAL = 32 * KTAL + 8;   // LDS pitch of the LDS-resident part of A
   // LDS map (bytes).  [0, REGION0) is the staging window, aliased by the rollout buffers.
   static constexpr int OFF_X = 0;
-  static constexpr int OFF_H1 = OFF_X + 2 * 16 * PX;
-  static constexpr int OFF_H2 = OFF_H1 + 2 * 16 * PH;
-  static constexpr int OFF_QA = OFF_H2 + 2 * 16 * PH;
-  static constexpr int OFF_P3 = OFF_QA + 2 * 16 * PA;
+  static constexpr int OFF_H1 = OFF_X + 2 * NC * PX;
+  static constexpr int OFF_H2 = OFF_H1 + 2 * NC * PH;
+  static constexpr int OFF_QA = OFF_H2 + 2 * NC * PH;
+  static constexpr int OFF_P3 = OFF_QA + 2 * NC * PA;
   static constexpr int OFF_RED = OFF_P3 + 4 * MT3 * 64 * 16;
   static constexpr int ROLL_END = OFF_RED + 4 * 16 * 8;
   static constexpr int WIN_BYTES = 2 * 256 * PW;
@@ -84,13 +85,15 @@ struct Variant {
   static constexpr int OFF_B2 = OFF_B1 + 4 * NHP;
   static constexpr int OFF_B3 = OFF_B2 + 4 * NHP;
   static constexpr int OFF_X0 = OFF_B3 + 4 * 16 * MT3;
-  static constexpr int OFF_SS0 = OFF_X0 + 2 * 16 * PX;
+  static constexpr int OFF_SS0 = OFF_X0 + 2 * NC * PX;
   static constexpr int LDS_BYTES = OFF_SS0 + 4 * 16;
   static_assert(2 * 16 * MT3 * PH <= WIN_BYTES, "the action layer is staged in one piece");
   static_assert(64 * MTE >= NOP, "the four wavefronts must cover the padded state");
   static_assert(64 * MTE <= 256, "staging window rows");
   static_assert(NAP >= 16 * MT3 && KTA <= KC, "action K padding");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(NC == 4 || NC == 16, "columns per pass");
+  static_assert(4 * MT3 * 64 * 16 >= 4 * 256, "scratch for the initial-state norms");
 };
 
 __device__ __forceinline__ bf16x8 lds_tile(const unsigned char* base, int byte_off) {
@@ -98,15 +101,50 @@ __device__ __forceinline__ bf16x8 lds_tile(const unsigned char* base, int byte_o
   return __builtin_bit_cast(bf16x8, raw);
 }
 
+// Keeps a weight tile in the accumulation-register half of the unified register file: an
+// empty asm that "updates" the tile in place pins its register class right at the use, so
+// the MFMA reads its A operand from there directly instead of through copies.
+__device__ __forceinline__ void pin_agpr(bf16x8& v) { asm volatile("" : "+a"(v)); }
+// ... and accumulators in the architectural half, where the epilogue's vector ALU work reads them.
+__device__ __forceinline__ void pin_vgpr(f32x4& v) { asm volatile("" : "+v"(v)); }
+
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Four binary32 values -> four bf16 (round to nearest even), by the packed hardware convert.
 __device__ __forceinline__ u32x2 pack_bf16x4(float a, float b, float c, float d) {
   u32x2 r;
-  r.x = bf16_bits(a) | (bf16_bits(b) << 16);
-  r.y = bf16_bits(c) | (bf16_bits(d) << 16);
+  r.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+  r.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{c, d}, bf16x2));
   return r;
+}
+
+__device__ __forceinline__ f32x4 tanh4(f32x4 v) {
+  return f32x4{tanh_fast(v.x), tanh_fast(v.y), tanh_fast(v.z), tanh_fast(v.w)};
+}
+
+// Column compaction for passes of 4 environment copies: the MFMA result tile has 16 columns
+// of which only 0..3 are real.  Lanes of bank q (columns 4q..4q+3) fetch tile q's values of
+// columns 0..3 with a row shift, so that the tanh epilogue runs once per lane, not once per tile.
+template <int CTRL, int BANK>
+__device__ __forceinline__ float dpp_take(float keep, float from) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, from),
+                                                                CTRL, 0xF, BANK, false));
+}
+template <int NT>
+__device__ __forceinline__ f32x4 compact4(const f32x4 (&t)[NT]) {
+  f32x4 v = t[0];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    if (NT > 1) v[r] = dpp_take<0x114, 0x2>(v[r], t[NT > 1 ? 1 : 0][r]);   // row_shr:4  -> columns 4..7
+    if (NT > 2) v[r] = dpp_take<0x118, 0x4>(v[r], t[NT > 2 ? 2 : 0][r]);   // row_shr:8  -> columns 8..11
+    if (NT > 3) v[r] = dpp_take<0x11C, 0x8>(v[r], t[NT > 3 ? 3 : 0][r]);   // row_shr:12 -> columns 12..15
+  }
+  return v;
 }
 
 // Fill dst[r * pitch + c] (bf16) for r < rows_p, c < COLS with the bf16-rounded source value of
@@ -138,10 +176,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void rollout_mfma_kernel(const MfmaArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int KT1 = V::KT1, MT3 = V::MT3, MTE = V::MTE, KTA = V::KTA, PX = V::PX, PA = V::PA;
+  constexpr bool ENV_ALL = (64 * MTE == V::NOP);   // every wavefront's next-state tiles are inside the padded state
+  constexpr int NC = V::NC;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, w = tid >> 6;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront index, known uniform
   const int g = lane >> 4, n = lane & 15;
+  const int col = n & (NC - 1);      // environment copy (column) this lane reads and keeps books for
+  const int q = n >> 2;              // NC == 4: which tile this lane finishes after compaction
   uint16_t* stage = reinterpret_cast<uint16_t*>(lds);
   float* b1s = reinterpret_cast<float*>(lds + V::OFF_B1);
   float* b2s = reinterpret_cast<float*>(lds + V::OFF_B2);
@@ -179,7 +222,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 
   const uint32_t per_unit = a.antithetic ? 2u : 1u;
   const uint32_t units = a.N / per_unit;
-  const uint32_t nblk = (a.E + 15u) / 16u;
+  const uint32_t nblk = (a.E + (uint32_t)NC - 1u) / (uint32_t)NC;
   int x0_block = -1;
 
   for (uint32_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
@@ -250,21 +293,22 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         // ---------------- initial states of this block of environment copies ----------------
         if (x0_block != (int)cb) {
           // thread -> (column n0, row group kq): s0[k] for k = kq, kq + 16, ...
-          const int n0 = tid & 15, kq = tid >> 4;
-          const uint32_t e0 = cb * 16u + (uint32_t)n0;
+          constexpr int KG = 256 / NC;               // row groups
+          const int n0 = tid % NC, kq = tid / NC;
+          const uint32_t e0 = cb * (uint32_t)NC + (uint32_t)n0;
           float part = 0.0f;
-          for (int k = kq; k < V::NOP; k += 16) {
+          for (int k = kq; k < V::NOP; k += KG) {
             float v = 0.0f;
             if (k < no && e0 < a.E) v = reset_value((uint32_t)k, e0, a.gen, a.k0, a.k1);
             part = __fmaf_rn(v, v, part);
             x0s[n0 * PX + k] = (uint16_t)bf16_bits(v);
           }
-          float* scratch = reinterpret_cast<float*>(lds + V::OFF_P3);   // 16 x 16 partial norms
-          scratch[kq * 16 + n0] = part;
+          float* scratch = reinterpret_cast<float*>(lds + V::OFF_P3);   // KG x NC partial norms
+          scratch[kq * NC + n0] = part;
           __syncthreads();
-          if (tid < 16) {
+          if (tid < NC) {
             float s = 0.0f;
-            for (int q = 0; q < 16; ++q) s += scratch[q * 16 + tid];
+            for (int r = 0; r < KG; ++r) s += scratch[r * NC + tid];
             ss0s[tid] = s;
           }
           x0_block = (int)cb;
@@ -274,58 +318,65 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           // copy the cached initial state into the working buffer; clear the action buffer
           const uint32_t* src = reinterpret_cast<const uint32_t*>(x0s);
           uint32_t* dst = reinterpret_cast<uint32_t*>(lds + V::OFF_X);
-          for (int q = tid; q < 16 * PX / 2; q += 256) dst[q] = src[q];
+          for (int r = tid; r < NC * PX / 2; r += 256) dst[r] = src[r];
           uint32_t* qz = reinterpret_cast<uint32_t*>(lds + V::OFF_QA);
-          for (int q = tid; q < 16 * PA / 2; q += 256) qz[q] = 0u;
+          for (int r = tid; r < NC * PA / 2; r += 256) qz[r] = 0u;
         }
         __syncthreads();
 
-        const uint32_t e = cb * 16u + (uint32_t)n;
+        const uint32_t e = cb * (uint32_t)NC + (uint32_t)col;
         bool alive = e < a.E;
-        float Rn = 0.0f, ssn = ss0s[n];
+        float Rn = 0.0f, ssn = ss0s[col];
         int32_t Ln = 0;
-        const float inv_no = 0.0f; (void)inv_no;
 
         for (uint32_t t = 0; t < a.T; ++t) {
           // ---- phase 1: h1 = tanh(W1 x + b1); start s' = A x ----
           f32x4 acc[MT_H], accE[MTE];
 #pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
+          for (int tt = 0; tt < MT_H; ++tt) { acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g); pin_vgpr(acc[tt]); }
 #pragma unroll
-          for (int tt = 0; tt < MTE; ++tt) accE[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int tt = 0; tt < MTE; ++tt) { accE[tt] = f32x4{0.f, 0.f, 0.f, 0.f}; pin_vgpr(accE[tt]); }
 #pragma unroll
           for (int kt = 0; kt < KT1; ++kt) {
-            const bf16x8 b = lds_tile(lds, V::OFF_X + 2 * (n * PX + 32 * kt + 8 * g));
+            const bf16x8 b = lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * kt + 8 * g));
 #pragma unroll
-            for (int tt = 0; tt < MT_H; ++tt) acc[tt] = mfma16(W1r[tt][kt], b, acc[tt]);
+            for (int tt = 0; tt < MT_H; ++tt) { pin_agpr(W1r[tt][kt]); acc[tt] = mfma16(W1r[tt][kt], b, acc[tt]); }
 #pragma unroll
             for (int tt = 0; tt < MTE; ++tt)
-              if (16 * (w * MTE + tt) < V::NOP) {
+              if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
                 if (kt < KTAR) accE[tt] = mfma16(Ar[tt][kt], b, accE[tt]);
                 else accE[tt] = mfma16(lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (kt - KTAR) + 8 * g)), b, accE[tt]);
               }
-            __builtin_amdgcn_sched_barrier(0);   // keep the operand loads of later K tiles from piling up in registers
           }
+          if (NC == 4) {
+            const f32x4 h = tanh4(compact4<MT_H>(acc));
+            *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+          } else {
 #pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) {
-            const u32x2 p = pack_bf16x4(tanh_fast(acc[tt].x), tanh_fast(acc[tt].y), tanh_fast(acc[tt].z), tanh_fast(acc[tt].w));
-            *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = p;
+            for (int tt = 0; tt < MT_H; ++tt) {
+              const f32x4 h = tanh4(acc[tt]);
+              *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            }
           }
           __syncthreads();
           // ---- phase 2: h2 = tanh(W2 h1 + b2) ----
 #pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
+          for (int tt = 0; tt < MT_H; ++tt) { acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g); pin_vgpr(acc[tt]); }
 #pragma unroll
           for (int kt = 0; kt < KT_H; ++kt) {
-            const bf16x8 b = lds_tile(lds, V::OFF_H1 + 2 * (n * PH + 32 * kt + 8 * g));
+            const bf16x8 b = lds_tile(lds, V::OFF_H1 + 2 * (col * PH + 32 * kt + 8 * g));
 #pragma unroll
-            for (int tt = 0; tt < MT_H; ++tt) acc[tt] = mfma16(W2r[tt][kt], b, acc[tt]);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int tt = 0; tt < MT_H; ++tt) { pin_agpr(W2r[tt][kt]); acc[tt] = mfma16(W2r[tt][kt], b, acc[tt]); }
           }
+          if (NC == 4) {
+            const f32x4 h = tanh4(compact4<MT_H>(acc));
+            *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+          } else {
 #pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) {
-            const u32x2 p = pack_bf16x4(tanh_fast(acc[tt].x), tanh_fast(acc[tt].y), tanh_fast(acc[tt].z), tanh_fast(acc[tt].w));
-            *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = p;
+            for (int tt = 0; tt < MT_H; ++tt) {
+              const f32x4 h = tanh4(acc[tt]);
+              *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            }
           }
           __syncthreads();
           // ---- phase 3: this wavefront's K slice of W3 h2 ----
@@ -334,7 +385,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             f32x4 p = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < KS3; ++kk) {
-              const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (n * PH + 32 * (w * KS3 + kk) + 8 * g));
+              const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * (w * KS3 + kk) + 8 * g));
               p = mfma16(W3r[mt][kk], b, p);
             }
             *reinterpret_cast<f32x4*>(lds + V::OFF_P3 + 16 * ((w * MT3 + mt) * 64 + lane)) = p;
@@ -342,18 +393,37 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           __syncthreads();
           // ---- phase 4: action (every wavefront, identically), reward, return ----
           float aa = 0.0f;
-#pragma unroll
-          for (int mt = 0; mt < MT3; ++mt) {
-            const f32x4 p0 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((0 * MT3 + mt) * 64 + lane));
-            const f32x4 p1 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((1 * MT3 + mt) * 64 + lane));
-            const f32x4 p2 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((2 * MT3 + mt) * 64 + lane));
-            const f32x4 p3 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((3 * MT3 + mt) * 64 + lane));
+          if (NC == 4) {
+            // lane (g, 4q + c) finishes action tile q of column c: its partials sit at lane 16g + c
+            const int mt = q & (MT3 - 1), src = 16 * g + col;
+            const bool valid = q < MT3;
+            const f32x4 p0 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((0 * MT3 + mt) * 64 + src));
+            const f32x4 p1 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((1 * MT3 + mt) * 64 + src));
+            const f32x4 p2 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((2 * MT3 + mt) * 64 + src));
+            const f32x4 p3 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((3 * MT3 + mt) * 64 + src));
             const f32x4 bb = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
             f32x4 v = (((p0 + p1) + p2) + p3) + bb;
-            if (a.out_tanh) { v.x = tanh_fast(v.x); v.y = tanh_fast(v.y); v.z = tanh_fast(v.z); v.w = tanh_fast(v.w); }
+            if (a.out_tanh) v = tanh4(v);
             aa = __fmaf_rn(v.x, v.x, aa); aa = __fmaf_rn(v.y, v.y, aa);
             aa = __fmaf_rn(v.z, v.z, aa); aa = __fmaf_rn(v.w, v.w, aa);
-            if (w == 0) *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (n * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
+            aa = valid ? aa : 0.0f;
+            if (w == 0 && valid) *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (col * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
+            aa += __shfl_xor(aa, 4, 64);
+            aa += __shfl_xor(aa, 8, 64);
+          } else {
+#pragma unroll
+            for (int mt = 0; mt < MT3; ++mt) {
+              const f32x4 p0 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((0 * MT3 + mt) * 64 + lane));
+              const f32x4 p1 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((1 * MT3 + mt) * 64 + lane));
+              const f32x4 p2 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((2 * MT3 + mt) * 64 + lane));
+              const f32x4 p3 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((3 * MT3 + mt) * 64 + lane));
+              const f32x4 bb = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
+              f32x4 v = (((p0 + p1) + p2) + p3) + bb;
+              if (a.out_tanh) v = tanh4(v);
+              aa = __fmaf_rn(v.x, v.x, aa); aa = __fmaf_rn(v.y, v.y, aa);
+              aa = __fmaf_rn(v.z, v.z, aa); aa = __fmaf_rn(v.w, v.w, aa);
+              if (w == 0) *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (n * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
+            }
           }
           aa += __shfl_xor(aa, 16, 64);
           aa += __shfl_xor(aa, 32, 64);
@@ -364,19 +434,42 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           __syncthreads();
           // ---- phase 5: s' = tanh(A x + B a); norms for the next reward and the termination test ----
           float ssp = 0.0f, mxp = 0.0f;
+          if (NC == 4) {
 #pragma unroll
-          for (int tt = 0; tt < MTE; ++tt) {
-            if (16 * (w * MTE + tt) < V::NOP) {
+            for (int tt = 0; tt < MTE; ++tt)
 #pragma unroll
               for (int kt = 0; kt < KTA; ++kt) {
-                const bf16x8 b = lds_tile(lds, V::OFF_QA + 2 * (n * PA + 32 * kt + 8 * g));
+                const bf16x8 b = lds_tile(lds, V::OFF_QA + 2 * (col * PA + 32 * kt + 8 * g));
                 accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
               }
-              const float s0 = tanh_fast(accE[tt].x), s1 = tanh_fast(accE[tt].y), s2 = tanh_fast(accE[tt].z), s3 = tanh_fast(accE[tt].w);
-              ssp = __fmaf_rn(s0, s0, ssp); ssp = __fmaf_rn(s1, s1, ssp);
-              ssp = __fmaf_rn(s2, s2, ssp); ssp = __fmaf_rn(s3, s3, ssp);
-              mxp = fmaxf(fmaxf(mxp, fmaxf(fabsf(s0), fabsf(s1))), fmaxf(fabsf(s2), fabsf(s3)));
-              *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (n * PX + 16 * (w * MTE + tt) + 4 * g)) = pack_bf16x4(s0, s1, s2, s3);
+            const int tile = w * MTE + q;
+            const bool valid = q < MTE && (ENV_ALL || 16 * tile < V::NOP);
+            const f32x4 sn = tanh4(compact4<MTE>(accE));
+            if (valid) {
+              ssp = __fmaf_rn(sn.x, sn.x, ssp); ssp = __fmaf_rn(sn.y, sn.y, ssp);
+              ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
+              mxp = fmaxf(fmaxf(fabsf(sn.x), fabsf(sn.y)), fmaxf(fabsf(sn.z), fabsf(sn.w)));
+              *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
+            }
+            ssp += __shfl_xor(ssp, 4, 64);
+            ssp += __shfl_xor(ssp, 8, 64);
+            mxp = fmaxf(mxp, __shfl_xor(mxp, 4, 64));
+            mxp = fmaxf(mxp, __shfl_xor(mxp, 8, 64));
+          } else {
+#pragma unroll
+            for (int tt = 0; tt < MTE; ++tt) {
+              if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
+#pragma unroll
+                for (int kt = 0; kt < KTA; ++kt) {
+                  const bf16x8 b = lds_tile(lds, V::OFF_QA + 2 * (n * PA + 32 * kt + 8 * g));
+                  accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
+                }
+                const f32x4 sn = tanh4(accE[tt]);
+                ssp = __fmaf_rn(sn.x, sn.x, ssp); ssp = __fmaf_rn(sn.y, sn.y, ssp);
+                ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
+                mxp = fmaxf(fmaxf(mxp, fmaxf(fabsf(sn.x), fabsf(sn.y))), fmaxf(fabsf(sn.z), fabsf(sn.w)));
+                *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (n * PX + 16 * (w * MTE + tt) + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
+              }
             }
           }
           ssp += __shfl_xor(ssp, 16, 64);
@@ -384,12 +477,12 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           mxp = fmaxf(mxp, __shfl_xor(mxp, 16, 64));
           mxp = fmaxf(mxp, __shfl_xor(mxp, 32, 64));
           float* red = reinterpret_cast<float*>(lds + V::OFF_RED);
-          if (g == 0) { red[(w * 16 + n) * 2] = ssp; red[(w * 16 + n) * 2 + 1] = mxp; }
+          if (g == 0 && n < NC) { red[(w * 16 + n) * 2] = ssp; red[(w * 16 + n) * 2 + 1] = mxp; }
           __syncthreads();
           // ---- phase 6: combine the four wavefronts in a fixed order; termination ----
-          ssn = ((red[(0 * 16 + n) * 2] + red[(1 * 16 + n) * 2]) + red[(2 * 16 + n) * 2]) + red[(3 * 16 + n) * 2];
-          const float mx = fmaxf(fmaxf(red[(0 * 16 + n) * 2 + 1], red[(1 * 16 + n) * 2 + 1]),
-                                 fmaxf(red[(2 * 16 + n) * 2 + 1], red[(3 * 16 + n) * 2 + 1]));
+          ssn = ((red[(0 * 16 + col) * 2] + red[(1 * 16 + col) * 2]) + red[(2 * 16 + col) * 2]) + red[(3 * 16 + col) * 2];
+          const float mx = fmaxf(fmaxf(red[(0 * 16 + col) * 2 + 1], red[(1 * 16 + col) * 2 + 1]),
+                                 fmaxf(red[(2 * 16 + col) * 2 + 1], red[(3 * 16 + col) * 2 + 1]));
           alive = alive && !(mx > a.done_thresh);
           if (__ballot(alive) == 0ull) break;       // identical in all four wavefronts
         }
@@ -397,12 +490,12 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 
         // ---------------- outputs of this block of environment copies ----------------
         if (w == 0) {
-          const uint32_t cnt = min(16u, a.E - cb * 16u);
+          const uint32_t cnt = min((uint32_t)NC, a.E - cb * (uint32_t)NC);
           if (g == 0 && (uint32_t)n < cnt) {
             a.returns[(size_t)i * a.E + e] = Rn;
             a.ep_len[(size_t)i * a.E + e] = Ln;
           }
-          for (uint32_t q = 0; q < cnt; ++q) fit_sum += __shfl(Rn, (int)q, 64);
+          for (uint32_t r = 0; r < cnt; ++r) fit_sum += __shfl(Rn, (int)r, 64);
         }
       }
       if (tid == 0) a.fitness[i] = fit_sum / (float)a.E;
@@ -410,10 +503,10 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   }
 }
 
-using V32 = Variant<1, 1, 1, 1>;     // obs <= 32,  act <= 16
-using V64 = Variant<2, 1, 1, 2>;     // obs <= 64,  act <= 16
-using V128 = Variant<4, 2, 2, 4>;    // obs <= 128, act <= 32
-using V256 = Variant<8, 2, 4, ES_V256_KTAR>;    // obs <= 256, act <= 32; part of A lives in LDS
+template <int NC> using V32 = Variant<1, 1, 1, 1, NC>;     // obs <= 32,  act <= 16
+template <int NC> using V64 = Variant<2, 1, 1, 2, NC>;     // obs <= 64,  act <= 16
+template <int NC> using V128 = Variant<4, 2, 2, 4, NC>;    // obs <= 128, act <= 32
+template <int NC> using V256 = Variant<8, 2, 4, ES_V256_KTAR, NC>;   // obs <= 256, act <= 32; part of A lives in LDS
 
 struct VariantInfo { int max_obs, max_act; const char* name; };
 static const VariantInfo kVariants[] = {
@@ -455,15 +548,16 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_bf16 = c.noise_dtype == 1;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
-  if ((int)V256::LDS_BYTES > ctx->lds_limit)
+  if ((int)V256<16>::LDS_BYTES > ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");
   const uint32_t units = c.antithetic ? s.N / 2 : s.N;
   const uint32_t grid = std::min<uint32_t>(units, (uint32_t)std::max(1, ctx->num_cus));
+  const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
   switch (ctx->mfma_variant) {
-    case 0: return launch_variant<V32>(ctx, a, grid, st);
-    case 1: return launch_variant<V64>(ctx, a, grid, st);
-    case 2: return launch_variant<V128>(ctx, a, grid, st);
-    case 3: return launch_variant<V256>(ctx, a, grid, st);
+    case 0: return narrow ? launch_variant<V32<4>>(ctx, a, grid, st) : launch_variant<V32<16>>(ctx, a, grid, st);
+    case 1: return narrow ? launch_variant<V64<4>>(ctx, a, grid, st) : launch_variant<V64<16>>(ctx, a, grid, st);
+    case 2: return narrow ? launch_variant<V128<4>>(ctx, a, grid, st) : launch_variant<V128<16>>(ctx, a, grid, st);
+    case 3: return narrow ? launch_variant<V256<4>>(ctx, a, grid, st) : launch_variant<V256<16>>(ctx, a, grid, st);
     default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident variant for this shape");
   }
 }
