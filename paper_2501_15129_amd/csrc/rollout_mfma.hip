@@ -12,9 +12,9 @@
 //   * Each wavefront owns 64 output units (four 16-row tiles) of every wide layer; the
 //     environment copies are the 16 columns of the MFMA.  Activations travel between
 //     wavefronts as bf16 through LDS ([column][unit], padded pitch, 16-byte reads).
-//   * The 256 -> act layer is split along K over the four wavefronts and summed in a fixed
-//     order; reward norms and the termination test are shuffle + LDS reductions in a
-//     fixed order, so reruns are bit-identical.
+//   * The narrow 256 -> act layer is read from LDS and computed by one wavefront per 16-row
+//     tile; reward norms and the termination test are reduced through per-wavefront LDS
+//     partials that every lane adds in the same fixed order, so reruns are bit-identical.
 //   * The grid is persistent: workgroup b handles noise rows b, b + grid, ...; the two
 //     mirrored individuals of a row run back to back.
 // Bound: MFMA issue (dense 16x16x32 bf16) plus the tanh epilogue on the vector ALU.
@@ -46,13 +46,14 @@ struct MfmaArgs {
 constexpr int NHP = 256;          // padded hidden width handled by this kernel
 constexpr int MT_H = NHP / 64;    // 16-row tiles of a wide layer per wavefront
 constexpr int KT_H = NHP / 32;    // 32-deep K tiles over the hidden width
-constexpr int KS3 = KT_H / 4;     // K tiles of the action layer per wavefront
 constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activation row
 
 #ifndef ES_V256_KTAR
 #define ES_V256_KTAR 4
 #endif
 
+constexpr int PSP = 20;           // floats per column of the norm partials (16 used; 80-byte pitch spreads the banks)
+constexpr int PAP = 12;           // floats per column of the action-norm partials (8 used)
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
@@ -75,25 +76,27 @@ struct Variant {
   static constexpr int OFF_H1 = OFF_X + 2 * NC * PX;
   static constexpr int OFF_H2 = OFF_H1 + 2 * NC * PH;
   static constexpr int OFF_QA = OFF_H2 + 2 * NC * PH;
-  static constexpr int OFF_P3 = OFF_QA + 2 * NC * PA;
-  static constexpr int OFF_RED = OFF_P3 + 4 * MT3 * 64 * 16;
-  static constexpr int ROLL_END = OFF_RED + 4 * 16 * 8;
+  static constexpr int OFF_SSP = OFF_QA + 2 * NC * PA;     // |s'|^2 partials  [column][wavefront*4 + row group]
+  static constexpr int OFF_MXP = OFF_SSP + 4 * 16 * PSP;   // max|s'| partials, same layout
+  static constexpr int OFF_AAP = OFF_MXP + 4 * 16 * PSP;   // |a|^2 partials    [column][tile*4 + row group]
+  static constexpr int OFF_SCR = OFF_AAP + 4 * 16 * PAP;   // scratch for the initial-state norms
+  static constexpr int ROLL_END = OFF_SCR + 4 * 256;
   static constexpr int WIN_BYTES = 2 * 256 * PW;
   static constexpr int REGION0 = ROLL_END > WIN_BYTES ? ROLL_END : WIN_BYTES;
   static constexpr int OFF_AL = REGION0;
-  static constexpr int OFF_B1 = OFF_AL + (KTAL ? 2 * 64 * MTE * PAL : 0);
+  static constexpr int OFF_W3 = OFF_AL + (KTAL ? 2 * 64 * MTE * PAL : 0);   // action-layer weights [16*MT3][PH]
+  static constexpr int OFF_B1 = OFF_W3 + 2 * 16 * MT3 * PH;
   static constexpr int OFF_B2 = OFF_B1 + 4 * NHP;
   static constexpr int OFF_B3 = OFF_B2 + 4 * NHP;
   static constexpr int OFF_X0 = OFF_B3 + 4 * 16 * MT3;
   static constexpr int OFF_SS0 = OFF_X0 + 2 * NC * PX;
   static constexpr int LDS_BYTES = OFF_SS0 + 4 * 16;
-  static_assert(2 * 16 * MT3 * PH <= WIN_BYTES, "the action layer is staged in one piece");
   static_assert(64 * MTE >= NOP, "the four wavefronts must cover the padded state");
   static_assert(64 * MTE <= 256, "staging window rows");
   static_assert(NAP >= 16 * MT3 && KTA <= KC, "action K padding");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
   static_assert(NC == 4 || NC == 16, "columns per pass");
-  static_assert(4 * MT3 * 64 * 16 >= 4 * 256, "scratch for the initial-state norms");
+  static_assert(MT3 <= 2 && MT3 <= 4, "action tiles: one wavefront each, partial layout holds two");
 };
 
 __device__ __forceinline__ bf16x8 lds_tile(const unsigned char* base, int byte_off) {
@@ -145,6 +148,20 @@ __device__ __forceinline__ f32x4 compact4(const f32x4 (&t)[NT]) {
     if (NT > 3) v[r] = dpp_take<0x11C, 0x8>(v[r], t[NT > 3 ? 3 : 0][r]);   // row_shr:12 -> columns 12..15
   }
   return v;
+}
+
+// Sum / max over the four banks of a 16-lane row (lanes c, c+4, c+8, c+12), result in lanes 0..3.
+template <int CTRL>
+__device__ __forceinline__ float dpp_shl(float v) {   // lane i <- lane i + n within the row, 0 past the end
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row_bank_sum(float v) {
+  v = v + dpp_shl<0x104>(v);
+  return v + dpp_shl<0x108>(v);
+}
+__device__ __forceinline__ float row_bank_max(float v) {   // for non-negative values
+  v = fmaxf(v, dpp_shl<0x104>(v));
+  return fmaxf(v, dpp_shl<0x108>(v));
 }
 
 // Fill dst[r * pitch + c] (bf16) for r < rows_p, c < COLS with the bf16-rounded source value of
@@ -234,7 +251,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
                              : static_cast<const void*>(static_cast<const float*>(a.noise) + (size_t)unit * a.ld);
 
       // ---------------- perturbed policy weights -> registers ----------------
-      bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H], W3r[MT3][KS3];
+      bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H];
       for (int u = tid; u < NHP; u += 256) {     // biases: perturbed, bf16-rounded, kept as binary32
         float v1 = 0.0f, v2 = 0.0f;
         if (u < nh) {
@@ -256,6 +273,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         }
         b3s[c] = v3;
       }
+      // action-layer weights stay in LDS (read by one wavefront per tile each step)
+      stage_cols<NHP, true>(reinterpret_cast<uint16_t*>(lds + V::OFF_W3), PH, 16 * MT3, na, nh, 0, a.theta, nrow,
+                            a.noise_bf16, scale, a.oW3);
 #pragma unroll
       for (int kr = 0; kr < (KT1 + KC - 1) / KC; ++kr) {
         stage_cols<32 * KC, true>(stage, PW, NHP, nh, no, 32 * KC * kr, a.theta, nrow, a.noise_bf16, scale, a.oW1);
@@ -279,14 +299,6 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             W2r[t][kr * KC + kk] = lds_tile(lds, 2 * ((16 * (w * MT_H + t) + n) * PW + 32 * kk + 8 * g));
         __syncthreads();
       }
-      stage_cols<NHP, true>(stage, PH, 16 * MT3, na, nh, 0, a.theta, nrow, a.noise_bf16, scale, a.oW3);
-      __syncthreads();
-#pragma unroll
-      for (int mt = 0; mt < MT3; ++mt)
-#pragma unroll
-        for (int kk = 0; kk < KS3; ++kk)
-          W3r[mt][kk] = lds_tile(lds, 2 * ((16 * mt + n) * PH + 32 * (w * KS3 + kk) + 8 * g));
-      __syncthreads();
 
       float fit_sum = 0.0f;
       for (uint32_t cb = 0; cb < nblk; ++cb) {
@@ -303,7 +315,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             part = __fmaf_rn(v, v, part);
             x0s[n0 * PX + k] = (uint16_t)bf16_bits(v);
           }
-          float* scratch = reinterpret_cast<float*>(lds + V::OFF_P3);   // KG x NC partial norms
+          float* scratch = reinterpret_cast<float*>(lds + V::OFF_SCR);   // KG x NC partial norms
           scratch[kq * NC + n0] = part;
           __syncthreads();
           if (tid < NC) {
@@ -326,26 +338,88 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 
         const uint32_t e = cb * (uint32_t)NC + (uint32_t)col;
         bool alive = e < a.E;
-        float Rn = 0.0f, ssn = ss0s[col];
+        float Rn = 0.0f;
         int32_t Ln = 0;
+        const float inv_no = 1.0f / (float)no;
+        constexpr int KA1 = (KT1 + 1) / 2;       // K tiles of A x done beside layer 1; the rest beside layer 2
 
-        for (uint32_t t = 0; t < a.T; ++t) {
-          // ---- phase 1: h1 = tanh(W1 x + b1); start s' = A x ----
-          f32x4 acc[MT_H], accE[MTE];
+        f32x4 acc[MT_H], accE[MTE];
 #pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) { acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g); pin_vgpr(acc[tt]); }
+        for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
+        // the norm partials of "step -1": |s_0|^2 in slot 0, nothing above the threshold, no action yet
+        if (tid < 16) {
+          float* sp = reinterpret_cast<float*>(lds + V::OFF_SSP) + tid * PSP;
+          float* mp = reinterpret_cast<float*>(lds + V::OFF_MXP) + tid * PSP;
+          float* ap = reinterpret_cast<float*>(lds + V::OFF_AAP) + tid * PAP;
+          for (int r = 0; r < 16; ++r) { sp[r] = 0.0f; mp[r] = 0.0f; }
+          for (int r = 0; r < 8; ++r) ap[r] = 0.0f;
+          if (tid < NC) sp[0] = ss0s[tid];
+        }
+        __syncthreads();
+        float ss_cur = 0.0f;      // |s_{t-1}|^2 while step t starts; the reward of step t-1 is booked in step t
+        bool first = true;
+
+        for (uint32_t t = 0; t <= a.T; ++t) {
+          // ---- phase A: h1 = tanh(W1 x + b1); first half of A x; books of the previous step ----
+          // partial norms of the previous step (consumed in the middle of the MFMA stream below)
+          const f32x4* sp = reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * PSP * col);
+          const f32x4* mp = reinterpret_cast<const f32x4*>(lds + V::OFF_MXP + 4 * PSP * col);
+          const f32x4* ap = reinterpret_cast<const f32x4*>(lds + V::OFF_AAP + 4 * PAP * col);
+          f32x4 s0, s1, s2, s3, m0, m1, m2, m3, a0, a1;
+          constexpr int BOOK_STAGE = KT1 > 3 ? KT1 - 3 : 0;   // loaded late in the stream: fewer live registers
+          // W1 stream: the B operand (state tiles) runs two stages ahead of the MFMAs
+          bf16x8 bx[KA1 > 0 ? KA1 : 1], bxr[3];     // tiles < KA1 are kept for A x below; the rest pass through a ring
+          auto xload = [&](int kt) { return lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * kt + 8 * g)); };
 #pragma unroll
-          for (int tt = 0; tt < MTE; ++tt) { accE[tt] = f32x4{0.f, 0.f, 0.f, 0.f}; pin_vgpr(accE[tt]); }
+          for (int kt = 0; kt < 2 && kt < KT1; ++kt) { if (kt < KA1) bx[kt] = xload(kt); else bxr[kt % 3] = xload(kt); }
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int kt = 0; kt < KT1; ++kt) {
-            const bf16x8 b = lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * kt + 8 * g));
+            if (kt + 2 < KT1) { if (kt + 2 < KA1) bx[kt + 2] = xload(kt + 2); else bxr[(kt + 2) % 3] = xload(kt + 2); }
+            if (kt == BOOK_STAGE) {
+              s0 = sp[0]; s1 = sp[1]; s2 = sp[2]; s3 = sp[3];
+              m0 = mp[0]; m1 = mp[1]; m2 = mp[2]; m3 = mp[3];
+              a0 = ap[0]; a1 = ap[MT3 > 1 ? 1 : 0];
+            }
 #pragma unroll
-            for (int tt = 0; tt < MT_H; ++tt) { pin_agpr(W1r[tt][kt]); acc[tt] = mfma16(W1r[tt][kt], b, acc[tt]); }
+            for (int tt = 0; tt < MT_H; ++tt) {
+              pin_agpr(W1r[tt][kt]);
+              acc[tt] = mfma16(W1r[tt][kt], kt < KA1 ? bx[kt < KA1 ? kt : 0] : bxr[kt % 3], acc[tt]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          // every lane adds the partials of its column in the same fixed order
+          float ss_new, mx, aa;
+          {
+            const f32x4 sv = (s0 + s1) + (s2 + s3);
+            ss_new = (sv.x + sv.y) + (sv.z + sv.w);
+            mx = fmaxf(fmaxf(fmaxf(m0.x, m0.y), fmaxf(m0.z, m0.w)), fmaxf(fmaxf(m1.x, m1.y), fmaxf(m1.z, m1.w)));
+            mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(m2.x, m2.y), fmaxf(m2.z, m2.w)), fmaxf(fmaxf(m3.x, m3.y), fmaxf(m3.z, m3.w))));
+            f32x4 av = a0;
+            if (MT3 > 1) av = av + a1;
+            aa = (av.x + av.y) + (av.z + av.w);
+          }
+          if (!first) {
+            if (alive) {
+              Rn += __fmaf_rn(-ss_cur, inv_no, 1.0f) - a.act_cost * aa;
+              Ln += 1;
+            }
+            alive = alive && !(mx > a.done_thresh);
+          }
+          first = false;
+          ss_cur = ss_new;
+          if (t == a.T || __ballot(alive) == 0ull) break;       // identical in all four wavefronts
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int tt = 0; tt < MTE; ++tt) accE[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          // first half of A x (register tiles first) interleaved with the layer-1 epilogue
+#pragma unroll
+          for (int kt = 0; kt < KA1; ++kt) {
 #pragma unroll
             for (int tt = 0; tt < MTE; ++tt)
               if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
-                if (kt < KTAR) accE[tt] = mfma16(Ar[tt][kt], b, accE[tt]);
-                else accE[tt] = mfma16(lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (kt - KTAR) + 8 * g)), b, accE[tt]);
+                if (kt < KTAR) accE[tt] = mfma16(Ar[tt][kt], bx[kt], accE[tt]);
+                else accE[tt] = mfma16(lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (kt - KTAR) + 8 * g)), bx[kt], accE[tt]);
               }
           }
           if (NC == 4) {
@@ -358,81 +432,87 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
             }
           }
-          __syncthreads();
-          // ---- phase 2: h2 = tanh(W2 h1 + b2) ----
 #pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) { acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g); pin_vgpr(acc[tt]); }
-#pragma unroll
-          for (int kt = 0; kt < KT_H; ++kt) {
-            const bf16x8 b = lds_tile(lds, V::OFF_H1 + 2 * (col * PH + 32 * kt + 8 * g));
-#pragma unroll
-            for (int tt = 0; tt < MT_H; ++tt) { pin_agpr(W2r[tt][kt]); acc[tt] = mfma16(W2r[tt][kt], b, acc[tt]); }
+          for (int r = 0; r < KA1 * MTE; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, NC == 4 ? 4 : 8, 0);
           }
-          if (NC == 4) {
-            const f32x4 h = tanh4(compact4<MT_H>(acc));
-            *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
-          } else {
 #pragma unroll
-            for (int tt = 0; tt < MT_H; ++tt) {
-              const f32x4 h = tanh4(acc[tt]);
-              *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
+          __syncthreads();
+          // ---- phase B: h2 = tanh(W2 h1 + b2); second half of A x ----
+          {
+            constexpr int NT2 = (KT1 - KA1) * MTE;      // MFMAs of the second half of A x; j = (kt - KA1) * MTE + tt
+            constexpr int PS = (NT2 + KT_H - 1) / KT_H; // ... of which this many ride in each stage of the W2 stream
+            bf16x8 bh[3], at[3 * (PS > 0 ? PS : 1)], bx2[KT1 - KA1 > 0 ? KT1 - KA1 : 1];
+            // operands of stage kt are fetched two stages ahead: h1 tile, LDS-resident A tiles, state tiles
+            auto fetch = [&](int kt) {
+              bh[kt % 3] = lds_tile(lds, V::OFF_H1 + 2 * (col * PH + 32 * kt + 8 * g));
+#pragma unroll
+              for (int r = 0; r < PS; ++r) {
+                const int j = kt * PS + r;
+                if (j < NT2) {
+                  const int ka = KA1 + j / MTE, tt = j % MTE;
+                  if (ka >= KTAR) at[(kt % 3) * PS + r] = lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (ka - KTAR) + 8 * g));
+                  if (tt == 0 || r == 0) bx2[ka - KA1] = lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * ka + 8 * g));
+                }
+              }
+            };
+            fetch(0);
+            fetch(1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kt = 0; kt < KT_H; ++kt) {
+              if (kt + 2 < KT_H) fetch(kt + 2);
+#pragma unroll
+              for (int tt = 0; tt < MT_H; ++tt) { pin_agpr(W2r[tt][kt]); acc[tt] = mfma16(W2r[tt][kt], bh[kt % 3], acc[tt]); }
+#pragma unroll
+              for (int r = 0; r < PS; ++r) {
+                const int j = kt * PS + r;
+                if (j < NT2) {
+                  const int ka = KA1 + j / MTE, tt = j % MTE;
+                  if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
+                    if (ka < KTAR) accE[tt] = mfma16(Ar[tt][ka < KTAR ? ka : 0], bx2[ka - KA1], accE[tt]);
+                    else accE[tt] = mfma16(at[(kt % 3) * PS + r], bx2[ka - KA1], accE[tt]);
+                  }
+                }
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            if (NC == 4) {
+              const f32x4 h = tanh4(compact4<MT_H>(acc));
+              *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            } else {
+#pragma unroll
+              for (int tt = 0; tt < MT_H; ++tt) {
+                const f32x4 h = tanh4(acc[tt]);
+                *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+              }
             }
           }
           __syncthreads();
-          // ---- phase 3: this wavefront's K slice of W3 h2 ----
+          // ---- phase C: a = tanh(W3 h2 + b3), one wavefront per 16-row tile, weights from LDS ----
+          if (w < MT3) {
+            f32x4 p[4];
+            p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
+            p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int mt = 0; mt < MT3; ++mt) {
-            f32x4 p = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < KS3; ++kk) {
-              const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * (w * KS3 + kk) + 8 * g));
-              p = mfma16(W3r[mt][kk], b, p);
+            for (int kt = 0; kt < KT_H; ++kt) {
+              const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * kt + 8 * g));
+              const bf16x8 wt = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
+              p[kt & 3] = mfma16(wt, b, p[kt & 3]);
             }
-            *reinterpret_cast<f32x4*>(lds + V::OFF_P3 + 16 * ((w * MT3 + mt) * 64 + lane)) = p;
-          }
-          __syncthreads();
-          // ---- phase 4: action (every wavefront, identically), reward, return ----
-          float aa = 0.0f;
-          if (NC == 4) {
-            // lane (g, 4q + c) finishes action tile q of column c: its partials sit at lane 16g + c
-            const int mt = q & (MT3 - 1), src = 16 * g + col;
-            const bool valid = q < MT3;
-            const f32x4 p0 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((0 * MT3 + mt) * 64 + src));
-            const f32x4 p1 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((1 * MT3 + mt) * 64 + src));
-            const f32x4 p2 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((2 * MT3 + mt) * 64 + src));
-            const f32x4 p3 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((3 * MT3 + mt) * 64 + src));
-            const f32x4 bb = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
-            f32x4 v = (((p0 + p1) + p2) + p3) + bb;
+            f32x4 v = (p[0] + p[1]) + (p[2] + p[3]);
             if (a.out_tanh) v = tanh4(v);
-            aa = __fmaf_rn(v.x, v.x, aa); aa = __fmaf_rn(v.y, v.y, aa);
-            aa = __fmaf_rn(v.z, v.z, aa); aa = __fmaf_rn(v.w, v.w, aa);
-            aa = valid ? aa : 0.0f;
-            if (w == 0 && valid) *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (col * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
-            aa += __shfl_xor(aa, 4, 64);
-            aa += __shfl_xor(aa, 8, 64);
-          } else {
-#pragma unroll
-            for (int mt = 0; mt < MT3; ++mt) {
-              const f32x4 p0 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((0 * MT3 + mt) * 64 + lane));
-              const f32x4 p1 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((1 * MT3 + mt) * 64 + lane));
-              const f32x4 p2 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((2 * MT3 + mt) * 64 + lane));
-              const f32x4 p3 = *reinterpret_cast<const f32x4*>(lds + V::OFF_P3 + 16 * ((3 * MT3 + mt) * 64 + lane));
-              const f32x4 bb = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
-              f32x4 v = (((p0 + p1) + p2) + p3) + bb;
-              if (a.out_tanh) v = tanh4(v);
-              aa = __fmaf_rn(v.x, v.x, aa); aa = __fmaf_rn(v.y, v.y, aa);
-              aa = __fmaf_rn(v.z, v.z, aa); aa = __fmaf_rn(v.w, v.w, aa);
-              if (w == 0) *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (n * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
+            float part = v.x * v.x;
+            part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+            if (n < NC) {     // with 4-column passes the lanes of columns 4..15 hold copies
+              *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (col * PA + 16 * w + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
+              reinterpret_cast<float*>(lds + V::OFF_AAP)[col * PAP + w * 4 + g] = part;
             }
           }
-          aa += __shfl_xor(aa, 16, 64);
-          aa += __shfl_xor(aa, 32, 64);
-          if (alive) {
-            Rn += (1.0f - ssn / (float)no) - a.act_cost * aa;
-            Ln += 1;
-          }
           __syncthreads();
-          // ---- phase 5: s' = tanh(A x + B a); norms for the next reward and the termination test ----
+          // ---- phase D: s' = tanh(A x + B a); partial norms for the reward and the termination test ----
           float ssp = 0.0f, mxp = 0.0f;
           if (NC == 4) {
 #pragma unroll
@@ -446,15 +526,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             const bool valid = q < MTE && (ENV_ALL || 16 * tile < V::NOP);
             const f32x4 sn = tanh4(compact4<MTE>(accE));
             if (valid) {
-              ssp = __fmaf_rn(sn.x, sn.x, ssp); ssp = __fmaf_rn(sn.y, sn.y, ssp);
-              ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
+              ssp = sn.x * sn.x;
+              ssp = __fmaf_rn(sn.y, sn.y, ssp); ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
               mxp = fmaxf(fmaxf(fabsf(sn.x), fabsf(sn.y)), fmaxf(fabsf(sn.z), fabsf(sn.w)));
               *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
             }
-            ssp += __shfl_xor(ssp, 4, 64);
-            ssp += __shfl_xor(ssp, 8, 64);
-            mxp = fmaxf(mxp, __shfl_xor(mxp, 4, 64));
-            mxp = fmaxf(mxp, __shfl_xor(mxp, 8, 64));
+            ssp = row_bank_sum(ssp);
+            mxp = row_bank_max(mxp);
           } else {
 #pragma unroll
             for (int tt = 0; tt < MTE; ++tt) {
@@ -472,19 +550,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               }
             }
           }
-          ssp += __shfl_xor(ssp, 16, 64);
-          ssp += __shfl_xor(ssp, 32, 64);
-          mxp = fmaxf(mxp, __shfl_xor(mxp, 16, 64));
-          mxp = fmaxf(mxp, __shfl_xor(mxp, 32, 64));
-          float* red = reinterpret_cast<float*>(lds + V::OFF_RED);
-          if (g == 0 && n < NC) { red[(w * 16 + n) * 2] = ssp; red[(w * 16 + n) * 2 + 1] = mxp; }
+          if (n < NC) {
+            reinterpret_cast<float*>(lds + V::OFF_SSP)[col * PSP + w * 4 + g] = ssp;
+            reinterpret_cast<float*>(lds + V::OFF_MXP)[col * PSP + w * 4 + g] = mxp;
+          }
+#pragma unroll
+          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
           __syncthreads();
-          // ---- phase 6: combine the four wavefronts in a fixed order; termination ----
-          ssn = ((red[(0 * 16 + col) * 2] + red[(1 * 16 + col) * 2]) + red[(2 * 16 + col) * 2]) + red[(3 * 16 + col) * 2];
-          const float mx = fmaxf(fmaxf(red[(0 * 16 + col) * 2 + 1], red[(1 * 16 + col) * 2 + 1]),
-                                 fmaxf(red[(2 * 16 + col) * 2 + 1], red[(3 * 16 + col) * 2 + 1]));
-          alive = alive && !(mx > a.done_thresh);
-          if (__ballot(alive) == 0ull) break;       // identical in all four wavefronts
         }
         __syncthreads();   // all reads of the rollout buffers are done before anything is restaged
 
