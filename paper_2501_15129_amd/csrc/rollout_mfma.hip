@@ -52,14 +52,16 @@ constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activ
 #define ES_V256_KTAR 4
 #endif
 
-constexpr int PSP = 20;           // floats per column of the norm partials (16 used; 80-byte pitch spreads the banks)
-constexpr int PAP = 12;           // floats per column of the action-norm partials (8 used)
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
 template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_>
 struct Variant {
   static constexpr int NC = NC_;              // environment copies per pass: 16, or 4 with column compaction
+  // One 16-row action tile: every wavefront computes it (no exchange before the environment
+  // step).  Two tiles: wavefront mt computes tile mt and the action goes through LDS, because
+  // the replicated version quadruples the LDS traffic of the weight tiles, which then dominates.
+  static constexpr bool ACT_SPLIT = MT3_ > 1;
   static constexpr int KT1 = KT1_;            // K tiles over the (padded) observation width
   static constexpr int MT3 = MT3_;            // 16-row tiles of the action layer
   static constexpr int MTE = MTE_;            // 16-row tiles of the next-state vector per wavefront
@@ -76,10 +78,10 @@ struct Variant {
   static constexpr int OFF_H1 = OFF_X + 2 * NC * PX;
   static constexpr int OFF_H2 = OFF_H1 + 2 * NC * PH;
   static constexpr int OFF_QA = OFF_H2 + 2 * NC * PH;
-  static constexpr int OFF_SSP = OFF_QA + 2 * NC * PA;     // |s'|^2 partials  [column][wavefront*4 + row group]
-  static constexpr int OFF_MXP = OFF_SSP + 4 * 16 * PSP;   // max|s'| partials, same layout
-  static constexpr int OFF_AAP = OFF_MXP + 4 * 16 * PSP;   // |a|^2 partials    [column][tile*4 + row group]
-  static constexpr int OFF_SCR = OFF_AAP + 4 * 16 * PAP;   // scratch for the initial-state norms
+  static constexpr int OFF_SSP = OFF_QA + 4 * 2 * NC * PA; // (one action buffer per wavefront) |s'|^2 partials [column][wavefront]
+  static constexpr int OFF_MXP = OFF_SSP + 4 * 16 * 4;     // max|s'| partials, same layout
+  static constexpr int OFF_AAP = OFF_MXP + 4 * 16 * 4;     // |a|^2 partials [column][action tile] (split action layer only)
+  static constexpr int OFF_SCR = OFF_AAP + 4 * 16 * 2;     // scratch for the initial-state norms
   static constexpr int ROLL_END = OFF_SCR + 4 * 256;
   static constexpr int WIN_BYTES = 2 * 256 * PW;
   static constexpr int REGION0 = ROLL_END > WIN_BYTES ? ROLL_END : WIN_BYTES;
@@ -150,6 +152,8 @@ __device__ __forceinline__ f32x4 compact4(const f32x4 (&t)[NT]) {
   return v;
 }
 
+__device__ __forceinline__ unsigned umax(unsigned a, unsigned b) { return a > b ? a : b; }
+
 // Sum / max over the four banks of a 16-lane row (lanes c, c+4, c+8, c+12), result in lanes 0..3.
 template <int CTRL>
 __device__ __forceinline__ float dpp_shl(float v) {   // lane i <- lane i + n within the row, 0 past the end
@@ -159,10 +163,29 @@ __device__ __forceinline__ float row_bank_sum(float v) {
   v = v + dpp_shl<0x104>(v);
   return v + dpp_shl<0x108>(v);
 }
-__device__ __forceinline__ float row_bank_max(float v) {   // for non-negative values
-  v = fmaxf(v, dpp_shl<0x104>(v));
-  return fmaxf(v, dpp_shl<0x108>(v));
+__device__ __forceinline__ unsigned row_bank_umax(unsigned v) {   // bit patterns of non-negative values
+  v = umax(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0xF, true));
+  return umax(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x108, 0xF, 0xF, true));
 }
+
+// Sum / max over the four 16-lane rows of the wavefront (lanes l, l+16, l+32, l+48), result in
+// every row, by the row-swap instructions of gfx950 (vector ALU speed, no LDS round trip).
+__device__ __forceinline__ float rows_sum(float v) {
+  const unsigned b = __builtin_bit_cast(unsigned, v);
+  const auto p = __builtin_amdgcn_permlane16_swap(b, b, false, false);     // (r0,r0,r2,r2) and (r1,r1,r3,r3)
+  const float t = __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
+  const unsigned c = __builtin_bit_cast(unsigned, t);
+  const auto r = __builtin_amdgcn_permlane32_swap(c, c, false, false);     // (lo,lo) and (hi,hi)
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+// max of non-negative binary32 values = max of their bit patterns as integers (no NaN canonicalisation needed)
+__device__ __forceinline__ unsigned rows_umax(unsigned b) {
+  const auto p = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+  const unsigned c = umax((unsigned)p[0], (unsigned)p[1]);
+  const auto r = __builtin_amdgcn_permlane32_swap(c, c, false, false);
+  return umax((unsigned)r[0], (unsigned)r[1]);
+}
+__device__ __forceinline__ unsigned abs_bits(float v) { return __builtin_bit_cast(unsigned, v) & 0x7FFFFFFFu; }
 
 // Fill dst[r * pitch + c] (bf16) for r < rows_p, c < COLS with the bf16-rounded source value of
 // matrix element (r, kbase + c) when r < rows and kbase + c < cols, and zero elsewhere.
@@ -332,7 +355,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           uint32_t* dst = reinterpret_cast<uint32_t*>(lds + V::OFF_X);
           for (int r = tid; r < NC * PX / 2; r += 256) dst[r] = src[r];
           uint32_t* qz = reinterpret_cast<uint32_t*>(lds + V::OFF_QA);
-          for (int r = tid; r < NC * PA / 2; r += 256) qz[r] = 0u;
+          for (int r = tid; r < 4 * NC * PA / 2; r += 256) qz[r] = 0u;
         }
         __syncthreads();
 
@@ -346,27 +369,26 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         f32x4 acc[MT_H], accE[MTE];
 #pragma unroll
         for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
-        // the norm partials of "step -1": |s_0|^2 in slot 0, nothing above the threshold, no action yet
+        // the norm partials of "step -1": |s_0|^2 in slot 0, nothing above the threshold
         if (tid < 16) {
-          float* sp = reinterpret_cast<float*>(lds + V::OFF_SSP) + tid * PSP;
-          float* mp = reinterpret_cast<float*>(lds + V::OFF_MXP) + tid * PSP;
-          float* ap = reinterpret_cast<float*>(lds + V::OFF_AAP) + tid * PAP;
-          for (int r = 0; r < 16; ++r) { sp[r] = 0.0f; mp[r] = 0.0f; }
-          for (int r = 0; r < 8; ++r) ap[r] = 0.0f;
+          float* sp = reinterpret_cast<float*>(lds + V::OFF_SSP) + tid * 4;
+          unsigned* mp = reinterpret_cast<unsigned*>(lds + V::OFF_MXP) + tid * 4;
+          for (int r = 0; r < 4; ++r) { sp[r] = 0.0f; mp[r] = 0u; }
+          reinterpret_cast<float*>(lds + V::OFF_AAP)[tid * 2] = 0.0f;
+          reinterpret_cast<float*>(lds + V::OFF_AAP)[tid * 2 + 1] = 0.0f;
           if (tid < NC) sp[0] = ss0s[tid];
         }
         __syncthreads();
+        float aa_prev = 0.0f;     // |a_{t-1}|^2 of this lane's column
         float ss_cur = 0.0f;      // |s_{t-1}|^2 while step t starts; the reward of step t-1 is booked in step t
         bool first = true;
 
         for (uint32_t t = 0; t <= a.T; ++t) {
           // ---- phase A: h1 = tanh(W1 x + b1); first half of A x; books of the previous step ----
-          // partial norms of the previous step (consumed in the middle of the MFMA stream below)
-          const f32x4* sp = reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * PSP * col);
-          const f32x4* mp = reinterpret_cast<const f32x4*>(lds + V::OFF_MXP + 4 * PSP * col);
-          const f32x4* ap = reinterpret_cast<const f32x4*>(lds + V::OFF_AAP + 4 * PAP * col);
-          f32x4 s0, s1, s2, s3, m0, m1, m2, m3, a0, a1;
-          constexpr int BOOK_STAGE = KT1 > 3 ? KT1 - 3 : 0;   // loaded late in the stream: fewer live registers
+          // partial norms of the previous step, one per wavefront (consumed after the MFMA stream below)
+          const f32x4 sp4 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 16 * col);
+          const u32x4 mp4 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 16 * col);
+          const f32x2 ap2 = *reinterpret_cast<const f32x2*>(lds + V::OFF_AAP + 8 * col);
           // W1 stream: the B operand (state tiles) runs two stages ahead of the MFMAs
           bf16x8 bx[KA1 > 0 ? KA1 : 1], bxr[3];     // tiles < KA1 are kept for A x below; the rest pass through a ring
           auto xload = [&](int kt) { return lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * kt + 8 * g)); };
@@ -376,11 +398,6 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 #pragma unroll
           for (int kt = 0; kt < KT1; ++kt) {
             if (kt + 2 < KT1) { if (kt + 2 < KA1) bx[kt + 2] = xload(kt + 2); else bxr[(kt + 2) % 3] = xload(kt + 2); }
-            if (kt == BOOK_STAGE) {
-              s0 = sp[0]; s1 = sp[1]; s2 = sp[2]; s3 = sp[3];
-              m0 = mp[0]; m1 = mp[1]; m2 = mp[2]; m3 = mp[3];
-              a0 = ap[0]; a1 = ap[MT3 > 1 ? 1 : 0];
-            }
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
               pin_agpr(W1r[tt][kt]);
@@ -388,17 +405,10 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             }
             __builtin_amdgcn_sched_barrier(0);
           }
-          // every lane adds the partials of its column in the same fixed order
-          float ss_new, mx, aa;
-          {
-            const f32x4 sv = (s0 + s1) + (s2 + s3);
-            ss_new = (sv.x + sv.y) + (sv.z + sv.w);
-            mx = fmaxf(fmaxf(fmaxf(m0.x, m0.y), fmaxf(m0.z, m0.w)), fmaxf(fmaxf(m1.x, m1.y), fmaxf(m1.z, m1.w)));
-            mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(m2.x, m2.y), fmaxf(m2.z, m2.w)), fmaxf(fmaxf(m3.x, m3.y), fmaxf(m3.z, m3.w))));
-            f32x4 av = a0;
-            if (MT3 > 1) av = av + a1;
-            aa = (av.x + av.y) + (av.z + av.w);
-          }
+          // every lane combines the four wavefronts' partials of its column in the same fixed order
+          const float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
+          const float mx = __builtin_bit_cast(float, umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w)));
+          const float aa = V::ACT_SPLIT ? ap2.x + ap2.y : aa_prev;
           if (!first) {
             if (alive) {
               Rn += __fmaf_rn(-ss_cur, inv_no, 1.0f) - a.act_cost * aa;
@@ -491,68 +501,104 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             }
           }
           __syncthreads();
-          // ---- phase C: a = tanh(W3 h2 + b3), one wavefront per 16-row tile, weights from LDS ----
-          if (w < MT3) {
-            f32x4 p[4];
-            p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
-            p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
+          // ---- phase C: a = tanh(W3 h2 + b3), weights from LDS ----
+          unsigned char* qaw = lds + V::OFF_QA + (V::ACT_SPLIT ? 0 : w * (2 * NC * PA));   // action buffer read below
+          if (V::ACT_SPLIT) {
+            if (w < MT3) {     // wavefront mt computes action tile mt
+              f32x4 p[4];
+              p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
+              p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+              for (int kt = 0; kt < KT_H; ++kt) {
+                const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * kt + 8 * g));
+                const bf16x8 wt = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
+                p[kt & 3] = mfma16(wt, b, p[kt & 3]);
+              }
+              f32x4 v = (p[0] + p[1]) + (p[2] + p[3]);
+              if (a.out_tanh) v = tanh4(v);
+              float part = v.x * v.x;
+              part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+              part = rows_sum(part);
+              if (n < NC) {     // with 4-column passes the lanes of columns 4..15 hold copies
+                *reinterpret_cast<u32x2*>(qaw + 2 * (col * PA + 16 * w + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
+                if (g == 0) reinterpret_cast<float*>(lds + V::OFF_AAP)[col * 2 + w] = part;
+              }
+            }
+            __syncthreads();
+          } else {
+            // every wavefront computes the single action tile itself: no exchange before the environment step
+            f32x4 p[MT3][2];
+#pragma unroll
+            for (int mt = 0; mt < MT3; ++mt) {
+              p[mt][0] = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
+              p[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
             for (int kt = 0; kt < KT_H; ++kt) {
               const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * kt + 8 * g));
-              const bf16x8 wt = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
-              p[kt & 3] = mfma16(wt, b, p[kt & 3]);
+#pragma unroll
+              for (int mt = 0; mt < MT3; ++mt) {
+                const bf16x8 wt = lds_tile(lds, V::OFF_W3 + 2 * ((16 * mt + n) * PH + 32 * kt + 8 * g));
+                p[mt][kt & 1] = mfma16(wt, b, p[mt][kt & 1]);
+              }
             }
-            f32x4 v = (p[0] + p[1]) + (p[2] + p[3]);
-            if (a.out_tanh) v = tanh4(v);
-            float part = v.x * v.x;
-            part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
-            if (n < NC) {     // with 4-column passes the lanes of columns 4..15 hold copies
-              *reinterpret_cast<u32x2*>(lds + V::OFF_QA + 2 * (col * PA + 16 * w + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
-              reinterpret_cast<float*>(lds + V::OFF_AAP)[col * PAP + w * 4 + g] = part;
+            float part = 0.0f;
+#pragma unroll
+            for (int mt = 0; mt < MT3; ++mt) {
+              f32x4 v = p[mt][0] + p[mt][1];
+              if (a.out_tanh) v = tanh4(v);
+              part = __fmaf_rn(v.x, v.x, part); part = __fmaf_rn(v.y, v.y, part);
+              part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+              if (n < NC)     // with 4-column passes the lanes of columns 4..15 hold copies
+                *reinterpret_cast<u32x2*>(qaw + 2 * (col * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
             }
+            aa_prev = rows_sum(part);      // |a_t|^2 of column `col` (lanes of columns >= NC hold copies)
           }
-          __syncthreads();
           // ---- phase D: s' = tanh(A x + B a); partial norms for the reward and the termination test ----
-          float ssp = 0.0f, mxp = 0.0f;
+          float ssp = 0.0f;
+          unsigned mxp = 0u;
           if (NC == 4) {
 #pragma unroll
-            for (int tt = 0; tt < MTE; ++tt)
+            for (int kt = 0; kt < KTA; ++kt) {
+              const bf16x8 b = lds_tile(qaw, 2 * (col * PA + 32 * kt + 8 * g));
 #pragma unroll
-              for (int kt = 0; kt < KTA; ++kt) {
-                const bf16x8 b = lds_tile(lds, V::OFF_QA + 2 * (col * PA + 32 * kt + 8 * g));
-                accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
-              }
+              for (int tt = 0; tt < MTE; ++tt) accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
+            }
             const int tile = w * MTE + q;
             const bool valid = q < MTE && (ENV_ALL || 16 * tile < V::NOP);
             const f32x4 sn = tanh4(compact4<MTE>(accE));
             if (valid) {
               ssp = sn.x * sn.x;
               ssp = __fmaf_rn(sn.y, sn.y, ssp); ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
-              mxp = fmaxf(fmaxf(fabsf(sn.x), fabsf(sn.y)), fmaxf(fabsf(sn.z), fabsf(sn.w)));
+              mxp = umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w)));
               *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
             }
             ssp = row_bank_sum(ssp);
-            mxp = row_bank_max(mxp);
+            mxp = row_bank_umax(mxp);
           } else {
+#pragma unroll
+            for (int kt = 0; kt < KTA; ++kt) {
+              const bf16x8 b = lds_tile(qaw, 2 * (n * PA + 32 * kt + 8 * g));
+#pragma unroll
+              for (int tt = 0; tt < MTE; ++tt)
+                if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
+            }
 #pragma unroll
             for (int tt = 0; tt < MTE; ++tt) {
               if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
-#pragma unroll
-                for (int kt = 0; kt < KTA; ++kt) {
-                  const bf16x8 b = lds_tile(lds, V::OFF_QA + 2 * (n * PA + 32 * kt + 8 * g));
-                  accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
-                }
                 const f32x4 sn = tanh4(accE[tt]);
                 ssp = __fmaf_rn(sn.x, sn.x, ssp); ssp = __fmaf_rn(sn.y, sn.y, ssp);
                 ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
-                mxp = fmaxf(fmaxf(mxp, fmaxf(fabsf(sn.x), fabsf(sn.y))), fmaxf(fabsf(sn.z), fabsf(sn.w)));
+                mxp = umax(mxp, umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w))));
                 *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (n * PX + 16 * (w * MTE + tt) + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
               }
             }
           }
-          if (n < NC) {
-            reinterpret_cast<float*>(lds + V::OFF_SSP)[col * PSP + w * 4 + g] = ssp;
-            reinterpret_cast<float*>(lds + V::OFF_MXP)[col * PSP + w * 4 + g] = mxp;
+          ssp = rows_sum(ssp);
+          mxp = rows_umax(mxp);
+          if (g == 0 && n < NC) {
+            reinterpret_cast<float*>(lds + V::OFF_SSP)[col * 4 + w] = ssp;
+            reinterpret_cast<unsigned*>(lds + V::OFF_MXP)[col * 4 + w] = mxp;
           }
 #pragma unroll
           for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
