@@ -39,6 +39,17 @@ def update_bytes(w, ctx) -> int:
     return w.noise_rows * w.n_params * elt + 24 * w.n_params + 4 * w.pop
 
 
+def measured_traffic(workload_name: str):
+    """HBM bytes per launch measured offline with rocprofv3 (see profiles/), or None for other workloads."""
+    f = ROOT / "profiles" / f"hbm_traffic_{workload_name.replace('-', '_')}.txt"
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        if line.strip() and not line.startswith("#"):
+            return json.loads(line)
+    return None
+
+
 def run_generations(torch, ctx, w, bufs, steps, warmup, gen0=0):
     """Runs warmup + steps generations; returns (wall seconds for `steps`, per-stage ms lists, live env steps)."""
     names = ("sample", "rollout", "rank", "update")
@@ -108,6 +119,8 @@ def main() -> int:
     ap.add_argument("--done-rule", action="store_true", help="time the workload with its termination rule on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run plain device copies of a known size instead (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; --gpus N with N > 1 is not supported "
@@ -122,6 +135,17 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n_bytes = 1 << 30
+        src = torch.empty(n_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": n_bytes, "bytes_written_per_copy": n_bytes,
+                          "copies": 3}))
+        return 0
     base = CONFIGS[args.config]
     w = base if args.done_rule else base.fixed_length()
     a_mat, b_mat, theta = make_inputs(w)
@@ -157,10 +181,13 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
+    traffic = measured_traffic(w.name) or {}
+    roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
     roofline_update = {"kernel": "grad_partial_kernel+adam_kernel", "bound": "hbm", "achieved": ugbs, "peak": HBM_PEAK_GBS,
-                       "unit": "GB/s", "frac": ugbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": ub,
+                       "unit": "GB/s", "frac": ugbs / HBM_PEAK_GBS, "traffic": traffic.get("update_bytes_per_launch"),
+                       "bytes_per_launch": ub,
                        "avg_launch_ms": upd_ms}
 
     out = {
