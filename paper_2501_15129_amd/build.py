@@ -10,7 +10,8 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libes_hip.so"
-SOURCES = ["api.hip", "sample.hip", "rank.hip", "update.hip", "rollout_wave.hip", "rollout_mfma.hip"]
+SOURCES = ["api.hip", "sample.hip", "rank.hip", "update.hip", "rollout_wave.hip", "rollout_wave_reg.hip",
+           "rollout_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

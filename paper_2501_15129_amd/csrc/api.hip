@@ -83,7 +83,11 @@ int es_create(const es_config* cfg, es_ctx** out) {
   ctx->num_cus = cus;
   ctx->lds_bytes_wave = wave_rollout_lds_bytes(c);
   ctx->mfma_variant = mfma_variant_for(c);
-  if (ctx->mfma_variant >= 0) {
+  ctx->reg_variant = reg_variant_for(c);
+  if (ctx->reg_variant >= 0) {
+    ctx->rollout_kind = ROLLOUT_WAVE_REG;
+    ctx->kernel_name = reg_variant_name(ctx->reg_variant);
+  } else if (ctx->mfma_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_MFMA_REG;
     ctx->kernel_name = mfma_variant_name(ctx->mfma_variant);
   } else {
@@ -125,6 +129,9 @@ int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const voi
     return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->rollout_kind == ROLLOUT_WAVE_REG)
+    return launch_rollout_reg(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
+                              fitness_d, workspace_d, st);
   if (ctx->rollout_kind == ROLLOUT_MFMA_REG)
     return launch_rollout_mfma(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
                                fitness_d, workspace_d, st);

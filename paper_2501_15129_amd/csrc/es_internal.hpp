@@ -12,6 +12,7 @@ namespace es {
 enum RolloutKind : int {
   ROLLOUT_WAVE_LDS = 0,   // one wavefront per (individual, env); weights in LDS
   ROLLOUT_MFMA_REG = 1,   // one workgroup per individual; bf16 weights resident in registers, MFMA
+  ROLLOUT_WAVE_REG = 2,   // one wavefront per (individual, env); binary32 weights resident in registers
 };
 
 struct Shape {
@@ -30,6 +31,7 @@ struct es_ctx {
   es::Shape shp;
   int rollout_kind;
   int mfma_variant;          // index of the instantiated register-resident kernel, or -1
+  int reg_variant;           // index of the register-resident binary32 kernel, or -1
   size_t lds_bytes_wave;     // dynamic LDS of the wave/LDS rollout
   uint32_t upd_chunks;       // row chunks of the update reduction
   size_t workspace_bytes;
@@ -59,6 +61,12 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
 int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
                         const float* A, const float* B, float* returns, int32_t* ep_len,
                         float* fitness, void* ws, hipStream_t st);
+int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
+                       const float* A, const float* B, float* returns, int32_t* ep_len,
+                       float* fitness, void* ws, hipStream_t st);
+int launch_fitness(es_ctx* ctx, const float* returns, float* fitness, hipStream_t st);
+int reg_variant_for(const es_config& cfg);        // -1 when no binary32 register-resident kernel is built for the shape
+const char* reg_variant_name(int variant);
 int mfma_variant_for(const es_config& cfg);       // -1 when no register-resident kernel fits
 const char* mfma_variant_name(int variant);
 size_t wave_rollout_lds_bytes(const es_config& cfg);

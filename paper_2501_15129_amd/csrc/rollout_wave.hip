@@ -188,6 +188,12 @@ __global__ __launch_bounds__(256) void fitness_kernel(const float* __restrict__ 
   fitness[i] = (s / (float)E);
 }
 
+int launch_fitness(es_ctx* ctx, const float* returns, float* fitness, hipStream_t st) {
+  const Shape& s = ctx->shp;
+  hipLaunchKernelGGL(fitness_kernel, dim3((s.N + 255) / 256), dim3(256), 0, st, returns, fitness, s.N, s.E);
+  return check_launch(ctx, "es_rollout (fitness)");
+}
+
 int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,
                         const float* B, float* returns, int32_t* ep_len, float* fitness, void* /*ws*/,
                         hipStream_t st) {
@@ -215,8 +221,7 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   }
   int rc = check_launch(ctx, "es_rollout (wave/LDS)");
   if (rc != ES_OK) return rc;
-  hipLaunchKernelGGL(fitness_kernel, dim3((s.N + 255) / 256), dim3(256), 0, st, returns, fitness, s.N, s.E);
-  return check_launch(ctx, "es_rollout (fitness)");
+  return launch_fitness(ctx, returns, fitness, st);
 }
 
 }  // namespace es

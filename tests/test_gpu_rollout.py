@@ -213,3 +213,29 @@ def test_rollout_bf16_configs_full_size_fixed_length(es, idx):
     short = replace(w, name=f"{w.name}-T{t_short}", horizon=t_short)
     got, chaotic_short = _full_size_sampled(es, short, gen=0, pairs=(0, 1, 2, 3, w.pop // 4, w.pop // 2 - 1))
     assert np.all(got[1] == t_short) and not chaotic_short
+
+
+# ---- register-resident binary32 variants (the narrow policies of configs[0..2]) ----
+REG = Workload("reg", pop=6, envs=3, horizon=50, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=41)
+
+
+@pytest.mark.parametrize("w", [
+    REG,
+    replace(REG, name="reg-11-32-3", obs=11, hid=32, act=3),
+    replace(REG, name="reg-T1", horizon=1),
+    replace(REG, name="reg-N2E1", pop=2, envs=1),
+    replace(REG, name="reg-noanti-linear", antithetic=0, pop=5, out_tanh=0),
+    replace(REG, name="reg-fixedlen", done_thresh=math.inf, horizon=120),
+    replace(REG, name="reg-len1", done_thresh=1e-6),
+    replace(REG, name="reg-bf16noise", noise_dtype=1),
+    replace(REG, name="reg-11-32-3-E7", obs=11, hid=32, act=3, envs=7, pop=8),
+], ids=lambda w: w.name)
+def test_rollout_register_resident_f32(es, w):
+    ctx = es.EsContext(w)
+    assert "wave_reg" in ctx.rollout_kernel
+    _case(es, w, gen=3)
+
+
+def test_rollout_register_resident_sigma_zero(es):
+    got, _ = _case(es, replace(REG, sigma=0.0))
+    assert np.all(got[2].view(np.uint32) == got[2].view(np.uint32)[0])
