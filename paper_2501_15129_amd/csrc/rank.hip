@@ -27,9 +27,29 @@ __global__ __launch_bounds__(256) void rank_kernel(const float* __restrict__ fit
   for (uint32_t base = 0; base < n; base += RANK_TILE) {
     const uint32_t len = min(RANK_TILE, n - base);
     __syncthreads();
-    for (uint32_t t = threadIdx.x; t < len; t += 256u) keys[t] = order_key(fit[base + t]);
+    // all loads of this tile are issued before any is used (16 independent loads per thread)
+    float f[RANK_TILE / 256];
+#pragma unroll
+    for (uint32_t r = 0; r < RANK_TILE / 256; ++r) {
+      const uint32_t t = threadIdx.x + 256u * r;
+      f[r] = t < len ? fit[base + t] : 0.0f;
+    }
+#pragma unroll
+    for (uint32_t r = 0; r < RANK_TILE / 256; ++r) {
+      const uint32_t t = threadIdx.x + 256u * r;
+      if (t < len) keys[t] = order_key(f[r]);
+    }
     __syncthreads();
-    for (uint32_t t = part; t < len; t += 16u) {
+    uint32_t t = part;
+    for (; t + 48u < len; t += 64u) {          // four independent compares per iteration
+#pragma unroll
+      for (uint32_t r = 0; r < 4; ++r) {
+        const uint32_t kj = keys[t + 16u * r];
+        const uint32_t j = base + t + 16u * r;
+        cnt += (kj < ki || (kj == ki && j < i)) ? 1u : 0u;
+      }
+    }
+    for (; t < len; t += 16u) {
       const uint32_t kj = keys[t];
       const uint32_t j = base + t;
       cnt += (kj < ki || (kj == ki && j < i)) ? 1u : 0u;

@@ -10,6 +10,9 @@
 
 namespace es {
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
 template <bool BF16>
 __global__ __launch_bounds__(256) void sample_kernel(void* __restrict__ noise, uint32_t D, uint32_t ld,
                                                      uint32_t gen, uint32_t k0, uint32_t k1) {
@@ -28,9 +31,9 @@ __global__ __launch_bounds__(256) void sample_kernel(void* __restrict__ noise, u
   }
   const size_t off = (size_t)row * ld + d0;
   if (BF16) {
-    uint2 v;
-    v.x = bf16_bits(z0) | (bf16_bits(z1) << 16);
-    v.y = bf16_bits(z2) | (bf16_bits(z3) << 16);
+    uint2 v;      // packed hardware convert: round to nearest even, the same result as the integer formula
+    v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{z0, z1}, bf16x2));
+    v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{z2, z3}, bf16x2));
     *reinterpret_cast<uint2*>(static_cast<uint16_t*>(noise) + off) = v;
   } else {
     *reinterpret_cast<float4*>(static_cast<float*>(noise) + off) = make_float4(z0, z1, z2, z3);
