@@ -500,18 +500,26 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               }
             }
           }
+          // action-layer operands that do not depend on h2 are fetched before the barrier (split mode)
+          constexpr int W3PRE = 4;       // of the KT_H weight tiles; the register file has no room for all of them
+          bf16x8 w3t[V::ACT_SPLIT ? W3PRE : 1];
+          f32x4 p[4];
+          if (V::ACT_SPLIT && w < MT3) {
+#pragma unroll
+            for (int kt = 0; kt < W3PRE; ++kt) w3t[kt] = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
+            p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
+          }
           __syncthreads();
           // ---- phase C: a = tanh(W3 h2 + b3), weights from LDS ----
           unsigned char* qaw = lds + V::OFF_QA + (V::ACT_SPLIT ? 0 : w * (2 * NC * PA));   // action buffer read below
           if (V::ACT_SPLIT) {
             if (w < MT3) {     // wavefront mt computes action tile mt
-              f32x4 p[4];
-              p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
               p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int kt = 0; kt < KT_H; ++kt) {
                 const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * kt + 8 * g));
-                const bf16x8 wt = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
+                const bf16x8 wt = kt < W3PRE ? w3t[kt < W3PRE ? kt : 0]
+                                             : lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
                 p[kt & 3] = mfma16(wt, b, p[kt & 3]);
               }
               f32x4 v = (p[0] + p[1]) + (p[2] + p[3]);
