@@ -44,7 +44,6 @@ struct MfmaArgs {
 };
 
 constexpr int NHP = 256;          // padded hidden width handled by this kernel
-constexpr int MT_H = NHP / 64;    // 16-row tiles of a wide layer per wavefront
 constexpr int KT_H = NHP / 32;    // 32-deep K tiles over the hidden width
 constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activation row
 
@@ -55,8 +54,13 @@ constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activ
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
-template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_>
+template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_, int NW_, int OCC_ = 1>
 struct Variant {
+  static constexpr int OCC = OCC_;            // workgroups per CU the register budget is sized for (1 or 2)
+  static constexpr int NW = NW_;              // wavefronts per workgroup: 4 (one per SIMD) or 8 (two per SIMD)
+  static constexpr int NT = 64 * NW;          // threads per workgroup
+  static constexpr int MT_H = NHP / (16 * NW);   // 16-row tiles of a wide layer per wavefront
+  static constexpr int ENV_ROWS = 16 * NW * MTE_;   // padded rows of the next-state vector covered by the workgroup
   static constexpr int NC = NC_;              // environment copies per pass: 16, or 4 with column compaction
   // One 16-row action tile: every wavefront computes it (no exchange before the environment
   // step).  Two tiles: wavefront mt computes tile mt and the action goes through LDS, because
@@ -78,23 +82,25 @@ struct Variant {
   static constexpr int OFF_H1 = OFF_X + 2 * NC * PX;
   static constexpr int OFF_H2 = OFF_H1 + 2 * NC * PH;
   static constexpr int OFF_QA = OFF_H2 + 2 * NC * PH;
-  static constexpr int OFF_SSP = OFF_QA + 4 * 2 * NC * PA; // (one action buffer per wavefront) |s'|^2 partials [column][wavefront]
-  static constexpr int OFF_MXP = OFF_SSP + 4 * 16 * 4;     // max|s'| partials, same layout
-  static constexpr int OFF_AAP = OFF_MXP + 4 * 16 * 4;     // |a|^2 partials [column][action tile] (split action layer only)
+  static constexpr int OFF_SSP = OFF_QA + NW * 2 * NC * PA; // (one action buffer per wavefront) |s'|^2 partials [column][wavefront]
+  static constexpr int OFF_MXP = OFF_SSP + 4 * 16 * NW;     // max|s'| partials, same layout
+  static constexpr int OFF_AAP = OFF_MXP + 4 * 16 * NW;     // |a|^2 partials [column][action tile] (split action layer only)
   static constexpr int OFF_SCR = OFF_AAP + 4 * 16 * 2;     // scratch for the initial-state norms
-  static constexpr int ROLL_END = OFF_SCR + 4 * 256;
+  static constexpr int ROLL_END = OFF_SCR + 4 * NT;
   static constexpr int WIN_BYTES = 2 * 256 * PW;
   static constexpr int REGION0 = ROLL_END > WIN_BYTES ? ROLL_END : WIN_BYTES;
   static constexpr int OFF_AL = REGION0;
-  static constexpr int OFF_W3 = OFF_AL + (KTAL ? 2 * 64 * MTE * PAL : 0);   // action-layer weights [16*MT3][PH]
+  static constexpr int OFF_W3 = OFF_AL + (KTAL ? 2 * ENV_ROWS * PAL : 0);   // action-layer weights [16*MT3][PH]
   static constexpr int OFF_B1 = OFF_W3 + 2 * 16 * MT3 * PH;
   static constexpr int OFF_B2 = OFF_B1 + 4 * NHP;
   static constexpr int OFF_B3 = OFF_B2 + 4 * NHP;
   static constexpr int OFF_X0 = OFF_B3 + 4 * 16 * MT3;
   static constexpr int OFF_SS0 = OFF_X0 + 2 * NC * PX;
   static constexpr int LDS_BYTES = OFF_SS0 + 4 * 16;
-  static_assert(64 * MTE >= NOP, "the four wavefronts must cover the padded state");
-  static_assert(64 * MTE <= 256, "staging window rows");
+  static_assert(ENV_ROWS >= NOP, "the wavefronts must cover the padded state");
+  static_assert(ENV_ROWS <= 256, "staging window rows");
+  static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
+  static_assert(MT_H >= 1 && MT_H <= 4, "wide-layer tiles per wavefront");
   static_assert(NAP >= 16 * MT3 && KTA <= KC, "action K padding");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
   static_assert(NC == 4 || NC == 16, "columns per pass");
@@ -195,7 +201,7 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
                                            const float* __restrict__ src, const void* __restrict__ noise_row,
                                            bool noise_bf16, float scale, uint32_t off) {
   const int total = rows_p * COLS;
-  for (int q = threadIdx.x; q < total; q += 256) {
+  for (int q = threadIdx.x; q < total; q += (int)blockDim.x) {
     const int r = q / COLS, k = kbase + q % COLS;
     float v = 0.0f;
     if (r < rows && k < cols) {
@@ -212,11 +218,12 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
 }
 
 template <class V>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(V::NT) __attribute__((amdgpu_waves_per_eu(V::OCC * V::NW / 4, V::OCC * V::NW / 4)))
 void rollout_mfma_kernel(const MfmaArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int KT1 = V::KT1, MT3 = V::MT3, MTE = V::MTE, KTA = V::KTA, PX = V::PX, PA = V::PA;
-  constexpr bool ENV_ALL = (64 * MTE == V::NOP);   // every wavefront's next-state tiles are inside the padded state
+  constexpr int NW = V::NW, NT = V::NT, MT_H = V::MT_H;
+  constexpr bool ENV_ALL = (V::ENV_ROWS == V::NOP);   // every wavefront's next-state tiles are inside the padded state
   constexpr int NC = V::NC;
 
   const int tid = threadIdx.x;
@@ -238,7 +245,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   bf16x8 Ar[MTE][KTAR > 0 ? KTAR : 1], Br[MTE][KTA];
 #pragma unroll
   for (int kr = 0; kr < (KTAR + KC - 1) / KC; ++kr) {
-    stage_cols<32 * KC, false>(stage, PW, 64 * MTE, no, no, 32 * KC * kr, a.A, nullptr, false, 0.0f, 0u);
+    stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, no, 32 * KC * kr, a.A, nullptr, false, 0.0f, 0u);
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < MTE; ++t)
@@ -249,9 +256,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
     __syncthreads();
   }
   if (KTAL > 0)
-    stage_cols<32 * (KTAL > 0 ? KTAL : 1), false>(reinterpret_cast<uint16_t*>(lds + V::OFF_AL), PAL, 64 * MTE, no, no,
+    stage_cols<32 * (KTAL > 0 ? KTAL : 1), false>(reinterpret_cast<uint16_t*>(lds + V::OFF_AL), PAL, V::ENV_ROWS, no, no,
                                                     32 * KTAR, a.A, nullptr, false, 0.0f, 0u);
-  stage_cols<32 * KC, false>(stage, PW, 64 * MTE, no, na, 0, a.B, nullptr, false, 0.0f, 0u);
+  stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, na, 0, a.B, nullptr, false, 0.0f, 0u);
   __syncthreads();
 #pragma unroll
   for (int t = 0; t < MTE; ++t)
@@ -275,7 +282,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 
       // ---------------- perturbed policy weights -> registers ----------------
       bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H];
-      for (int u = tid; u < NHP; u += 256) {     // biases: perturbed, bf16-rounded, kept as binary32
+      for (int u = tid; u < NHP; u += NT) {     // biases: perturbed, bf16-rounded, kept as binary32
         float v1 = 0.0f, v2 = 0.0f;
         if (u < nh) {
           const uint32_t i1 = a.ob1 + u, i2 = a.ob2 + u;
@@ -287,7 +294,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         b1s[u] = v1;
         b2s[u] = v2;
       }
-      for (int c = tid; c < 16 * MT3; c += 256) {
+      for (int c = tid; c < 16 * MT3; c += NT) {
         float v3 = 0.0f;
         if (c < na) {
           const uint32_t i3 = a.ob3 + c;
@@ -328,7 +335,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         // ---------------- initial states of this block of environment copies ----------------
         if (x0_block != (int)cb) {
           // thread -> (column n0, row group kq): s0[k] for k = kq, kq + 16, ...
-          constexpr int KG = 256 / NC;               // row groups
+          constexpr int KG = NT / NC;                // row groups
           const int n0 = tid % NC, kq = tid / NC;
           const uint32_t e0 = cb * (uint32_t)NC + (uint32_t)n0;
           float part = 0.0f;
@@ -353,9 +360,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           // copy the cached initial state into the working buffer; clear the action buffer
           const uint32_t* src = reinterpret_cast<const uint32_t*>(x0s);
           uint32_t* dst = reinterpret_cast<uint32_t*>(lds + V::OFF_X);
-          for (int r = tid; r < NC * PX / 2; r += 256) dst[r] = src[r];
+          for (int r = tid; r < NC * PX / 2; r += NT) dst[r] = src[r];
           uint32_t* qz = reinterpret_cast<uint32_t*>(lds + V::OFF_QA);
-          for (int r = tid; r < 4 * NC * PA / 2; r += 256) qz[r] = 0u;
+          for (int r = tid; r < NW * NC * PA / 2; r += NT) qz[r] = 0u;
         }
         __syncthreads();
 
@@ -371,9 +378,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
         // the norm partials of "step -1": |s_0|^2 in slot 0, nothing above the threshold
         if (tid < 16) {
-          float* sp = reinterpret_cast<float*>(lds + V::OFF_SSP) + tid * 4;
-          unsigned* mp = reinterpret_cast<unsigned*>(lds + V::OFF_MXP) + tid * 4;
-          for (int r = 0; r < 4; ++r) { sp[r] = 0.0f; mp[r] = 0u; }
+          float* sp = reinterpret_cast<float*>(lds + V::OFF_SSP) + tid * NW;
+          unsigned* mp = reinterpret_cast<unsigned*>(lds + V::OFF_MXP) + tid * NW;
+          for (int r = 0; r < NW; ++r) { sp[r] = 0.0f; mp[r] = 0u; }
           reinterpret_cast<float*>(lds + V::OFF_AAP)[tid * 2] = 0.0f;
           reinterpret_cast<float*>(lds + V::OFF_AAP)[tid * 2 + 1] = 0.0f;
           if (tid < NC) sp[0] = ss0s[tid];
@@ -386,8 +393,10 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         for (uint32_t t = 0; t <= a.T; ++t) {
           // ---- phase A: h1 = tanh(W1 x + b1); first half of A x; books of the previous step ----
           // partial norms of the previous step, one per wavefront (consumed after the MFMA stream below)
-          const f32x4 sp4 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 16 * col);
-          const u32x4 mp4 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 16 * col);
+          const f32x4 sp4 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col);
+          const u32x4 mp4 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col);
+          const f32x4 sp8 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col + (NW > 4 ? 16 : 0));
+          const u32x4 mp8 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col + (NW > 4 ? 16 : 0));
           const f32x2 ap2 = *reinterpret_cast<const f32x2*>(lds + V::OFF_AAP + 8 * col);
           // W1 stream: the B operand (state tiles) runs two stages ahead of the MFMAs
           bf16x8 bx[KA1 > 0 ? KA1 : 1], bxr[3];     // tiles < KA1 are kept for A x below; the rest pass through a ring
@@ -400,14 +409,19 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             if (kt + 2 < KT1) { if (kt + 2 < KA1) bx[kt + 2] = xload(kt + 2); else bxr[(kt + 2) % 3] = xload(kt + 2); }
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
-              pin_agpr(W1r[tt][kt]);
+              if (V::OCC == 1) pin_agpr(W1r[tt][kt]);    // with two workgroups per CU only the 256x256 layer fits the accumulation half
               acc[tt] = mfma16(W1r[tt][kt], kt < KA1 ? bx[kt < KA1 ? kt : 0] : bxr[kt % 3], acc[tt]);
             }
             __builtin_amdgcn_sched_barrier(0);
           }
           // every lane combines the four wavefronts' partials of its column in the same fixed order
-          const float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
-          const float mx = __builtin_bit_cast(float, umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w)));
+          float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
+          unsigned mxb = umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w));
+          if (NW > 4) {
+            ss_new += (sp8.x + sp8.y) + (sp8.z + sp8.w);
+            mxb = umax(mxb, umax(umax(mp8.x, mp8.y), umax(mp8.z, mp8.w)));
+          }
+          const float mx = __builtin_bit_cast(float, mxb);
           const float aa = V::ACT_SPLIT ? ap2.x + ap2.y : aa_prev;
           if (!first) {
             if (alive) {
@@ -434,7 +448,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           }
           if (NC == 4) {
             const f32x4 h = tanh4(compact4<MT_H>(acc));
-            *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            if (q < MT_H)
+              *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
           } else {
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
@@ -491,7 +506,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             }
             if (NC == 4) {
               const f32x4 h = tanh4(compact4<MT_H>(acc));
-              *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+              if (q < MT_H)
+                *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
             } else {
 #pragma unroll
               for (int tt = 0; tt < MT_H; ++tt) {
@@ -605,8 +621,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           ssp = rows_sum(ssp);
           mxp = rows_umax(mxp);
           if (g == 0 && n < NC) {
-            reinterpret_cast<float*>(lds + V::OFF_SSP)[col * 4 + w] = ssp;
-            reinterpret_cast<unsigned*>(lds + V::OFF_MXP)[col * 4 + w] = mxp;
+            reinterpret_cast<float*>(lds + V::OFF_SSP)[col * NW + w] = ssp;
+            reinterpret_cast<unsigned*>(lds + V::OFF_MXP)[col * NW + w] = mxp;
           }
 #pragma unroll
           for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
@@ -629,10 +645,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   }
 }
 
-template <int NC> using V32 = Variant<1, 1, 1, 1, NC>;     // obs <= 32,  act <= 16
-template <int NC> using V64 = Variant<2, 1, 1, 2, NC>;     // obs <= 64,  act <= 16
-template <int NC> using V128 = Variant<4, 2, 2, 4, NC>;    // obs <= 128, act <= 32
-template <int NC> using V256 = Variant<8, 2, 4, ES_V256_KTAR, NC>;   // obs <= 256, act <= 32; part of A lives in LDS
+constexpr int env_tiles(int nop, int nw) { return (nop / 16 + nw - 1) / nw > 0 ? (nop / 16 + nw - 1) / nw : 1; }
+// The smallest-observation variant leaves half of the register file free: two workgroups (two
+// individuals) share a CU and hide each other's LDS round trips and barriers (1.5x at obs 27).
+template <int NC, int NW> using V32 = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2>;   // obs <= 32,  act <= 16
+template <int NC, int NW> using V64 = Variant<2, 1, env_tiles(64, NW), 2, NC, NW>;      // obs <= 64,  act <= 16
+template <int NC, int NW> using V128 = Variant<4, 2, env_tiles(128, NW), 4, NC, NW>;    // obs <= 128, act <= 32
+template <int NC, int NW> using V256 = Variant<8, 2, env_tiles(256, NW), ES_V256_KTAR, NC, NW>;   // obs <= 256, act <= 32; part of A lives in LDS
 
 struct VariantInfo { int max_obs, max_act; const char* name; };
 static const VariantInfo kVariants[] = {
@@ -654,11 +673,14 @@ int mfma_variant_for(const es_config& c) {
 const char* mfma_variant_name(int v) { return (v >= 0 && v < 4) ? kVariants[v].name : "none"; }
 
 template <class V>
-static int launch_variant(es_ctx* ctx, const MfmaArgs& a, uint32_t grid, hipStream_t st) {
+static int launch_variant(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStream_t st) {
   const void* fn = reinterpret_cast<const void*>(rollout_mfma_kernel<V>);
   hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, V::LDS_BYTES);
   if (err != hipSuccess) return fail(ctx, ES_EHIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(err));
-  hipLaunchKernelGGL(rollout_mfma_kernel<V>, dim3(grid), dim3(256), V::LDS_BYTES, st, a);
+  // persistent grid: as many workgroups as the chip holds at once (register- and LDS-limited)
+  const int per_cu = std::min(V::OCC, std::max(1, ctx->lds_limit / V::LDS_BYTES));
+  const uint32_t grid = std::min<uint32_t>(units, (uint32_t)(std::max(1, ctx->num_cus) * per_cu));
+  hipLaunchKernelGGL(rollout_mfma_kernel<V>, dim3(grid), dim3(V::NT), V::LDS_BYTES, st, a);
   return check_launch(ctx, "es_rollout (MFMA)");
 }
 
@@ -674,16 +696,15 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_bf16 = c.noise_dtype == 1;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
-  if ((int)V256<16>::LDS_BYTES > ctx->lds_limit)
+  if ((int)V256<16, 4>::LDS_BYTES > ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");
   const uint32_t units = c.antithetic ? s.N / 2 : s.N;
-  const uint32_t grid = std::min<uint32_t>(units, (uint32_t)std::max(1, ctx->num_cus));
   const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
   switch (ctx->mfma_variant) {
-    case 0: return narrow ? launch_variant<V32<4>>(ctx, a, grid, st) : launch_variant<V32<16>>(ctx, a, grid, st);
-    case 1: return narrow ? launch_variant<V64<4>>(ctx, a, grid, st) : launch_variant<V64<16>>(ctx, a, grid, st);
-    case 2: return narrow ? launch_variant<V128<4>>(ctx, a, grid, st) : launch_variant<V128<16>>(ctx, a, grid, st);
-    case 3: return narrow ? launch_variant<V256<4>>(ctx, a, grid, st) : launch_variant<V256<16>>(ctx, a, grid, st);
+    case 0: return narrow ? launch_variant<V32<4, 4>>(ctx, a, units, st) : launch_variant<V32<16, 4>>(ctx, a, units, st);
+    case 1: return narrow ? launch_variant<V64<4, 4>>(ctx, a, units, st) : launch_variant<V64<16, 4>>(ctx, a, units, st);
+    case 2: return narrow ? launch_variant<V128<4, 4>>(ctx, a, units, st) : launch_variant<V128<16, 4>>(ctx, a, units, st);
+    case 3: return narrow ? launch_variant<V256<4, 4>>(ctx, a, units, st) : launch_variant<V256<16, 4>>(ctx, a, units, st);
     default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident variant for this shape");
   }
 }
