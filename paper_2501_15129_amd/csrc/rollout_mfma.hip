@@ -200,6 +200,33 @@ template <int COLS, bool PERTURB>
 __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p, int rows, int cols, int kbase,
                                            const float* __restrict__ src, const void* __restrict__ noise_row,
                                            bool noise_bf16, float scale, uint32_t off) {
+  if (((cols | (int)off | kbase) & 3) == 0) {
+    // four consecutive columns per thread: 16-byte parameter loads, 8/16-byte noise loads, 8-byte LDS stores
+    constexpr int C4 = COLS / 4;
+    const int total = rows_p * C4;
+#pragma unroll 4
+    for (int q = threadIdx.x; q < total; q += (int)blockDim.x) {
+      const int r = q / C4, c = (q % C4) * 4, k = kbase + c;
+      f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (r < rows && k < cols) {
+        const uint32_t idx = off + (uint32_t)r * (uint32_t)cols + (uint32_t)k;
+        v = *reinterpret_cast<const f32x4*>(src + idx);
+        if (PERTURB) {
+          f32x4 e;
+          if (noise_bf16) {
+            const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(noise_row) + idx);
+            e = f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
+                      __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
+          } else {
+            e = *reinterpret_cast<const f32x4*>(static_cast<const float*>(noise_row) + idx);
+          }
+          v = f32x4{__fmaf_rn(scale, e.x, v.x), __fmaf_rn(scale, e.y, v.y), __fmaf_rn(scale, e.z, v.z), __fmaf_rn(scale, e.w, v.w)};
+        }
+      }
+      *reinterpret_cast<u32x2*>(dst + r * pitch + c) = pack_bf16x4(v.x, v.y, v.z, v.w);
+    }
+    return;
+  }
   const int total = rows_p * COLS;
   for (int q = threadIdx.x; q < total; q += (int)blockDim.x) {
     const int r = q / COLS, k = kbase + q % COLS;
