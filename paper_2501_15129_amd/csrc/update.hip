@@ -1,6 +1,13 @@
 // es_update: search-gradient estimate g = noise^T w / (N sigma) followed by an Adam step
 // (paper App. B Table 5b: OpenES with Adam, lr 0.01, weight decay 0.005, noise std 0.02).
 //
+// Two paths, both deterministic and both streaming the noise matrix exactly once:
+//  * large matrices (two kernels): stage 1 below writes binary64 partial rows per chunk of rows,
+//    stage 2 adds them and applies Adam - the split keeps >2000 workgroups in flight, which
+//    is what the HBM needs at 0.5 GB;
+//  * small and medium matrices (one kernel): a workgroup of eight wavefronts owns its columns for
+//    ALL rows and applies Adam itself - no partials, one launch (the launch is what costs there).
+//
 // Stage 1 streams the noise matrix exactly once (HBM-bound: rows * ld * sizeof(elt) bytes,
 // ~1 flop per byte).  A workgroup owns a tile of 64*VEC consecutive columns and one chunk
 // of rows; its four wavefronts take every fourth row, each lane loads 16 bytes per row
@@ -125,9 +132,96 @@ __global__ __launch_bounds__(256) void adam_kernel(const double* __restrict__ pa
   theta[d] = (float)tn;
 }
 
+constexpr int UPD1_WAVES = 8;        // single-pass kernel: wavefronts per workgroup
+constexpr int UPD1_INFLIGHT = 8;     // ... and rows of one wavefront in flight
+constexpr uint32_t UPD_COEF_ROWS = 2048;   // row weights staged in LDS per pass
+
+struct AdamArgs {
+  double inv_scale;      // N * sigma
+  double lr, b1, b2, eps, wd, corr1, corr2;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(const void* __restrict__ noise,
+                                                                const float* __restrict__ shaped, uint32_t rows,
+                                                                uint32_t ld, uint32_t D, uint32_t antithetic,
+                                                                const AdamArgs ad, float* __restrict__ theta,
+                                                                float* __restrict__ m, float* __restrict__ v,
+                                                                float* __restrict__ grad) {
+  using NQ = NoiseVec<BF16>;
+  using Raw = typename NQ::Raw;
+  constexpr int VEC = NQ::VEC, UPD_TILE = 64 * VEC;
+  __shared__ double coef[UPD_COEF_ROWS];
+  __shared__ double red[UPD1_WAVES][UPD_TILE];
+
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t col0 = blockIdx.x * UPD_TILE;
+  const Raw* base = reinterpret_cast<const Raw*>(noise) + ((size_t)col0 / VEC + lane);
+  const size_t row_stride = ld / VEC;     // in Raw units
+
+  double acc[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) acc[k] = 0.0;
+  for (uint32_t rb = 0; rb < rows; rb += UPD_COEF_ROWS) {
+    const uint32_t rn = min(UPD_COEF_ROWS, rows - rb);
+    __syncthreads();
+    for (uint32_t r = threadIdx.x; r < rn; r += 64u * UPD1_WAVES)
+      coef[r] = antithetic ? (double)shaped[2 * (rb + r)] - (double)shaped[2 * (rb + r) + 1] : (double)shaped[rb + r];
+    __syncthreads();
+    uint32_t r = wave;
+    for (; r + UPD1_WAVES * (UPD1_INFLIGHT - 1) < rn; r += UPD1_WAVES * UPD1_INFLIGHT) {
+      Raw q[UPD1_INFLIGHT];
+#pragma unroll
+      for (int u = 0; u < UPD1_INFLIGHT; ++u)
+        q[u] = __builtin_nontemporal_load(base + (size_t)(rb + r + UPD1_WAVES * u) * row_stride);
+#pragma unroll
+      for (int u = 0; u < UPD1_INFLIGHT; ++u) {
+        float f[VEC];
+        NQ::unpack(q[u], f);
+        const double c = coef[r + UPD1_WAVES * u];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] = fma(c, (double)f[k], acc[k]);
+      }
+    }
+    for (; r < rn; r += UPD1_WAVES) {
+      const Raw q = __builtin_nontemporal_load(base + (size_t)(rb + r) * row_stride);
+      float f[VEC];
+      NQ::unpack(q, f);
+      const double c = coef[r];
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) acc[k] = fma(c, (double)f[k], acc[k]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) red[wave][lane * VEC + k] = acc[k];
+  __syncthreads();
+
+  // Adam on this workgroup's 256 parameters (columns past D are padding)
+  for (uint32_t c = threadIdx.x; c < (uint32_t)UPD_TILE; c += 64u * UPD1_WAVES) {
+    const uint32_t d = col0 + c;
+    if (d >= D) break;
+    double g = red[0][c];
+#pragma unroll
+    for (int w = 1; w < UPD1_WAVES; ++w) g += red[w][c];
+    g = g / ad.inv_scale;                              // divide by N * sigma
+    const double th = (double)theta[d];
+    const double gr = -g + ad.wd * th;
+    const double mn = ad.b1 * (double)m[d] + (1.0 - ad.b1) * gr;
+    const double vn = ad.b2 * (double)v[d] + (1.0 - ad.b2) * gr * gr;
+    const double mhat = mn / ad.corr1, vhat = vn / ad.corr2;
+    const double tn = th - ad.lr * mhat / (sqrt(vhat) + ad.eps);
+    if (grad) grad[d] = (float)g;
+    m[d] = (float)mn;
+    v[d] = (float)vn;
+    theta[d] = (float)tn;
+  }
+}
+
+
 uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16) {
   const uint32_t tile = 64u * (bf16 ? 8u : 4u);
   const uint32_t col_tiles = ld / tile;
+  if ((uint64_t)rows * ld * (bf16 ? 2u : 4u) < (256ull << 20)) return 1;     // single-pass kernel
   uint32_t chunks = (2048u + col_tiles - 1) / col_tiles;
   chunks = std::min(chunks, std::max(1u, rows / 16u));
   while ((rows + chunks - 1) / chunks > UPD_MAX_ROWS_PER_CHUNK) ++chunks;
@@ -140,6 +234,22 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
   const es_config& c = ctx->cfg;
   const bool bf16 = c.noise_dtype == 1;
   const uint32_t chunks = ctx->upd_chunks;
+  if (chunks == 1) {
+    AdamArgs ad;
+    ad.b1 = (double)c.beta1; ad.b2 = (double)c.beta2;
+    ad.corr1 = 1.0 - std::pow(ad.b1, (double)step);
+    ad.corr2 = 1.0 - std::pow(ad.b2, (double)step);
+    ad.inv_scale = (double)s.N * (double)c.sigma;
+    ad.lr = (double)c.lr; ad.eps = (double)c.adam_eps; ad.wd = (double)c.weight_decay;
+    const dim3 grid1(s.ld / (64 * (bf16 ? 8 : 4))), block1(64 * UPD1_WAVES);
+    if (bf16)
+      hipLaunchKernelGGL(update_single_pass_kernel<true>, grid1, block1, 0, st, noise, shaped, s.rows, s.ld, s.D,
+                         c.antithetic, ad, theta, m, v, grad);
+    else
+      hipLaunchKernelGGL(update_single_pass_kernel<false>, grid1, block1, 0, st, noise, shaped, s.rows, s.ld, s.D,
+                         c.antithetic, ad, theta, m, v, grad);
+    return check_launch(ctx, "es_update (single pass)");
+  }
   const uint32_t rpc = (s.rows + chunks - 1) / chunks;
   const uint32_t tile = 64u * (bf16 ? 8u : 4u);
   double* partial = static_cast<double*>(ws);
