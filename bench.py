@@ -185,7 +185,7 @@ def main() -> int:
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
-    roofline_update = {"kernel": "grad_partial_kernel+adam_kernel", "bound": "hbm", "achieved": ugbs, "peak": HBM_PEAK_GBS,
+    roofline_update = {"kernel": ctx.update_kernel, "bound": "hbm", "achieved": ugbs, "peak": HBM_PEAK_GBS,
                        "unit": "GB/s", "frac": ugbs / HBM_PEAK_GBS, "traffic": traffic.get("update_bytes_per_launch"),
                        "bytes_per_launch": ub,
                        "avg_launch_ms": upd_ms}

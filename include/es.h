@@ -81,6 +81,7 @@ size_t es_noise_ld(const es_ctx* ctx);         /* row stride of the noise matrix
 size_t es_noise_bytes(const es_ctx* ctx);      /* rows * ld * sizeof(element)                 */
 size_t es_workspace_bytes(const es_ctx* ctx);  /* scratch for es_rollout / es_update (>= 256) */
 const char* es_rollout_kernel(const es_ctx* ctx); /* name of the rollout variant chosen       */
+const char* es_update_kernel(const es_ctx* ctx);  /* name of the es_update kernel(s) chosen        */
 const char* es_strerror(int status);
 const char* es_last_error(const es_ctx* ctx);
 

@@ -49,6 +49,8 @@ def load_library() -> C.CDLL:
         getattr(lib, fn).restype = sz
     lib.es_rollout_kernel.argtypes = [vp]
     lib.es_rollout_kernel.restype = C.c_char_p
+    lib.es_update_kernel.argtypes = [vp]
+    lib.es_update_kernel.restype = C.c_char_p
     lib.es_strerror.argtypes = [C.c_int]
     lib.es_strerror.restype = C.c_char_p
     lib.es_last_error.argtypes = [vp]
@@ -104,6 +106,7 @@ class EsContext:
         self.noise_bytes = int(_lib.es_noise_bytes(h))
         self.workspace_bytes = int(_lib.es_workspace_bytes(h))
         self.rollout_kernel = _lib.es_rollout_kernel(h).decode()
+        self.update_kernel = _lib.es_update_kernel(h).decode()
         self.noise_torch_dtype = torch.bfloat16 if self.cfg.noise_dtype == 1 else torch.float32
 
     def close(self):

@@ -113,6 +113,10 @@ size_t es_noise_bytes(const es_ctx* ctx) {
 }
 size_t es_workspace_bytes(const es_ctx* ctx) { return ctx ? ctx->workspace_bytes : 0; }
 const char* es_rollout_kernel(const es_ctx* ctx) { return ctx ? ctx->kernel_name.c_str() : ""; }
+const char* es_update_kernel(const es_ctx* ctx) {
+  if (!ctx) return "";
+  return ctx->upd_chunks == 1 ? "update_single_pass_kernel" : "grad_partial_kernel+adam_kernel";
+}
 
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {
   if (!ctx) return ES_EINVAL;
