@@ -113,8 +113,8 @@ def cpu_baseline(w, budget_s=12.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="index into the five workloads (default: the largest)")
     ap.add_argument("--done-rule", action="store_true", help="time the workload with its termination rule on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -165,6 +165,7 @@ def main() -> int:
     ctx, bufs = setup(w)
     wall, stage, live = run_generations(torch, ctx, w, bufs, args.steps, args.warmup)
     mean = lambda xs: float(sum(xs) / len(xs))
+    median = lambda xs: float(sorted(xs)[len(xs) // 2]) if len(xs) % 2 else float(sum(sorted(xs)[len(xs) // 2 - 1:len(xs) // 2 + 1]) / 2)
     ms_per_step = wall * 1e3 / args.steps
     nominal = w.env_steps
     executed = live if args.done_rule else nominal     # fixed-length: every step of every episode runs
@@ -203,6 +204,7 @@ def main() -> int:
         "generations_per_s": args.steps / wall,
         "env_steps_per_generation": executed,
         "stage_ms": {k: mean(v) for k, v in stage.items()},
+        "stage_ms_median": {k: median(v) for k, v in stage.items()},
         "roofline": roofline,
         "roofline_update": roofline_update,
     }
