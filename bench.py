@@ -25,6 +25,8 @@ if str(ROOT) not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 FP32_VALU_PEAK_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+VALU_PEAK_TLANEOPS = 78.6       # the same figure as vector-lane operations per second (one FMA = one operation)
+REGEN_VALU_OPS_PER_BLOCK = 245  # vector instructions per Philox block + two Gaussian transforms + four fp64 FMAs (counted in the built kernel)
 
 
 def flop_per_env_step(w) -> int:
@@ -117,6 +119,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="index into the five workloads (default: the largest)")
     ap.add_argument("--done-rule", action="store_true", help="time the workload with its termination rule on")
+    ap.add_argument("--noise-dtype", type=int, default=None, choices=[0, 1, 2, 3],
+                    help="override the workload's noise storage: 0/1 stored binary32/bf16 matrix, 2/3 no matrix, values "
+                         "regenerated from the counter stream in es_rollout and es_update")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -147,6 +152,8 @@ def main() -> int:
                           "copies": 3}))
         return 0
     base = CONFIGS[args.config]
+    if args.noise_dtype is not None:
+        base = replace(base, noise_dtype=args.noise_dtype)
     w = base if args.done_rule else base.fixed_length()
     a_mat, b_mat, theta = make_inputs(w)
 
@@ -182,7 +189,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = measured_traffic(w.name) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
@@ -190,6 +197,12 @@ def main() -> int:
                        "unit": "GB/s", "frac": ugbs / HBM_PEAK_GBS, "traffic": traffic.get("update_bytes_per_launch"),
                        "bytes_per_launch": ub,
                        "avg_launch_ms": upd_ms}
+    if w.noise_dtype >= 2:      # no noise matrix: the update recomputes every value and is bound by the vector ALUs
+        ops = w.noise_rows * ((w.n_params + 3) // 4) * REGEN_VALU_OPS_PER_BLOCK
+        tops = ops / (upd_ms * 1e-3) / 1e12
+        roofline_update = {"kernel": ctx.update_kernel, "bound": "alu", "achieved": tops, "peak": VALU_PEAK_TLANEOPS,
+                           "unit": "T lane-op/s", "frac": tops / VALU_PEAK_TLANEOPS, "traffic": None,
+                           "lane_ops_per_launch": ops, "noise_bytes_in_hbm": 0, "avg_launch_ms": upd_ms}
 
     out = {
         "metric": "env-steps/sec (policy fwd + env step), whole OpenES generation",
@@ -200,6 +213,8 @@ def main() -> int:
                                f"{'bf16 operands / fp32 accumulate' if bf16 else 'fp32'}, "
                                f"{'termination rule on (live env-steps counted)' if args.done_rule else 'fixed-length episodes (paper Sec. 5.1 protocol)'}",
                    "population": w.pop, "envs_per_individual": w.envs, "horizon": w.horizon, "params": w.n_params,
+                   "noise": {0: "binary32 matrix", 1: "bf16 matrix", 2: "regenerated (binary32 values), no matrix",
+                             3: "regenerated (bf16-rounded values), no matrix"}[w.noise_dtype],
                    "rollout_kernel": ctx.rollout_kernel},
         "generations_per_s": args.steps / wall,
         "env_steps_per_generation": executed,

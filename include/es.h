@@ -29,6 +29,13 @@
  * type binary32 (noise_dtype 0) or bf16 bit patterns (noise_dtype 1).  Columns
  * D <= d < ld are written as zero by es_sample_population and must be zero if the caller
  * fills the matrix itself.
+ *
+ * Regenerated noise (noise_dtype 2 and 3; paper Sec. 5.1, generation on the fly taken to its
+ * end): no matrix exists.  es_noise_bytes() is 0, every noise_d argument is ignored and may
+ * be NULL, es_sample_population only records the generation (host side, no device work), and
+ * es_rollout / es_update recompute each value from the counter stream where they need it.
+ * Mode 2 uses the binary32 values (the results of noise_dtype 0), mode 3 rounds them to bf16
+ * (the results of noise_dtype 1), bit for bit.
  */
 #ifndef ES_H_
 #define ES_H_
@@ -56,7 +63,8 @@ typedef struct es_config {
                             (perturbed weights and biases, env matrices A and B, the state,
                             hidden activations and action as inputs of the next product) is
                             rounded to bf16; accumulation, tanh, reward, return are binary32 */
-  uint32_t noise_dtype;  /* 0: binary32 noise matrix ; 1: bf16 noise matrix                  */
+  uint32_t noise_dtype;  /* 0: binary32 noise matrix ; 1: bf16 noise matrix ;
+                            2 / 3: no matrix, values regenerated (binary32 / bf16-rounded)   */
   uint32_t antithetic;   /* 1: individuals 2j and 2j+1 use +eps_j and -eps_j                 */
   uint32_t out_tanh;     /* 1: tanh on the action layer as well                              */
   float sigma;           /* noise std (paper App. B Table 5b: 0.02)                          */
@@ -91,7 +99,8 @@ const char* es_last_error(const es_ctx* ctx);
  * variate (d mod 4) of the Philox4x32-10 block with counter (d / 4, j, generation, 1) and
  * key (seed low, seed high), mapped to N(0,1) by a fixed binary32 Box-Muller sequence, then
  * rounded to bf16 (nearest-even) when noise_dtype = 1.  generation < 2^32.
- * Writes rows * ld elements to noise_d.
+ * Writes rows * ld elements to noise_d.  With regenerated noise (noise_dtype 2, 3) nothing is
+ * written: the call records `generation` in the context for the next es_update.
  */
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream);
 
@@ -130,6 +139,8 @@ int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_
  * In: noise_d, shaped_d [N] f32.  In/out: theta_d, m_d, v_d [D] f32.
  * Out (optional, may be NULL): grad_d [D] f32 receives g.
  * workspace_d: es_workspace_bytes() bytes.  sigma must be > 0.
+ * With regenerated noise the values are those of the generation passed to the most recent
+ * es_sample_population call on this context (ES_EINVAL if there was none).
  */
 int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d,
               float* theta_d, float* m_d, float* v_d, float* grad_d, void* workspace_d,

@@ -108,6 +108,7 @@ class EsContext:
         self.rollout_kernel = _lib.es_rollout_kernel(h).decode()
         self.update_kernel = _lib.es_update_kernel(h).decode()
         self.noise_torch_dtype = torch.bfloat16 if self.cfg.noise_dtype == 1 else torch.float32
+        self.noise_regenerated = self.cfg.noise_dtype >= 2      # no matrix: every `noise` argument is None
 
     def close(self):
         if getattr(self, "_h", None):
@@ -123,15 +124,20 @@ class EsContext:
 
     # -- buffers (plumbing: torch owns the memory) --------------------------------
     def alloc_noise(self, device="cuda"):
+        if self.noise_regenerated:
+            return None
         return torch.empty((self.noise_rows, self.noise_ld), dtype=self.noise_torch_dtype, device=device)
 
     def alloc_workspace(self, device="cuda"):
         return torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
 
+    def _noise_ptr(self, noise, n):
+        return None if self.noise_regenerated else _ptr(noise, self.noise_torch_dtype, n, "noise")
+
     # -- the four hot calls ---------------------------------------------------------
     def sample_population(self, generation: int, noise):
         n = self.noise_rows * self.noise_ld
-        self._check(_lib.es_sample_population(self._h, generation, _ptr(noise, self.noise_torch_dtype, n, "noise"),
+        self._check(_lib.es_sample_population(self._h, generation, self._noise_ptr(noise, n),
                                               _stream()))
 
     def rollout(self, generation: int, theta, noise, a_mat, b_mat, returns, ep_len, fitness, workspace):
@@ -139,7 +145,7 @@ class EsContext:
         f32, n = torch.float32, self.noise_rows * self.noise_ld
         self._check(_lib.es_rollout(
             self._h, generation, _ptr(theta, f32, self.param_count, "theta"),
-            _ptr(noise, self.noise_torch_dtype, n, "noise"),
+            self._noise_ptr(noise, n),
             _ptr(a_mat, f32, c.obs_dim * c.obs_dim, "A"), _ptr(b_mat, f32, c.obs_dim * c.act_dim, "B"),
             _ptr(returns, f32, c.pop * c.envs_per_ind, "returns"),
             _ptr(ep_len, torch.int32, c.pop * c.envs_per_ind, "ep_len"),
@@ -155,7 +161,7 @@ class EsContext:
     def update(self, adam_step: int, noise, shaped, theta, m, v, grad, workspace):
         f32, d, n = torch.float32, self.param_count, self.noise_rows * self.noise_ld
         self._check(_lib.es_update(
-            self._h, adam_step, _ptr(noise, self.noise_torch_dtype, n, "noise"),
+            self._h, adam_step, self._noise_ptr(noise, n),
             _ptr(shaped, f32, self.cfg.pop, "shaped"), _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"),
             _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"),
             _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))

@@ -47,7 +47,8 @@ int es_create(const es_config* cfg, es_ctx** out) {
   auto bad = [&](const char* why) { g_create_error = std::string("es_create: ") + why; return (int)ES_EINVAL; };
   if (c.pop == 0 || c.envs_per_ind == 0 || c.horizon == 0) return bad("pop, envs_per_ind and horizon must be positive");
   if (c.obs_dim == 0 || c.hid_dim == 0 || c.act_dim == 0) return bad("layer widths must be positive");
-  if (c.dtype > 1 || c.noise_dtype > 1) return bad("dtype and noise_dtype must be 0 or 1");
+  if (c.dtype > 1) return bad("dtype must be 0 or 1");
+  if (c.noise_dtype > 3) return bad("noise_dtype must be 0..3");
   if (c.antithetic > 1 || c.out_tanh > 1) return bad("antithetic and out_tanh must be 0 or 1");
   if (c.antithetic && (c.pop & 1u)) return bad("pop must be even with mirrored sampling");
   if (!(c.sigma >= 0.0f) || !std::isfinite(c.sigma)) return bad("sigma must be finite and >= 0");
@@ -94,7 +95,9 @@ int es_create(const es_config* cfg, es_ctx** out) {
     ctx->rollout_kind = ROLLOUT_WAVE_LDS;
     ctx->kernel_name = c.dtype == 1 ? "rollout_wave_lds_bf16" : "rollout_wave_lds_f32";
   }
-  ctx->upd_chunks = update_chunks(s.rows, s.ld, c.noise_dtype == 1);
+  ctx->regen_generation = 0;
+  ctx->regen_valid = false;
+  ctx->upd_chunks = c.noise_dtype >= 2 ? update_chunks_regen(s.rows, s.D) : update_chunks(s.rows, s.ld, c.noise_dtype == 1);
   ctx->workspace_bytes = std::max<size_t>(256, (size_t)ctx->upd_chunks * s.ld * sizeof(double));
   *out = ctx;
   return ES_OK;
@@ -109,19 +112,26 @@ size_t es_param_count(const es_ctx* ctx) { return ctx ? ctx->shp.D : 0; }
 size_t es_noise_rows(const es_ctx* ctx) { return ctx ? ctx->shp.rows : 0; }
 size_t es_noise_ld(const es_ctx* ctx) { return ctx ? ctx->shp.ld : 0; }
 size_t es_noise_bytes(const es_ctx* ctx) {
-  return ctx ? (size_t)ctx->shp.rows * ctx->shp.ld * (ctx->cfg.noise_dtype == 1 ? 2 : 4) : 0;
+  if (!ctx || ctx->cfg.noise_dtype >= 2) return 0;       // regenerated noise is never stored
+  return (size_t)ctx->shp.rows * ctx->shp.ld * (ctx->cfg.noise_dtype == 1 ? 2 : 4);
 }
 size_t es_workspace_bytes(const es_ctx* ctx) { return ctx ? ctx->workspace_bytes : 0; }
 const char* es_rollout_kernel(const es_ctx* ctx) { return ctx ? ctx->kernel_name.c_str() : ""; }
 const char* es_update_kernel(const es_ctx* ctx) {
   if (!ctx) return "";
+  if (ctx->cfg.noise_dtype >= 2) return "grad_regen_kernel+adam_kernel";
   return ctx->upd_chunks == 1 ? "update_single_pass_kernel" : "grad_partial_kernel+adam_kernel";
 }
 
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_sample_population: generation must be < 2^32");
+  if (ctx->cfg.noise_dtype >= 2) {     // nothing to store: remember which generation es_update regenerates
+    ctx->regen_generation = (uint32_t)generation;
+    ctx->regen_valid = true;
+    return ES_OK;
+  }
+  if (!noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
   return launch_sample(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
 }
 
@@ -129,7 +139,8 @@ int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const voi
                const float* B_d, float* returns_d, int32_t* ep_len_d, float* fitness_d, void* workspace_d,
                void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!theta_d || !noise_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d)
+  if (!theta_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d ||
+      (!noise_d && ctx->cfg.noise_dtype < 2))
     return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -156,8 +167,10 @@ int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_
 int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, float* theta_d,
               float* m_d, float* v_d, float* grad_d, void* workspace_d, void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!noise_d || !shaped_d || !theta_d || !m_d || !v_d || !workspace_d)
+  if (!shaped_d || !theta_d || !m_d || !v_d || !workspace_d || (!noise_d && ctx->cfg.noise_dtype < 2))
     return fail(ctx, ES_EINVAL, "es_update: null device pointer");
+  if (ctx->cfg.noise_dtype >= 2 && !ctx->regen_valid)
+    return fail(ctx, ES_EINVAL, "es_update: with regenerated noise, es_sample_population must name the generation first");
   if (adam_step < 1) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
   if (!(ctx->cfg.sigma > 0.0f)) return fail(ctx, ES_EINVAL, "es_update: sigma must be > 0");
   return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, workspace_d,

@@ -98,6 +98,37 @@ __device__ __forceinline__ uint32_t bf16_bits(float x) {
 __device__ __forceinline__ float bf16_round(float x) { return __uint_as_float(bf16_bits(x) << 16); }
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
+// Noise values recomputed from the counter stream instead of being read back (paper Sec. 5.1:
+// perturbations generated on the fly; nothing is stored when the caller asks for that).
+// Columns d0..d0+3 (d0 a multiple of 4) of noise row `row`: one Philox block, two transforms.
+// `round` reproduces the value a bf16-stored matrix would hold.
+__device__ __forceinline__ void noise_regen4(uint32_t row, uint32_t d0, uint32_t gen, uint32_t k0, uint32_t k1,
+                                             bool round, float (&z)[4]) {
+  const Words4 w = philox4x32_10(d0 >> 2, row, gen, 1u, k0, k1);     // stream 1 = noise
+  gauss_pair(w.x, w.y, z[0], z[1]);
+  gauss_pair(w.z, w.w, z[2], z[3]);
+  if (round) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) z[k] = bf16_round(z[k]);
+  }
+}
+// A single column (one transform; used where a thread's columns are not aligned groups of four).
+__device__ __forceinline__ float noise_regen1(uint32_t row, uint32_t d, uint32_t gen, uint32_t k0, uint32_t k1, bool round) {
+  const Words4 w = philox4x32_10(d >> 2, row, gen, 1u, k0, k1);
+  const uint32_t xa = (d & 2u) ? w.z : w.x, xb = (d & 2u) ? w.w : w.y;
+  float za, zb;
+  gauss_pair(xa, xb, za, zb);
+  const float z = (d & 1u) ? zb : za;
+  return round ? bf16_round(z) : z;
+}
+// Noise element (row, d) under any of the four storage modes of es_config.noise_dtype.
+__device__ __forceinline__ float noise_value(uint32_t mode, const void* base, uint32_t ld, uint32_t row, uint32_t d,
+                                             uint32_t gen, uint32_t k0, uint32_t k1) {
+  if (mode >= 2u) return noise_regen1(row, d, gen, k0, k1, mode == 3u);
+  if (mode == 1u) return bf16_to_f32(static_cast<const uint16_t*>(base)[(size_t)row * ld + d]);
+  return static_cast<const float*>(base)[(size_t)row * ld + d];
+}
+
 // Initial state element k of environment copy e: uniform on [-0.1, 0.1).
 __device__ __forceinline__ float reset_value(uint32_t k, uint32_t e, uint32_t gen, uint32_t k0, uint32_t k1) {
   const Words4 w = philox4x32_10(k >> 2, e, gen, 2u, k0, k1);

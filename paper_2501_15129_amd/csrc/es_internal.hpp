@@ -34,6 +34,8 @@ struct es_ctx {
   int reg_variant;           // index of the register-resident binary32 kernel, or -1
   size_t lds_bytes_wave;     // dynamic LDS of the wave/LDS rollout
   uint32_t upd_chunks;       // row chunks of the update reduction
+  uint32_t regen_generation; // regenerated noise: the generation named by the last es_sample_population call
+  bool regen_valid;          // ... and whether there has been one
   size_t workspace_bytes;
   int lds_limit;             // LDS bytes per workgroup on the device seen at es_create
   int num_cus;               // compute units of that device
@@ -71,5 +73,6 @@ int mfma_variant_for(const es_config& cfg);       // -1 when no register-residen
 const char* mfma_variant_name(int variant);
 size_t wave_rollout_lds_bytes(const es_config& cfg);
 uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16);
+uint32_t update_chunks_regen(uint32_t rows, uint32_t D);
 
 }  // namespace es

@@ -39,7 +39,7 @@ struct MfmaArgs {
   uint32_t N, E, T, no, nh, na, ld;
   uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, out_tanh, noise_bf16;
+  uint32_t antithetic, out_tanh, noise_mode;
   float sigma, done_thresh, act_cost;
 };
 
@@ -193,13 +193,22 @@ __device__ __forceinline__ unsigned rows_umax(unsigned b) {
 }
 __device__ __forceinline__ unsigned abs_bits(float v) { return __builtin_bit_cast(unsigned, v) & 0x7FFFFFFFu; }
 
+// One noise row under any storage mode: a pointer to the stored row, or the counters to recompute it.
+struct NoiseRow {
+  const void* ptr;
+  uint32_t mode, row, gen, k0, k1;
+};
+__device__ __forceinline__ float row_noise(const NoiseRow& nz, uint32_t idx) {
+  if (nz.mode >= 2u) return noise_regen1(nz.row, idx, nz.gen, nz.k0, nz.k1, nz.mode == 3u);
+  return nz.mode == 1u ? bf16_to_f32(static_cast<const uint16_t*>(nz.ptr)[idx]) : static_cast<const float*>(nz.ptr)[idx];
+}
+
 // Fill dst[r * pitch + c] (bf16) for r < rows_p, c < COLS with the bf16-rounded source value of
 // matrix element (r, kbase + c) when r < rows and kbase + c < cols, and zero elsewhere.
 // PERTURB: value = fma(scale, noise[idx], theta[idx]) with idx = off + r * cols + (kbase + c).
 template <int COLS, bool PERTURB>
 __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p, int rows, int cols, int kbase,
-                                           const float* __restrict__ src, const void* __restrict__ noise_row,
-                                           bool noise_bf16, float scale, uint32_t off) {
+                                           const float* __restrict__ src, const NoiseRow nz, float scale, uint32_t off) {
   if (((cols | (int)off | kbase) & 3) == 0) {
     // four consecutive columns per thread: 16-byte parameter loads, 8/16-byte noise loads, 8-byte LDS stores
     constexpr int C4 = COLS / 4;
@@ -213,12 +222,16 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
         v = *reinterpret_cast<const f32x4*>(src + idx);
         if (PERTURB) {
           f32x4 e;
-          if (noise_bf16) {
-            const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(noise_row) + idx);
+          if (nz.mode >= 2u) {
+            float z[4];
+            noise_regen4(nz.row, idx, nz.gen, nz.k0, nz.k1, nz.mode == 3u, z);
+            e = f32x4{z[0], z[1], z[2], z[3]};
+          } else if (nz.mode == 1u) {
+            const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(nz.ptr) + idx);
             e = f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
                       __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
           } else {
-            e = *reinterpret_cast<const f32x4*>(static_cast<const float*>(noise_row) + idx);
+            e = *reinterpret_cast<const f32x4*>(static_cast<const float*>(nz.ptr) + idx);
           }
           v = f32x4{__fmaf_rn(scale, e.x, v.x), __fmaf_rn(scale, e.y, v.y), __fmaf_rn(scale, e.z, v.z), __fmaf_rn(scale, e.w, v.w)};
         }
@@ -235,9 +248,7 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
       const uint32_t idx = off + (uint32_t)r * (uint32_t)cols + (uint32_t)k;
       v = src[idx];
       if (PERTURB) {
-        const float eps = noise_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(noise_row)[idx])
-                                     : static_cast<const float*>(noise_row)[idx];
-        v = __fmaf_rn(scale, eps, v);
+        v = __fmaf_rn(scale, row_noise(nz, idx), v);
       }
     }
     dst[r * pitch + (q % COLS)] = (uint16_t)bf16_bits(v);
@@ -272,7 +283,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   bf16x8 Ar[MTE][KTAR > 0 ? KTAR : 1], Br[MTE][KTA];
 #pragma unroll
   for (int kr = 0; kr < (KTAR + KC - 1) / KC; ++kr) {
-    stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, no, 32 * KC * kr, a.A, nullptr, false, 0.0f, 0u);
+    stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, no, 32 * KC * kr, a.A, NoiseRow{}, 0.0f, 0u);
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < MTE; ++t)
@@ -284,8 +295,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   }
   if (KTAL > 0)
     stage_cols<32 * (KTAL > 0 ? KTAL : 1), false>(reinterpret_cast<uint16_t*>(lds + V::OFF_AL), PAL, V::ENV_ROWS, no, no,
-                                                    32 * KTAR, a.A, nullptr, false, 0.0f, 0u);
-  stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, na, 0, a.B, nullptr, false, 0.0f, 0u);
+                                                    32 * KTAR, a.A, NoiseRow{}, 0.0f, 0u);
+  stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, na, 0, a.B, NoiseRow{}, 0.0f, 0u);
   __syncthreads();
 #pragma unroll
   for (int t = 0; t < MTE; ++t)
@@ -303,9 +314,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
     for (uint32_t sub = 0; sub < per_unit; ++sub) {
       const uint32_t i = unit * per_unit + sub;
       const float scale = sub ? -a.sigma : a.sigma;
-      const void* nrow = a.noise_bf16
-                             ? static_cast<const void*>(static_cast<const uint16_t*>(a.noise) + (size_t)unit * a.ld)
-                             : static_cast<const void*>(static_cast<const float*>(a.noise) + (size_t)unit * a.ld);
+      NoiseRow nz;
+      nz.mode = a.noise_mode; nz.row = unit; nz.gen = a.gen; nz.k0 = a.k0; nz.k1 = a.k1;
+      nz.ptr = nullptr;           // regenerated noise has no buffer
+      if (a.noise_mode == 1u) nz.ptr = static_cast<const uint16_t*>(a.noise) + (size_t)unit * a.ld;
+      else if (a.noise_mode == 0u) nz.ptr = static_cast<const float*>(a.noise) + (size_t)unit * a.ld;
 
       // ---------------- perturbed policy weights -> registers ----------------
       bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H];
@@ -313,8 +326,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         float v1 = 0.0f, v2 = 0.0f;
         if (u < nh) {
           const uint32_t i1 = a.ob1 + u, i2 = a.ob2 + u;
-          const float e1 = a.noise_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(nrow)[i1]) : static_cast<const float*>(nrow)[i1];
-          const float e2 = a.noise_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(nrow)[i2]) : static_cast<const float*>(nrow)[i2];
+          const float e1 = row_noise(nz, i1), e2 = row_noise(nz, i2);
           v1 = bf16_round(__fmaf_rn(scale, e1, a.theta[i1]));
           v2 = bf16_round(__fmaf_rn(scale, e2, a.theta[i2]));
         }
@@ -325,17 +337,16 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         float v3 = 0.0f;
         if (c < na) {
           const uint32_t i3 = a.ob3 + c;
-          const float e3 = a.noise_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(nrow)[i3]) : static_cast<const float*>(nrow)[i3];
+          const float e3 = row_noise(nz, i3);
           v3 = bf16_round(__fmaf_rn(scale, e3, a.theta[i3]));
         }
         b3s[c] = v3;
       }
       // action-layer weights stay in LDS (read by one wavefront per tile each step)
-      stage_cols<NHP, true>(reinterpret_cast<uint16_t*>(lds + V::OFF_W3), PH, 16 * MT3, na, nh, 0, a.theta, nrow,
-                            a.noise_bf16, scale, a.oW3);
+      stage_cols<NHP, true>(reinterpret_cast<uint16_t*>(lds + V::OFF_W3), PH, 16 * MT3, na, nh, 0, a.theta, nz, scale, a.oW3);
 #pragma unroll
       for (int kr = 0; kr < (KT1 + KC - 1) / KC; ++kr) {
-        stage_cols<32 * KC, true>(stage, PW, NHP, nh, no, 32 * KC * kr, a.theta, nrow, a.noise_bf16, scale, a.oW1);
+        stage_cols<32 * KC, true>(stage, PW, NHP, nh, no, 32 * KC * kr, a.theta, nz, scale, a.oW1);
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < MT_H; ++t)
@@ -347,7 +358,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       }
 #pragma unroll
       for (int kr = 0; kr < KT_H / KC; ++kr) {
-        stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, a.theta, nrow, a.noise_bf16, scale, a.oW2);
+        stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, a.theta, nz, scale, a.oW2);
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < MT_H; ++t)
@@ -721,7 +732,7 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.ld = s.ld;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_bf16 = c.noise_dtype == 1;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   if ((int)V256<16, 4>::LDS_BYTES > ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");

@@ -27,7 +27,7 @@ struct WaveArgs {
   uint32_t N, E, T, no, nh, na, D, ld;
   uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, out_tanh, noise_bf16;
+  uint32_t antithetic, out_tanh, noise_mode;
   float sigma, done_thresh, act_cost;
 };
 
@@ -93,10 +93,7 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
   const uint32_t no = a.no, nh = a.nh, na = a.na;
 
   // ---- stage the perturbed parameters of individual i (fused perturbation) ----
-  for (uint32_t d = lane; d < a.D; d += 64u) {
-    float eps;
-    if (a.noise_bf16) eps = bf16_to_f32(static_cast<const uint16_t*>(a.noise)[(size_t)row * a.ld + d]);
-    else eps = static_cast<const float*>(a.noise)[(size_t)row * a.ld + d];
+  auto place = [&](uint32_t d, float eps) {
     float v = __fmaf_rn(scale, eps, a.theta[d]);
     if (BF16) v = bf16_round(v);
     if (d < a.ob1) { const uint32_t u = d / no, k = d - u * no; wt[L.w1 + (size_t)k * L.p_h + u] = WS::put(v); }
@@ -105,6 +102,17 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     else if (d < a.oW3) fl[L.b2 + (d - a.ob2)] = v;
     else if (d < a.ob3) { const uint32_t q = d - a.oW3, u = q / nh, k = q - u * nh; wt[L.w3 + (size_t)k * L.p_a + u] = WS::put(v); }
     else fl[L.b3 + (d - a.ob3)] = v;
+  };
+  if (a.noise_mode >= 2u) {       // regenerated noise: one counter block gives four consecutive parameters
+    for (uint32_t d0 = 4u * lane; d0 < a.D; d0 += 256u) {
+      float z[4];
+      noise_regen4(row, d0, a.gen, a.k0, a.k1, a.noise_mode == 3u, z);
+#pragma unroll
+      for (uint32_t k = 0; k < 4u; ++k)
+        if (d0 + k < a.D) place(d0 + k, z[k]);
+    }
+  } else {
+    for (uint32_t d = lane; d < a.D; d += 64u) place(d, noise_value(a.noise_mode, a.noise, a.ld, row, d, a.gen, a.k0, a.k1));
   }
   for (uint32_t q = lane; q < no * no; q += 64u) {
     const uint32_t k = q / no, j = q - k * no;
@@ -204,7 +212,7 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.D = s.D; a.ld = s.ld;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_bf16 = c.noise_dtype == 1;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const size_t lds = ctx->lds_bytes_wave;
   hipError_t err;

@@ -25,7 +25,7 @@ struct RegArgs {
   int32_t* ep_len;
   uint32_t N, E, T, ld;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, out_tanh, noise_bf16;
+  uint32_t antithetic, out_tanh, noise_mode;
   float sigma, done_thresh, act_cost;
 };
 
@@ -68,9 +68,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   const bool hid = u < NH, obs = u < NO;
 
   auto param = [&](uint32_t d) -> float {     // perturbed parameter d of individual i (binary32, one rounding)
-    const float eps = a.noise_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(a.noise)[(size_t)row * a.ld + d])
-                                   : static_cast<const float*>(a.noise)[(size_t)row * a.ld + d];
-    return __fmaf_rn(scale, eps, a.theta[d]);
+    return __fmaf_rn(scale, noise_value(a.noise_mode, a.noise, a.ld, row, d, a.gen, a.k0, a.k1), a.theta[d]);
   };
 
   // ---- this lane's weights ----
@@ -168,7 +166,7 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_bf16 = c.noise_dtype == 1;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const dim3 grid(s.N * s.E), block(64);
   switch (ctx->reg_variant) {

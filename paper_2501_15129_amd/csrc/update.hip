@@ -7,6 +7,10 @@
 //    is what the HBM needs at 0.5 GB;
 //  * small and medium matrices (one kernel): a workgroup of eight wavefronts owns its columns for
 //    ALL rows and applies Adam itself - no partials, one launch (the launch is what costs there).
+// A third path serves contexts that store no noise at all (paper Sec. 5.1: perturbations generated
+// on the fly): stage 1 recomputes every noise value from the counter stream instead of reading it -
+// bound by the integer/floating-point ALUs (one Philox block and two Gaussian transforms per four
+// values), with zero noise bytes in HBM - and stage 2 is shared.
 //
 // Stage 1 streams the noise matrix exactly once (HBM-bound: rows * ld * sizeof(elt) bytes,
 // ~1 flop per byte).  A workgroup owns a tile of 64*VEC consecutive columns and one chunk
@@ -107,6 +111,33 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
   double* out = partial + (size_t)blockIdx.y * ld + col0;
   for (uint32_t c = threadIdx.x; c < 64u * VEC; c += 256u)
     out[c] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+}
+
+// Stage 1 without a noise matrix: thread = four consecutive columns (one counter block per row),
+// workgroup = 1024 columns x one chunk of rows.
+__global__ __launch_bounds__(256) void grad_regen_kernel(const float* __restrict__ shaped, double* __restrict__ partial,
+                                                         uint32_t rows, uint32_t ld, uint32_t D,
+                                                         uint32_t rows_per_chunk, uint32_t antithetic, uint32_t round_bf16,
+                                                         uint32_t gen, uint32_t k0, uint32_t k1) {
+  __shared__ double coef[UPD_MAX_ROWS_PER_CHUNK];
+  const uint32_t r0 = blockIdx.y * rows_per_chunk;
+  const uint32_t r1 = min(rows, r0 + rows_per_chunk);
+  for (uint32_t r = r0 + threadIdx.x; r < r1; r += 256u)
+    coef[r - r0] = antithetic ? (double)shaped[2 * r] - (double)shaped[2 * r + 1] : (double)shaped[r];
+  __syncthreads();
+  const uint32_t d0 = 4u * (blockIdx.x * 256u + threadIdx.x);
+  if (d0 >= D) return;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (uint32_t r = r0; r < r1; ++r) {
+    float z[4];
+    noise_regen4(r, d0, gen, k0, k1, round_bf16 != 0u, z);
+    const double c = coef[r - r0];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = fma(c, (double)z[k], acc[k]);
+  }
+  double* out = partial + (size_t)blockIdx.y * ld + d0;       // ld is a multiple of 4: columns D..ld-1 are never read
+#pragma unroll
+  for (int k = 0; k < 4; ++k) out[k] = acc[k];
 }
 
 __global__ __launch_bounds__(256) void adam_kernel(const double* __restrict__ partial, uint32_t chunks,
@@ -218,6 +249,14 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
 }
 
 
+// Row chunks of the regenerating stage 1: enough workgroups to fill every SIMD several times over.
+uint32_t update_chunks_regen(uint32_t rows, uint32_t D) {
+  const uint32_t wgs_per_chunk = ((D + 3u) / 4u + 255u) / 256u;
+  uint32_t chunks = std::max(1u, std::min(rows, (2048u + wgs_per_chunk - 1u) / wgs_per_chunk));
+  while ((rows + chunks - 1) / chunks > UPD_MAX_ROWS_PER_CHUNK) ++chunks;
+  return chunks;
+}
+
 uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16) {
   const uint32_t tile = 64u * (bf16 ? 8u : 4u);
   const uint32_t col_tiles = ld / tile;
@@ -234,6 +273,21 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
   const es_config& c = ctx->cfg;
   const bool bf16 = c.noise_dtype == 1;
   const uint32_t chunks = ctx->upd_chunks;
+  if (c.noise_dtype >= 2) {
+    const uint32_t rpc = (s.rows + chunks - 1) / chunks;
+    double* partial = static_cast<double*>(ws);
+    const dim3 grid(((s.D + 3u) / 4u + 255u) / 256u, chunks);       // one thread per group of four columns
+    hipLaunchKernelGGL(grad_regen_kernel, grid, dim3(256), 0, st, shaped, partial, s.rows, s.ld, s.D, rpc, c.antithetic,
+                       c.noise_dtype == 3 ? 1u : 0u, ctx->regen_generation, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
+    int rc = check_launch(ctx, "es_update (regenerated gradient partials)");
+    if (rc != ES_OK) return rc;
+    const double b1 = (double)c.beta1, b2 = (double)c.beta2;
+    const double corr1 = 1.0 - std::pow(b1, (double)step), corr2 = 1.0 - std::pow(b2, (double)step);
+    hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D,
+                       (double)s.N * (double)c.sigma, (double)c.lr, b1, b2, (double)c.adam_eps,
+                       (double)c.weight_decay, corr1, corr2, theta, m, v, grad);
+    return check_launch(ctx, "es_update (adam)");
+  }
   if (chunks == 1) {
     AdamArgs ad;
     ad.b1 = (double)c.beta1; ad.b2 = (double)c.beta2;

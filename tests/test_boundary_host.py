@@ -53,9 +53,20 @@ def test_context_queries(binding):
         ctx.close()
 
 
+def test_regenerated_noise_contexts_store_nothing(binding):
+    from dataclasses import replace
+    for mode in (2, 3):
+        ctx = binding.EsContext(replace(CONFIGS[4], noise_dtype=mode))
+        assert ctx.noise_bytes == 0 and ctx.noise_regenerated and ctx.alloc_noise() is None
+        assert ctx.noise_rows == CONFIGS[4].pop // 2                  # the rows still exist, as counters
+        assert ctx.update_kernel.startswith("grad_regen_kernel")
+        assert ctx.workspace_bytes >= 8 * ctx.noise_ld                # at least one binary64 partial row
+        ctx.close()
+
+
 @pytest.mark.parametrize("bad", [
     dict(pop=7), dict(pop=0), dict(envs=0), dict(horizon=0), dict(obs=0), dict(hid=0), dict(act=0),
-    dict(dtype=2), dict(noise_dtype=3), dict(antithetic=2), dict(out_tanh=5),
+    dict(dtype=2), dict(noise_dtype=4), dict(antithetic=2), dict(out_tanh=5),
     dict(sigma=-1.0), dict(sigma=math.nan), dict(beta1=1.0), dict(beta2=-0.1), dict(adam_eps=0.0),
     dict(done_thresh=math.nan), dict(lr=math.inf),
 ])

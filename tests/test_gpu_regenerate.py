@@ -1,0 +1,155 @@
+"""Regenerated noise (noise_dtype 2 and 3): no noise matrix exists; es_rollout and es_update
+recompute every value from the counter stream.  Parity against the CPU checker, whose noise
+values do not depend on where they are kept (it is run with noise_dtype = mode & 1), plus the
+property that mode 2 / 3 reproduce the stored-matrix modes 0 / 1 bit for bit."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs, random_fitness
+from gpu_util import assert_params_close, compare_rollout, dev, run_rollout
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def es():
+    import paper_2501_15129_amd as pkg
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return pkg
+
+
+def stored(w):
+    """The same workload with its noise kept in a matrix (what the checker evaluates)."""
+    return replace(w, noise_dtype=w.noise_dtype & 1)
+
+
+ROLLOUT_CASES = [
+    Workload("regen-tiny", pop=6, envs=3, horizon=7, obs=5, hid=8, act=2, dtype=0, noise_dtype=2, seed=21),
+    Workload("regen-odd", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=2, seed=22),
+    Workload("regen-odd-noanti", pop=7, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=2, antithetic=0, seed=22),
+    Workload("regen-odd-bf16", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=1, noise_dtype=3, seed=22),
+    replace(CONFIGS[0], name="regen-cfg0", noise_dtype=2),
+    replace(CONFIGS[0], name="regen-cfg0-rounded", noise_dtype=3),
+    replace(CONFIGS[1], name="regen-cfg1-T120", noise_dtype=2, horizon=120),
+    Workload("regen-mfma32", pop=6, envs=16, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=3, seed=31),
+    Workload("regen-mfma32-f32noise", pop=4, envs=5, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=2, seed=31),
+    Workload("regen-mfma128", pop=4, envs=16, horizon=30, obs=100, hid=200, act=20, dtype=1, noise_dtype=3, seed=33),
+    Workload("regen-mfma256", pop=4, envs=4, horizon=16, obs=244, hid=256, act=17, dtype=1, noise_dtype=3, seed=34,
+             done_thresh=math.inf),
+]
+
+
+@pytest.mark.parametrize("w", ROLLOUT_CASES, ids=lambda w: w.name)
+def test_rollout_regenerated_matches_checker_and_stored_mode(es, w):
+    a_mat, b_mat, theta = make_inputs(w)
+    ws = stored(w)
+    ctx = es.EsContext(w)
+    assert ctx.noise_bytes == 0 and ctx.alloc_noise() is None
+    got = run_rollout(ctx, w, 3, theta, None, a_mat, b_mat)
+    eps = oracle.sample_population(ws, 3)
+    ref = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat)
+    probe = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat, arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
+    assert not chaotic
+    # the stored-matrix mode of the same library: identical bits
+    ctx_s = es.EsContext(ws)
+    noise = ctx_s.alloc_noise()
+    ctx_s.sample_population(3, noise)
+    twin = run_rollout(ctx_s, ws, 3, theta, noise, a_mat, b_mat)
+    for x, y, name in zip(got, twin, ("returns", "ep_len", "fitness")):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), f"{w.name}: {name} differ from the stored mode"
+
+
+UPDATE_CASES = [
+    Workload("regen-upd-small", pop=6, envs=1, horizon=1, obs=3, hid=5, act=2, dtype=0, noise_dtype=2, seed=5),
+    Workload("regen-upd-ragged", pop=34, envs=1, horizon=1, obs=13, hid=29, act=7, dtype=0, noise_dtype=2, seed=6),
+    Workload("regen-upd-noanti", pop=33, envs=1, horizon=1, obs=13, hid=29, act=7, dtype=0, noise_dtype=3, antithetic=0,
+             weight_decay=0.0, seed=7),
+    replace(CONFIGS[0], name="regen-upd-cfg0", noise_dtype=2),
+    replace(CONFIGS[2], name="regen-upd-cfg2", noise_dtype=3),
+    Workload("regen-upd-mid", pop=1024, envs=1, horizon=1, obs=27, hid=64, act=8, dtype=1, noise_dtype=3, seed=8),
+]
+
+
+@pytest.mark.parametrize("w", UPDATE_CASES, ids=lambda w: w.name)
+def test_update_regenerated_matches_checker(es, w):
+    ws = stored(w)
+    rng = np.random.default_rng(w.pop)
+    ctx = es.EsContext(w)
+    assert ctx.update_kernel.startswith("grad_regen")
+    d = w.n_params
+    theta = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    m, v = np.zeros(d, dtype=np.float32), np.zeros(d, dtype=np.float32)
+    th_d, m_d, v_d = dev(theta), dev(m), dev(v)
+    g_d = torch.empty(d, dtype=torch.float32, device="cuda")
+    wsp = ctx.alloc_workspace()
+    for k in range(1, 4):
+        gen = 10 + k
+        eps = oracle.sample_population(ws, gen)
+        _, shaped = oracle.rank(random_fitness(w.pop, seed=w.pop + k, ties=True))
+        theta, m, v, g = oracle.update(ws, k, eps, shaped, theta, m, v)
+        ctx.sample_population(gen, None)          # names the generation; nothing is stored
+        ctx.update(k, None, dev(shaped), th_d, m_d, v_d, g_d, wsp)
+        torch.cuda.synchronize()
+        for got, ref, name in ((g_d, g, "grad"), (th_d, theta, "theta"), (m_d, m, "m"), (v_d, v, "v")):
+            assert_params_close(got.cpu().numpy(), ref, f"{w.name} step {k} {name}")
+
+
+def test_update_regenerated_needs_a_generation(es):
+    w = UPDATE_CASES[0]
+    ctx = es.EsContext(w)
+    d = w.n_params
+    z = torch.zeros(d, device="cuda")
+    with pytest.raises(es.EsError):
+        ctx.update(1, None, torch.zeros(w.pop, device="cuda"), z, z.clone(), z.clone(), None, ctx.alloc_workspace())
+
+
+def test_generation_regenerated_full_size_cfg4(es):
+    """configs[4] at full size without a noise matrix: one whole generation.  The stored-matrix
+    mode of the same library (checked against the checker elsewhere) must be reproduced bit for
+    bit by the rollout; the update is compared with the checker on the full parameter vector."""
+    base = CONFIGS[4]
+    w = replace(base, name="cfg4-regen", noise_dtype=3)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    got = run_rollout(ctx, w, 1, theta, None, a_mat, b_mat)
+    ctx_s = es.EsContext(base)
+    noise = ctx_s.alloc_noise()
+    ctx_s.sample_population(1, noise)
+    twin = run_rollout(ctx_s, base, 1, theta, noise, a_mat, b_mat)
+    del noise
+    torch.cuda.empty_cache()
+    for x, y in zip(got, twin):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    # sampled mirrored pairs against the checker
+    refs, probes, subs = [], [], []
+    for j in (0, 777, base.pop // 2 - 1):
+        eps = oracle.sample_population(base, 1, rows=(j, j + 1))
+        ind = (2 * j, 2 * j + 2)
+        refs.append(oracle.rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j))
+        probes.append(oracle.rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, arith=1))
+        subs.append(tuple(x[ind[0]:ind[1]] for x in got))
+    cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
+    _, worst, _, chaotic = compare_rollout(base, cat(subs), cat(refs), w.name, cat(probes))
+    assert not chaotic
+    # update over all 132 881 parameters
+    d = w.n_params
+    rng = np.random.default_rng(44)
+    th = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    m = (rng.standard_normal(d) * 0.01).astype(np.float32)
+    v = (rng.random(d) * 1e-3).astype(np.float32)
+    _, shaped = oracle.rank(got[2])
+    want = oracle.update(base, 3, oracle.sample_population(base, 1), shaped, th, m, v)
+    th_d, m_d, v_d = dev(th), dev(m), dev(v)
+    g_d = torch.empty(d, dtype=torch.float32, device="cuda")
+    ctx.sample_population(1, None)
+    ctx.update(3, None, dev(shaped), th_d, m_d, v_d, g_d, ctx.alloc_workspace())
+    torch.cuda.synchronize()
+    for gpu, ref, name in ((th_d, want[0], "theta"), (m_d, want[1], "m"), (v_d, want[2], "v"), (g_d, want[3], "grad")):
+        assert_params_close(gpu.cpu().numpy(), ref, f"cfg4 regenerated {name}")
