@@ -177,3 +177,44 @@ def update(w, adam_step: int, noise, shaped, theta, m, v):
     lib().orc_update(C.byref(c), C.c_uint64(adam_step), _p(noise, C.c_float), _p(shaped, C.c_float),
                      _p(th, C.c_float), _p(mm, C.c_float), _p(vv, C.c_float), _p(g, C.c_float))
     return th, mm, vv, g
+
+
+def rank_ars(fitness, elites: int):
+    """ARS direction selection: ``(rank [N] i32, shaped [N] f32)`` (see ``orc_rank_ars``)."""
+    f = _f32(fitness)
+    r = np.empty(f.size, dtype=np.int32)
+    u = np.empty(f.size, dtype=np.float32)
+    lib().orc_rank_ars(C.c_uint32(f.size), C.c_uint32(elites), _p(f, C.c_float), _p(r, C.c_int32), _p(u, C.c_float))
+    return r, u
+
+
+def update_ars(w, elites: int, noise, shaped, theta):
+    """ARS step (plain SGD ascent).  Returns new ``(theta, g)``."""
+    c = config(w)
+    noise, shaped = _f32(noise), _f32(shaped)
+    assert noise.shape == (w.pop // 2, param_count(w)) and shaped.size == w.pop
+    th = np.array(theta, dtype=np.float32, copy=True)
+    g = np.empty(param_count(w), dtype=np.float32)
+    lib().orc_update_ars(C.byref(c), C.c_uint32(elites), _p(noise, C.c_float), _p(shaped, C.c_float),
+                         _p(th, C.c_float), _p(g, C.c_float))
+    return th, g
+
+
+def rank_vanilla(fitness, elites: int):
+    """VanillaES truncation selection with log-rank weights: ``(rank, shaped)``."""
+    f = _f32(fitness)
+    r = np.empty(f.size, dtype=np.int32)
+    u = np.empty(f.size, dtype=np.float32)
+    lib().orc_rank_vanilla(C.c_uint32(f.size), C.c_uint32(elites), _p(f, C.c_float), _p(r, C.c_int32), _p(u, C.c_float))
+    return r, u
+
+
+def update_vanilla(w, noise, shaped, theta):
+    """VanillaES recombination.  Returns new ``(theta, g)`` with ``g = theta_new - theta``."""
+    c = config(w)
+    noise, shaped = _f32(noise), _f32(shaped)
+    assert noise.shape == (w.pop, param_count(w)) and shaped.size == w.pop and not w.antithetic
+    th = np.array(theta, dtype=np.float32, copy=True)
+    g = np.empty(param_count(w), dtype=np.float32)
+    lib().orc_update_vanilla(C.byref(c), _p(noise, C.c_float), _p(shaped, C.c_float), _p(th, C.c_float), _p(g, C.c_float))
+    return th, g

@@ -356,6 +356,101 @@ void orc_update(const orc_config *cfg, uint64_t adam_step, const float *noise, c
   free(g);
 }
 
+/* ------------------------------------------------------------------ */
+/* Sibling evolution strategies on the same sampling and evaluation     */
+/* (paper Sec. 4.2 lists ARS and VanillaES beside OpenES; App. B        */
+/* Table 5(a): ARS, 16 elites, SGD, learning rate 0.02, noise std 0.03; */
+/* Table 5(c): VanillaES, 16 elites, noise std 0.02).  The paper        */
+/* delegates both algorithms to their publications; what is written     */
+/* here is the published update of each, on mirrored pairs for ARS and  */
+/* on independent offspring for VanillaES.                              */
+/* ------------------------------------------------------------------ */
+
+/* ARS (Mania et al. 2018): direction j = the mirrored pair (2j, 2j+1).  Directions are     */
+/* ordered by max(F+, F-) descending (ties: lower j first; the comparison is the integer     */
+/* order of the sign-folded bit patterns, as in orc_rank) and the best b are kept.           */
+/* sigma_R = population standard deviation of the 2b returns of the kept directions.         */
+/* rank[2j] = rank[2j+1] = position of direction j (0 = best);                               */
+/* shaped_i = F_i / sigma_R for members of kept directions, else 0 (all 0 if sigma_R = 0).   */
+void orc_rank_ars(uint32_t n, uint32_t b, const float *fitness, int32_t *rank, float *shaped) {
+  uint32_t R = n / 2;
+  for (uint32_t j = 0; j < R; ++j) {
+    uint32_t a0 = order_key(fitness[2 * j]), a1 = order_key(fitness[2 * j + 1]);
+    uint32_t kj = a0 > a1 ? a0 : a1;
+    int32_t pos = 0;
+    for (uint32_t l = 0; l < R; ++l) {
+      uint32_t b0 = order_key(fitness[2 * l]), b1 = order_key(fitness[2 * l + 1]);
+      uint32_t kl = b0 > b1 ? b0 : b1;
+      if (kl > kj || (kl == kj && l < j)) ++pos;
+    }
+    rank[2 * j] = rank[2 * j + 1] = pos;
+  }
+  double sum = 0.0, cnt = 0.0;
+  for (uint32_t i = 0; i < 2 * R; ++i)
+    if ((uint32_t)rank[i] < b) { sum += (double)fitness[i]; cnt += 1.0; }
+  double mean = cnt > 0.0 ? sum / cnt : 0.0, var = 0.0;
+  for (uint32_t i = 0; i < 2 * R; ++i)
+    if ((uint32_t)rank[i] < b) { double dlt = (double)fitness[i] - mean; var += dlt * dlt; }
+  double sigma_r = cnt > 0.0 ? sqrt(var / cnt) : 0.0;
+  for (uint32_t i = 0; i < 2 * R; ++i)
+    shaped[i] = ((uint32_t)rank[i] < b && sigma_r > 0.0) ? (float)((double)fitness[i] / sigma_r) : 0.0f;
+}
+
+/* theta <- theta + lr/b * sum_j (shaped_{2j} - shaped_{2j+1}) eps[j, :]   (plain SGD ascent). */
+void orc_update_ars(const orc_config *cfg, uint32_t b, const float *noise, const float *shaped,
+                    float *theta, float *grad_out) {
+  size_t D = orc_param_count(cfg);
+  uint32_t R = cfg->pop / 2;
+  double *g = (double *)calloc(D, sizeof(double));
+  for (uint32_t j = 0; j < R; ++j) {
+    double c = (double)shaped[2 * j] - (double)shaped[2 * j + 1];
+    const float *eps = noise + (size_t)j * D;
+    for (size_t d = 0; d < D; ++d) g[d] += c * (double)eps[d];
+  }
+  for (size_t d = 0; d < D; ++d) {
+    g[d] /= (double)b;
+    if (grad_out) grad_out[d] = (float)g[d];
+    theta[d] = (float)((double)theta[d] + (double)cfg->lr * g[d]);
+  }
+  free(g);
+}
+
+/* VanillaES, the canonical (mu, lambda) strategy of Chrabaszcz et al. 2018: offspring i =   */
+/* theta + sigma eps[i, :] (no mirroring); ordered by fitness descending (ties: lower i      */
+/* first); the best mu are recombined with weights w_k = (ln(mu + 1/2) - ln k) / sum_j (...) */
+/* for k = 1..mu.  rank_i = position (0 = best); shaped_i = w_{rank_i + 1} or 0.             */
+void orc_rank_vanilla(uint32_t n, uint32_t mu, const float *fitness, int32_t *rank, float *shaped) {
+  double wsum = 0.0;
+  for (uint32_t k = 1; k <= mu; ++k) wsum += log((double)mu + 0.5) - log((double)k);
+  for (uint32_t i = 0; i < n; ++i) {
+    uint32_t ki = order_key(fitness[i]);
+    int32_t pos = 0;
+    for (uint32_t l = 0; l < n; ++l) {
+      uint32_t kl = order_key(fitness[l]);
+      if (kl > ki || (kl == ki && l < i)) ++pos;
+    }
+    rank[i] = pos;
+    shaped[i] = (uint32_t)pos < mu ? (float)((log((double)mu + 0.5) - log((double)pos + 1.0)) / wsum) : 0.0f;
+  }
+}
+
+/* theta <- sum_k w_k (theta + sigma eps_(k)) = theta + sigma * sum_i shaped_i eps[i, :]. */
+void orc_update_vanilla(const orc_config *cfg, const float *noise, const float *shaped, float *theta,
+                        float *grad_out) {
+  size_t D = orc_param_count(cfg);
+  double *g = (double *)calloc(D, sizeof(double));
+  for (uint32_t i = 0; i < cfg->pop; ++i) {
+    const float *eps = noise + (size_t)i * D;
+    for (size_t d = 0; d < D; ++d) g[d] += (double)shaped[i] * (double)eps[d];
+  }
+  for (size_t d = 0; d < D; ++d) {
+    g[d] *= (double)cfg->sigma;
+    if (grad_out) grad_out[d] = (float)g[d];
+    theta[d] = (float)((double)theta[d] + g[d]);
+  }
+  free(g);
+}
+
 int orc_max_threads(void) {
 #ifdef _OPENMP
   extern int omp_get_max_threads(void);
