@@ -92,12 +92,18 @@ def cpu_baseline(w, budget_s=12.0):
     a_mat, b_mat, theta = make_inputs(w)
 
     def timed(n_ind):
-        ws = replace(w, pop=n_ind)
+        ws = replace(w, pop=n_ind, noise_dtype=w.noise_dtype & 1)     # the checker's noise values do not depend on storage
         t0 = time.perf_counter()
         eps = oracle.sample_population(ws, 0)
         ret, ln, fit, _ = oracle.rollout(ws, 0, theta, eps, a_mat, b_mat)
-        _, shaped = oracle.rank(fit)
-        oracle.update(ws, 1, eps, shaped, theta, np.zeros_like(theta), np.zeros_like(theta))
+        if ws.algorithm == 1:
+            b = max(1, min(ws.num_elites, n_ind // 2))
+            oracle.update_ars(ws, b, eps, oracle.rank_ars(fit, b)[1], theta)
+        elif ws.algorithm == 2:
+            oracle.update_vanilla(ws, eps, oracle.rank_vanilla(fit, max(1, min(ws.num_elites, n_ind)))[1], theta)
+        else:
+            _, shaped = oracle.rank(fit)
+            oracle.update(ws, 1, eps, shaped, theta, np.zeros_like(theta), np.zeros_like(theta))
         return time.perf_counter() - t0, int(ln.sum())
 
     n = min(w.pop, 2 * ((threads + 1) // 2))
@@ -122,6 +128,9 @@ def main() -> int:
     ap.add_argument("--noise-dtype", type=int, default=None, choices=[0, 1, 2, 3],
                     help="override the workload's noise storage: 0/1 stored binary32/bf16 matrix, 2/3 no matrix, values "
                          "regenerated from the counter stream in es_rollout and es_update")
+    ap.add_argument("--algorithm", choices=["openes", "ars", "vanilla"], default="openes",
+                    help="strategy of es_rank / es_update (paper Sec. 4.2); ars and vanilla keep pop/8 elites "
+                         "(the ratio of App. B Table 5) and use that table's step sizes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -154,6 +163,10 @@ def main() -> int:
     base = CONFIGS[args.config]
     if args.noise_dtype is not None:
         base = replace(base, noise_dtype=args.noise_dtype)
+    if args.algorithm == "ars":
+        base = replace(base, name=base.name + "-ars", algorithm=1, num_elites=max(1, base.pop // 8), lr=0.02, sigma=0.03)
+    elif args.algorithm == "vanilla":
+        base = replace(base, name=base.name + "-vanilla", algorithm=2, num_elites=max(1, base.pop // 8), antithetic=0)
     w = base if args.done_rule else base.fixed_length()
     a_mat, b_mat, theta = make_inputs(w)
 
@@ -189,7 +202,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None else None) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
@@ -205,7 +218,7 @@ def main() -> int:
                            "lane_ops_per_launch": ops, "noise_bytes_in_hbm": 0, "avg_launch_ms": upd_ms}
 
     out = {
-        "metric": "env-steps/sec (policy fwd + env step), whole OpenES generation",
+        "metric": "env-steps/sec (policy fwd + env step), whole %s generation" % {"openes": "OpenES", "ars": "ARS", "vanilla": "VanillaES"}[args.algorithm],
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",

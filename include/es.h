@@ -74,7 +74,23 @@ typedef struct es_config {
                             +inf = fixed-length episodes (the paper's timing protocol, Sec. 5.1) */
   float act_cost;        /* reward = 1 - |s|^2/obs_dim - act_cost |a|^2                      */
   uint64_t seed;         /* key of the counter-based noise / reset streams                   */
+  uint32_t algorithm;    /* which strategy es_rank / es_update implement (es_algorithm)      */
+  uint32_t num_elites;   /* ARS: directions kept (b); VanillaES: parents (mu); else ignored  */
 } es_config;
+
+/*
+ * The strategies of the paper's Sec. 4.2 that share this sampling and evaluation.
+ * Sampling and es_rollout are the same for all; es_rank and es_update differ:
+ *   ES_OPENES   centred ranks, Adam                                  (App. B Table 5b)
+ *   ES_ARS      the best b mirrored directions by max(F+, F-), returns divided by the standard
+ *               deviation of the 2b kept returns, plain SGD ascent   (Table 5a; Mania et al. 2018)
+ *               requires antithetic = 1, 1 <= num_elites <= pop / 2
+ *   ES_VANILLA  (mu, lambda) truncation selection with log-rank weights, recombination
+ *               theta <- sum_k w_k (theta + sigma eps_(k))           (Table 5c; Chrabaszcz et al. 2018)
+ *               requires antithetic = 0, 1 <= num_elites <= pop
+ * ES_ARS and ES_VANILLA support pop <= 8192.
+ */
+typedef enum es_algorithm { ES_OPENES = 0, ES_ARS = 1, ES_VANILLA = 2 } es_algorithm;
 
 typedef struct es_ctx es_ctx; /* opaque, host-side: validated config + kernel choice */
 
@@ -127,6 +143,12 @@ int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const voi
  * rank_i = position of individual i in ascending fitness order, ties broken by index
  * (-0 equals +0; NaNs sort by bit pattern, no error); shaped_i = rank_i / (N-1) - 1/2.
  * In: fitness_d [N] f32.  Out: rank_d [N] i32, shaped_d [N] f32.
+ * ES_ARS: rank_d[2j] = rank_d[2j+1] = position of direction j when directions are ordered by
+ *   max(F_2j, F_2j+1) descending (ties: lower j first); shaped_i = F_i / sigma_R for the members
+ *   of the best num_elites directions, 0 elsewhere (all 0 when sigma_R = 0).
+ * ES_VANILLA: rank_d[i] = position of individual i in descending fitness order (ties: lower i
+ *   first); shaped_i = (ln(mu + 1/2) - ln(rank_i + 1)) / sum_{k<=mu} (ln(mu + 1/2) - ln k) for
+ *   rank_i < mu = num_elites, 0 elsewhere.
  */
 int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_d, void* stream);
 
@@ -141,6 +163,9 @@ int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_
  * workspace_d: es_workspace_bytes() bytes.  sigma must be > 0.
  * With regenerated noise the values are those of the generation passed to the most recent
  * es_sample_population call on this context (ES_EINVAL if there was none).
+ * ES_ARS:     g = 1/b * sum_j (shaped_2j - shaped_2j+1) noise[j, :] ;  theta <- theta + lr g.
+ * ES_VANILLA: g = sigma * sum_i shaped_i noise[i, :] ;                 theta <- theta + g.
+ * For both, adam_step is ignored and m_d, v_d are neither read nor written (may be NULL).
  */
 int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d,
               float* theta_d, float* m_d, float* v_d, float* grad_d, void* workspace_d,

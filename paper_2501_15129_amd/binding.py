@@ -27,6 +27,7 @@ class EsConfig(C.Structure):
         ("adam_eps", C.c_float), ("weight_decay", C.c_float),
         ("done_thresh", C.c_float), ("act_cost", C.c_float),
         ("seed", C.c_uint64),
+        ("algorithm", C.c_uint32), ("num_elites", C.c_uint32),
     ]
 
 
@@ -71,7 +72,8 @@ def make_config(w) -> EsConfig:
                     act_dim=w.act, dtype=w.dtype, noise_dtype=w.noise_dtype, antithetic=w.antithetic,
                     out_tanh=w.out_tanh, sigma=w.sigma, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
                     adam_eps=w.adam_eps, weight_decay=w.weight_decay, done_thresh=w.done_thresh,
-                    act_cost=w.act_cost, seed=w.seed)
+                    act_cost=w.act_cost, seed=w.seed,
+                    algorithm=getattr(w, "algorithm", 0), num_elites=getattr(w, "num_elites", 0))
 
 
 def _stream() -> int:
@@ -163,7 +165,7 @@ class EsContext:
         self._check(_lib.es_update(
             self._h, adam_step, self._noise_ptr(noise, n),
             _ptr(shaped, f32, self.cfg.pop, "shaped"), _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"),
-            _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"),
+            _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"),      # m, v may be None for ARS / VanillaES
             _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
 
 

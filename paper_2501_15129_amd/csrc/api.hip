@@ -51,6 +51,12 @@ int es_create(const es_config* cfg, es_ctx** out) {
   if (c.noise_dtype > 3) return bad("noise_dtype must be 0..3");
   if (c.antithetic > 1 || c.out_tanh > 1) return bad("antithetic and out_tanh must be 0 or 1");
   if (c.antithetic && (c.pop & 1u)) return bad("pop must be even with mirrored sampling");
+  if (c.algorithm > ES_VANILLA) return bad("algorithm must be ES_OPENES, ES_ARS or ES_VANILLA");
+  if (c.algorithm == ES_ARS && (!c.antithetic || c.num_elites < 1 || c.num_elites > c.pop / 2))
+    return bad("ES_ARS needs mirrored sampling and 1 <= num_elites <= pop / 2");
+  if (c.algorithm == ES_VANILLA && (c.antithetic || c.num_elites < 1 || c.num_elites > c.pop))
+    return bad("ES_VANILLA needs antithetic = 0 and 1 <= num_elites <= pop");
+  if (c.algorithm != ES_OPENES && c.pop > 8192) return bad("ES_ARS and ES_VANILLA support pop <= 8192");
   if (!(c.sigma >= 0.0f) || !std::isfinite(c.sigma)) return bad("sigma must be finite and >= 0");
   if (std::isnan(c.done_thresh)) return bad("done_thresh is NaN");
   if (!std::isfinite(c.lr) || !std::isfinite(c.weight_decay) || !std::isfinite(c.act_cost)) return bad("non-finite hyper-parameter");
@@ -167,11 +173,12 @@ int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_
 int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, float* theta_d,
               float* m_d, float* v_d, float* grad_d, void* workspace_d, void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!shaped_d || !theta_d || !m_d || !v_d || !workspace_d || (!noise_d && ctx->cfg.noise_dtype < 2))
+  if (!shaped_d || !theta_d || !workspace_d || (!noise_d && ctx->cfg.noise_dtype < 2) ||
+      ((!m_d || !v_d) && ctx->cfg.algorithm == ES_OPENES))
     return fail(ctx, ES_EINVAL, "es_update: null device pointer");
   if (ctx->cfg.noise_dtype >= 2 && !ctx->regen_valid)
     return fail(ctx, ES_EINVAL, "es_update: with regenerated noise, es_sample_population must name the generation first");
-  if (adam_step < 1) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
+  if (adam_step < 1 && ctx->cfg.algorithm == ES_OPENES) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
   if (!(ctx->cfg.sigma > 0.0f)) return fail(ctx, ES_EINVAL, "es_update: sigma must be > 0");
   return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, workspace_d,
                        static_cast<hipStream_t>(stream));

@@ -140,37 +140,48 @@ __global__ __launch_bounds__(256) void grad_regen_kernel(const float* __restrict
   for (int k = 0; k < 4; ++k) out[k] = acc[k];
 }
 
+// The parameter step that follows the noise reduction, per strategy (paper Sec. 4.2, App. B Table 5):
+// OpenES = Adam on -g + weight_decay * theta; ARS and VanillaES = theta + step * g, no optimiser state.
+struct AdamArgs {
+  double inv_scale;      // the reduced sum is divided by this: N sigma (OpenES), b (ARS), 1 / sigma (VanillaES)
+  double lr, b1, b2, eps, wd, corr1, corr2;
+  double step;           // additive mode: lr (ARS) or 1 (VanillaES)
+  uint32_t additive;     // 0: Adam ; 1: theta += step * g
+};
+
+__device__ __forceinline__ void apply_step(const AdamArgs& ad, double sum, uint32_t d, float* __restrict__ theta,
+                                           float* __restrict__ m, float* __restrict__ v, float* __restrict__ grad) {
+  const double g = sum / ad.inv_scale;
+  const double th = (double)theta[d];
+  if (grad) grad[d] = (float)g;
+  if (ad.additive) {
+    theta[d] = (float)(th + ad.step * g);
+    return;
+  }
+  const double gr = -g + ad.wd * th;
+  const double mn = ad.b1 * (double)m[d] + (1.0 - ad.b1) * gr;
+  const double vn = ad.b2 * (double)v[d] + (1.0 - ad.b2) * gr * gr;
+  const double mhat = mn / ad.corr1, vhat = vn / ad.corr2;
+  m[d] = (float)mn;
+  v[d] = (float)vn;
+  theta[d] = (float)(th - ad.lr * mhat / (sqrt(vhat) + ad.eps));
+}
+
 __global__ __launch_bounds__(256) void adam_kernel(const double* __restrict__ partial, uint32_t chunks,
-                                                   uint32_t ld, uint32_t D, double inv_scale,
-                                                   double lr, double b1, double b2, double eps, double wd,
-                                                   double corr1, double corr2, float* __restrict__ theta,
-                                                   float* __restrict__ m, float* __restrict__ v,
-                                                   float* __restrict__ grad) {
+                                                   uint32_t ld, uint32_t D, const AdamArgs ad,
+                                                   float* __restrict__ theta, float* __restrict__ m,
+                                                   float* __restrict__ v, float* __restrict__ grad) {
   const uint32_t d = blockIdx.x * 256u + threadIdx.x;
   if (d >= D) return;
   double g = 0.0;
   for (uint32_t c = 0; c < chunks; ++c) g += partial[(size_t)c * ld + d];
-  g = g / inv_scale;                                   // divide by N * sigma
-  const double th = (double)theta[d];
-  const double gr = -g + wd * th;
-  const double mn = b1 * (double)m[d] + (1.0 - b1) * gr;
-  const double vn = b2 * (double)v[d] + (1.0 - b2) * gr * gr;
-  const double mhat = mn / corr1, vhat = vn / corr2;
-  const double tn = th - lr * mhat / (sqrt(vhat) + eps);
-  if (grad) grad[d] = (float)g;
-  m[d] = (float)mn;
-  v[d] = (float)vn;
-  theta[d] = (float)tn;
+  apply_step(ad, g, d, theta, m, v, grad);
 }
 
 constexpr int UPD1_WAVES = 8;        // single-pass kernel: wavefronts per workgroup
 constexpr int UPD1_INFLIGHT = 8;     // ... and rows of one wavefront in flight
 constexpr uint32_t UPD_COEF_ROWS = 2048;   // row weights staged in LDS per pass
 
-struct AdamArgs {
-  double inv_scale;      // N * sigma
-  double lr, b1, b2, eps, wd, corr1, corr2;
-};
 
 template <bool BF16>
 __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(const void* __restrict__ noise,
@@ -234,17 +245,7 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
     double g = red[0][c];
 #pragma unroll
     for (int w = 1; w < UPD1_WAVES; ++w) g += red[w][c];
-    g = g / ad.inv_scale;                              // divide by N * sigma
-    const double th = (double)theta[d];
-    const double gr = -g + ad.wd * th;
-    const double mn = ad.b1 * (double)m[d] + (1.0 - ad.b1) * gr;
-    const double vn = ad.b2 * (double)v[d] + (1.0 - ad.b2) * gr * gr;
-    const double mhat = mn / ad.corr1, vhat = vn / ad.corr2;
-    const double tn = th - ad.lr * mhat / (sqrt(vhat) + ad.eps);
-    if (grad) grad[d] = (float)g;
-    m[d] = (float)mn;
-    v[d] = (float)vn;
-    theta[d] = (float)tn;
+    apply_step(ad, g, d, theta, m, v, grad);
   }
 }
 
@@ -267,12 +268,29 @@ uint32_t update_chunks(uint32_t rows, uint32_t ld, bool bf16) {
   return chunks;
 }
 
+static AdamArgs step_args(const es_ctx* ctx, uint64_t step) {
+  const Shape& s = ctx->shp;
+  const es_config& c = ctx->cfg;
+  AdamArgs ad;
+  ad.b1 = (double)c.beta1; ad.b2 = (double)c.beta2;
+  ad.corr1 = 1.0 - std::pow(ad.b1, (double)step);
+  ad.corr2 = 1.0 - std::pow(ad.b2, (double)step);
+  ad.lr = (double)c.lr; ad.eps = (double)c.adam_eps; ad.wd = (double)c.weight_decay;
+  ad.additive = c.algorithm != ES_OPENES;
+  ad.step = c.algorithm == ES_ARS ? (double)c.lr : 1.0;
+  ad.inv_scale = c.algorithm == ES_ARS ? (double)c.num_elites
+               : c.algorithm == ES_VANILLA ? 1.0 / (double)c.sigma
+                                           : (double)s.N * (double)c.sigma;
+  return ad;
+}
+
 int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* shaped, float* theta,
                   float* m, float* v, float* grad, void* ws, hipStream_t st) {
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   const bool bf16 = c.noise_dtype == 1;
   const uint32_t chunks = ctx->upd_chunks;
+  const AdamArgs ad = step_args(ctx, step);
   if (c.noise_dtype >= 2) {
     const uint32_t rpc = (s.rows + chunks - 1) / chunks;
     double* partial = static_cast<double*>(ws);
@@ -281,20 +299,11 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
                        c.noise_dtype == 3 ? 1u : 0u, ctx->regen_generation, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
     int rc = check_launch(ctx, "es_update (regenerated gradient partials)");
     if (rc != ES_OK) return rc;
-    const double b1 = (double)c.beta1, b2 = (double)c.beta2;
-    const double corr1 = 1.0 - std::pow(b1, (double)step), corr2 = 1.0 - std::pow(b2, (double)step);
-    hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D,
-                       (double)s.N * (double)c.sigma, (double)c.lr, b1, b2, (double)c.adam_eps,
-                       (double)c.weight_decay, corr1, corr2, theta, m, v, grad);
-    return check_launch(ctx, "es_update (adam)");
+    hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D, ad,
+                       theta, m, v, grad);
+    return check_launch(ctx, "es_update (parameter step)");
   }
   if (chunks == 1) {
-    AdamArgs ad;
-    ad.b1 = (double)c.beta1; ad.b2 = (double)c.beta2;
-    ad.corr1 = 1.0 - std::pow(ad.b1, (double)step);
-    ad.corr2 = 1.0 - std::pow(ad.b2, (double)step);
-    ad.inv_scale = (double)s.N * (double)c.sigma;
-    ad.lr = (double)c.lr; ad.eps = (double)c.adam_eps; ad.wd = (double)c.weight_decay;
     const dim3 grid1(s.ld / (64 * (bf16 ? 8 : 4))), block1(64 * UPD1_WAVES);
     if (bf16)
       hipLaunchKernelGGL(update_single_pass_kernel<true>, grid1, block1, 0, st, noise, shaped, s.rows, s.ld, s.D,
@@ -316,12 +325,9 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
                        s.ld, rpc, c.antithetic);
   int rc = check_launch(ctx, "es_update (gradient partials)");
   if (rc != ES_OK) return rc;
-  const double b1 = (double)c.beta1, b2 = (double)c.beta2;
-  const double corr1 = 1.0 - std::pow(b1, (double)step), corr2 = 1.0 - std::pow(b2, (double)step);
-  hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D,
-                     (double)s.N * (double)c.sigma, (double)c.lr, b1, b2, (double)c.adam_eps,
-                     (double)c.weight_decay, corr1, corr2, theta, m, v, grad);
-  return check_launch(ctx, "es_update (adam)");
+  hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D, ad,
+                     theta, m, v, grad);
+  return check_launch(ctx, "es_update (parameter step)");
 }
 
 }  // namespace es

@@ -42,6 +42,8 @@ class Workload:
     act_cost: float = 0.01
     antithetic: int = 1
     out_tanh: int = 1
+    algorithm: int = 0  # 0 OpenES ; 1 ARS ; 2 VanillaES (paper Sec. 4.2)
+    num_elites: int = 0 # ARS: directions kept ; VanillaES: parents
 
     @property
     def n_params(self) -> int:
