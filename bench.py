@@ -131,6 +131,8 @@ def main() -> int:
     ap.add_argument("--algorithm", choices=["openes", "ars", "vanilla"], default="openes",
                     help="strategy of es_rank / es_update (paper Sec. 4.2); ars and vanilla keep pop/8 elites "
                          "(the ratio of App. B Table 5) and use that table's step sizes")
+    ap.add_argument("--hidden-act", choices=["tanh", "relu"], default="tanh",
+                    help="hidden-layer activation (the paper's EA experiments use ReLU MLPs, App. B)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -163,6 +165,8 @@ def main() -> int:
     base = CONFIGS[args.config]
     if args.noise_dtype is not None:
         base = replace(base, noise_dtype=args.noise_dtype)
+    if args.hidden_act == "relu":
+        base = replace(base, name=base.name + "-relu", hidden_act=1)
     if args.algorithm == "ars":
         base = replace(base, name=base.name + "-ars", algorithm=1, num_elites=max(1, base.pop // 8), lr=0.02, sigma=0.03)
     elif args.algorithm == "vanilla":
@@ -202,7 +206,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" else None) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
@@ -222,7 +226,7 @@ def main() -> int:
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs, T={w.horizon}, MLP {w.obs}-{w.hid}-{w.hid}-{w.act} tanh, "
+        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs, T={w.horizon}, MLP {w.obs}-{w.hid}-{w.hid}-{w.act} {args.hidden_act}, "
                                f"{'bf16 operands / fp32 accumulate' if bf16 else 'fp32'}, "
                                f"{'termination rule on (live env-steps counted)' if args.done_rule else 'fixed-length episodes (paper Sec. 5.1 protocol)'}",
                    "population": w.pop, "envs_per_individual": w.envs, "horizon": w.horizon, "params": w.n_params,

@@ -76,6 +76,8 @@ typedef struct es_config {
   uint64_t seed;         /* key of the counter-based noise / reset streams                   */
   uint32_t algorithm;    /* which strategy es_rank / es_update implement (es_algorithm)      */
   uint32_t num_elites;   /* ARS: directions kept (b); VanillaES: parents (mu); else ignored  */
+  uint32_t hidden_act;   /* activation of the two hidden layers: 0 tanh ; 1 ReLU (the paper's
+                            EA experiments use ReLU MLPs, App. B); the action layer follows out_tanh */
 } es_config;
 
 /*
@@ -127,7 +129,7 @@ int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* 
  * mirrored, else j = i, +):
  *     theta_i = fma(sign * sigma, noise[j, :], theta)        (binary32; bf16-rounded if dtype 1)
  *     s_0[e]  = uniform[-0.1, 0.1) from Philox counter (k / 4, e, generation, 2), the same for all i
- *     per step: h1 = tanh(W1 s + b1), h2 = tanh(W2 h1 + b2), a = tanh(W3 h2 + b3),
+ *     per step: h1 = act(W1 s + b1), h2 = act(W2 h1 + b2), a = tanh(W3 h2 + b3),   (act = tanh or ReLU)
  *               r = 1 - |s|^2/obs_dim - act_cost |a|^2,  R += r,  L += 1,
  *               s <- tanh(A s + B a),  stop after this step if max|s| > done_thresh.
  * In:  theta_d [D] f32, noise_d (layout above), A_d [obs,obs] f32, B_d [obs,act] f32 (row-major).

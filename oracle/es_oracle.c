@@ -53,6 +53,7 @@ typedef struct orc_config {
   float sigma, lr, beta1, beta2, adam_eps, weight_decay;
   float done_thresh, act_cost;
   uint64_t seed;
+  uint32_t hidden_act;   /* hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B: the EA experiments use ReLU MLPs) */
 } orc_config;
 
 enum { STREAM_NOISE = 1, STREAM_RESET = 2 };

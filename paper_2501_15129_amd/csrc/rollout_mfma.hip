@@ -137,6 +137,13 @@ __device__ __forceinline__ u32x2 pack_bf16x4(float a, float b, float c, float d)
 __device__ __forceinline__ f32x4 tanh4(f32x4 v) {
   return f32x4{tanh_fast(v.x), tanh_fast(v.y), tanh_fast(v.z), tanh_fast(v.w)};
 }
+// hidden-layer activation: tanh, or ReLU (the paper's EA experiments, App. B) - a compile-time choice,
+// so that the MFMA / vector-ALU interleaving below stays one straight-line region
+template <bool RELU>
+__device__ __forceinline__ f32x4 hidden4(f32x4 v) {
+  if (RELU) return f32x4{fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)};
+  return tanh4(v);
+}
 
 // Column compaction for passes of 4 environment copies: the MFMA result tile has 16 columns
 // of which only 0..3 are real.  Lanes of bank q (columns 4q..4q+3) fetch tile q's values of
@@ -255,7 +262,7 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
   }
 }
 
-template <class V>
+template <class V, bool RELU>
 __global__ __launch_bounds__(V::NT) __attribute__((amdgpu_waves_per_eu(V::OCC * V::NW / 4, V::OCC * V::NW / 4)))
 void rollout_mfma_kernel(const MfmaArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -485,13 +492,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               }
           }
           if (NC == 4) {
-            const f32x4 h = tanh4(compact4<MT_H>(acc));
+            const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
             if (q < MT_H)
               *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
           } else {
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
-              const f32x4 h = tanh4(acc[tt]);
+              const f32x4 h = hidden4<RELU>(acc[tt]);
               *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
             }
           }
@@ -543,13 +550,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               __builtin_amdgcn_sched_barrier(0);
             }
             if (NC == 4) {
-              const f32x4 h = tanh4(compact4<MT_H>(acc));
+              const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
               if (q < MT_H)
                 *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
             } else {
 #pragma unroll
               for (int tt = 0; tt < MT_H; ++tt) {
-                const f32x4 h = tanh4(acc[tt]);
+                const f32x4 h = hidden4<RELU>(acc[tt]);
                 *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
               }
             }
@@ -710,16 +717,20 @@ int mfma_variant_for(const es_config& c) {
 
 const char* mfma_variant_name(int v) { return (v >= 0 && v < 4) ? kVariants[v].name : "none"; }
 
-template <class V>
-static int launch_variant(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStream_t st) {
-  const void* fn = reinterpret_cast<const void*>(rollout_mfma_kernel<V>);
+template <class V, bool RELU>
+static int launch_variant_act(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStream_t st) {
+  const void* fn = reinterpret_cast<const void*>(rollout_mfma_kernel<V, RELU>);
   hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, V::LDS_BYTES);
   if (err != hipSuccess) return fail(ctx, ES_EHIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(err));
   // persistent grid: as many workgroups as the chip holds at once (register- and LDS-limited)
   const int per_cu = std::min(V::OCC, std::max(1, ctx->lds_limit / V::LDS_BYTES));
   const uint32_t grid = std::min<uint32_t>(units, (uint32_t)(std::max(1, ctx->num_cus) * per_cu));
-  hipLaunchKernelGGL(rollout_mfma_kernel<V>, dim3(grid), dim3(V::NT), V::LDS_BYTES, st, a);
+  hipLaunchKernelGGL((rollout_mfma_kernel<V, RELU>), dim3(grid), dim3(V::NT), V::LDS_BYTES, st, a);
   return check_launch(ctx, "es_rollout (MFMA)");
+}
+template <class V>
+static int launch_variant(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStream_t st) {
+  return ctx->cfg.hidden_act == 1 ? launch_variant_act<V, true>(ctx, a, units, st) : launch_variant_act<V, false>(ctx, a, units, st);
 }
 
 int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,

@@ -27,7 +27,7 @@ struct WaveArgs {
   uint32_t N, E, T, no, nh, na, D, ld;
   uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, out_tanh, noise_mode;
+  uint32_t antithetic, out_tanh, noise_mode, hidden_relu;
   float sigma, done_thresh, act_cost;
 };
 
@@ -143,14 +143,14 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     for (uint32_t u = lane; u < nh; u += 64u) {
       float acc = fl[L.b1 + u];
       for (uint32_t k = 0; k < no; ++k) acc = __fmaf_rn(WS::get(wt[L.w1 + (size_t)k * L.p_h + u]), fl[L.x + k], acc);
-      const float h = tanh_accurate(acc);
+      const float h = a.hidden_relu ? fmaxf(acc, 0.0f) : tanh_accurate(acc);
       fl[L.h1 + u] = BF16 ? bf16_round(h) : h;
     }
     __syncthreads();
     for (uint32_t u = lane; u < nh; u += 64u) {
       float acc = fl[L.b2 + u];
       for (uint32_t k = 0; k < nh; ++k) acc = __fmaf_rn(WS::get(wt[L.w2 + (size_t)k * L.p_h + u]), fl[L.h1 + k], acc);
-      const float h = tanh_accurate(acc);
+      const float h = a.hidden_relu ? fmaxf(acc, 0.0f) : tanh_accurate(acc);
       fl[L.h2 + u] = BF16 ? bf16_round(h) : h;
     }
     __syncthreads();
@@ -212,7 +212,7 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.D = s.D; a.ld = s.ld;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype; a.hidden_relu = c.hidden_act == 1;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const size_t lds = ctx->lds_bytes_wave;
   hipError_t err;

@@ -25,7 +25,7 @@ struct RegArgs {
   int32_t* ep_len;
   uint32_t N, E, T, ld;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, out_tanh, noise_mode;
+  uint32_t antithetic, out_tanh, noise_mode, hidden_relu;
   float sigma, done_thresh, act_cost;
 };
 
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
       const float sk = lane_value(s, k);
       if (k & 1) acc1 = __fmaf_rn(w1[k], sk, acc1); else acc0 = __fmaf_rn(w1[k], sk, acc0);
     }
-    const float h1 = hid ? tanh_accurate(acc0 + acc1) : 0.f;
+    const float h1 = hid ? (a.hidden_relu ? fmaxf(acc0 + acc1, 0.f) : tanh_accurate(acc0 + acc1)) : 0.f;
     // h2 = tanh(W2 h1 + b2): four chains
     float c0 = b2, c1 = 0.f, c2 = 0.f, c3 = 0.f;
 #pragma unroll
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
       if (k + 2 < NH) c2 = __fmaf_rn(w2[k + 2], lane_value(h1, k + 2), c2);
       if (k + 3 < NH) c3 = __fmaf_rn(w2[k + 3], lane_value(h1, k + 3), c3);
     }
-    const float h2 = hid ? tanh_accurate((c0 + c1) + (c2 + c3)) : 0.f;
+    const float h2 = hid ? (a.hidden_relu ? fmaxf((c0 + c1) + (c2 + c3), 0.f) : tanh_accurate((c0 + c1) + (c2 + c3))) : 0.f;
     // a = tanh(W3 h2 + b3): per-lane products, wavefront reductions, results as uniform scalars
     float act[NA];
     float aa = 0.f;
@@ -166,7 +166,7 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype; a.hidden_relu = c.hidden_act == 1;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const dim3 grid(s.N * s.E), block(64);
   switch (ctx->reg_variant) {

@@ -44,6 +44,7 @@ class Workload:
     out_tanh: int = 1
     algorithm: int = 0  # 0 OpenES ; 1 ARS ; 2 VanillaES (paper Sec. 4.2)
     num_elites: int = 0 # ARS: directions kept ; VanillaES: parents
+    hidden_act: int = 0 # hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B)
 
     @property
     def n_params(self) -> int:

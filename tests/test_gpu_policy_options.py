@@ -1,0 +1,91 @@
+"""Policy options of the paper's EA experiments (App. B): ReLU hidden layers and small [16, 16]
+networks (Sec. 5.2), on every rollout kernel, against the CPU checker."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs
+from gpu_util import compare_rollout, noise_to_device, run_rollout
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def es():
+    import paper_2501_15129_amd as pkg
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return pkg
+
+
+def _case(es, w, gen=1, expect_kernel=None):
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    if expect_kernel:
+        assert expect_kernel in ctx.rollout_kernel, ctx.rollout_kernel
+    eps = oracle.sample_population(w, gen)
+    got = run_rollout(ctx, w, gen, theta, noise_to_device(ctx, eps), a_mat, b_mat)
+    ref = oracle.rollout(w, gen, theta, eps, a_mat, b_mat)
+    probe = oracle.rollout(w, gen, theta, eps, a_mat, b_mat, arith=1)
+    flips, worst, sens, chaotic = compare_rollout(w, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
+    assert not chaotic
+    return got
+
+
+RELU_CASES = [
+    (Workload("relu-odd", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=22, hidden_act=1), "wave_lds_f32"),
+    (Workload("relu-odd-bf16", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=22, hidden_act=1), "wave_lds_bf16"),
+    (Workload("relu-linear-out", pop=6, envs=3, horizon=40, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=23, hidden_act=1, out_tanh=0), "wave_lds"),
+    (replace(CONFIGS[0], name="relu-cfg0", hidden_act=1), "wave_reg"),
+    (replace(CONFIGS[1], name="relu-cfg1-T150", hidden_act=1, horizon=150), "wave_reg"),
+    (Workload("relu-mfma32", pop=6, envs=16, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=31, hidden_act=1), "mfma"),
+    (Workload("relu-mfma32-narrow", pop=4, envs=3, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=32, hidden_act=1), "mfma"),
+    (Workload("relu-mfma64", pop=4, envs=16, horizon=30, obs=60, hid=256, act=10, dtype=1, noise_dtype=1, seed=35, hidden_act=1), "mfma"),
+    (Workload("relu-mfma128", pop=4, envs=16, horizon=30, obs=100, hid=200, act=20, dtype=1, noise_dtype=1, seed=33, hidden_act=1), "mfma"),
+    (Workload("relu-mfma256", pop=4, envs=4, horizon=16, obs=244, hid=256, act=17, dtype=1, noise_dtype=1, seed=34, hidden_act=1,
+              done_thresh=math.inf), "mfma"),
+]
+
+
+@pytest.mark.parametrize("w,kernel", RELU_CASES, ids=lambda x: x.name if isinstance(x, Workload) else x)
+def test_rollout_relu_hidden_layers(es, w, kernel):
+    _case(es, w, expect_kernel=kernel)
+
+
+@pytest.mark.parametrize("hidden_act", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_rollout_small_16_16_network(es, hidden_act, dtype):
+    """The [16, 16] policies of the paper's Sec. 5.2 comparison."""
+    w = Workload(f"net16-a{hidden_act}-d{dtype}", pop=12, envs=4, horizon=80, obs=17, hid=16, act=6, dtype=dtype,
+                 noise_dtype=dtype, seed=40 + hidden_act, hidden_act=hidden_act)
+    _case(es, w)
+
+
+@pytest.mark.parametrize("idx", [3, 4])
+def test_rollout_relu_full_size_bf16_configs(es, idx):
+    """configs[3] and [4] with ReLU hidden layers, full population, in the launch configuration of
+    `bench.py --hidden-act relu`; the checker recomputes sampled mirrored pairs."""
+    w = replace(CONFIGS[idx], name=f"cfg{idx}-relu", hidden_act=1)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    noise = ctx.alloc_noise()
+    ctx.sample_population(0, noise)
+    got = run_rollout(ctx, w, 0, theta, noise, a_mat, b_mat)
+    del noise
+    torch.cuda.empty_cache()
+    assert np.all(np.isfinite(got[0])) and np.all(got[1] >= 1) and np.all(got[1] <= w.horizon)
+    refs, probes, subs = [], [], []
+    for j in (0, 1, w.pop // 4, w.pop // 2 - 1):
+        eps = oracle.sample_population(w, 0, rows=(j, j + 1))
+        ind = (2 * j, 2 * j + 2)
+        refs.append(oracle.rollout(w, 0, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j))
+        probes.append(oracle.rollout(w, 0, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, arith=1))
+        subs.append(tuple(x[ind[0]:ind[1]] for x in got))
+    cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
+    flips, worst, sens, chaotic = compare_rollout(w, cat(subs), cat(refs), w.name, cat(probes))
+    print(f"[{w.name}] worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
+    assert not chaotic

@@ -4,6 +4,7 @@ import math
 from dataclasses import replace
 
 import numpy as np
+import pytest
 import torch
 import torch.nn.functional as F
 
@@ -25,8 +26,9 @@ def _unpack(w, theta):
 def _policy_torch(w, theta, s):
     w1, b1, w2, b2, w3, b3 = (torch.from_numpy(x) for x in _unpack(w, theta))
     x = torch.from_numpy(np.asarray(s, dtype=np.float64))
-    h1 = torch.tanh(F.linear(x, w1, b1))
-    h2 = torch.tanh(F.linear(h1, w2, b2))
+    act = torch.relu if getattr(w, "hidden_act", 0) == 1 else torch.tanh
+    h1 = act(F.linear(x, w1, b1))
+    h2 = act(F.linear(h1, w2, b2))
     a = F.linear(h2, w3, b3)
     return (torch.tanh(a) if w.out_tanh else a).numpy()
 
@@ -45,8 +47,8 @@ def test_sigma_zero_gives_identical_fitness():
 
 
 def test_one_step_return_against_library_forward():
-    for out_tanh in (1, 0):
-        w = replace(W, horizon=1, out_tanh=out_tanh)
+    for out_tanh, hidden_act in ((1, 0), (0, 0), (1, 1), (0, 1)):
+        w = replace(W, horizon=1, out_tanh=out_tanh, hidden_act=hidden_act)
         a_mat, b_mat, theta = make_inputs(w)
         eps = oracle.sample_population(w, 4)
         ret, ln, fit, _ = oracle.rollout(w, 4, theta, eps, a_mat, b_mat)
@@ -61,8 +63,9 @@ def test_one_step_return_against_library_forward():
         assert np.allclose(fit, ret.astype(np.float64).mean(axis=1), rtol=1e-6)
 
 
-def test_multi_step_against_library_forward():
-    w = replace(W, horizon=6, done_thresh=math.inf)
+@pytest.mark.parametrize("hidden_act", [0, 1])
+def test_multi_step_against_library_forward(hidden_act):
+    w = replace(W, horizon=6, done_thresh=math.inf, hidden_act=hidden_act)
     a_mat, b_mat, theta = make_inputs(w)
     eps = oracle.sample_population(w, 1)
     ret, ln, _, _ = oracle.rollout(w, 1, theta, eps, a_mat, b_mat)
@@ -144,11 +147,13 @@ def test_termination_rule_and_indexing():
         assert mar[0, e] > 0
 
 
-def test_two_individual_enumeration_pure_python():
+@pytest.mark.parametrize("hidden_act", [0, 1])
+def test_two_individual_enumeration_pure_python(hidden_act):
     """N = 2 (one mirrored pair), E = 1, T in {1, 2}: everything recomputed with scalar Python."""
+    hid = (lambda z: max(z, 0.0)) if hidden_act else math.tanh
     for horizon in (1, 2):
         w = Workload("enum", pop=2, envs=1, horizon=horizon, obs=2, hid=2, act=1, dtype=0, noise_dtype=0,
-                     seed=5, done_thresh=math.inf)
+                     seed=5, done_thresh=math.inf, hidden_act=hidden_act)
         a_mat, b_mat, theta = make_inputs(w)
         eps = oracle.sample_population(w, 0)
         ret, ln, fit, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
@@ -162,8 +167,8 @@ def test_two_individual_enumeration_pure_python():
             s = list(s_init)
             total = 0.0
             for _ in range(horizon):
-                h1 = [math.tanh(w1[u][0] * s[0] + w1[u][1] * s[1] + b1[u]) for u in range(2)]
-                h2 = [math.tanh(w2[u][0] * h1[0] + w2[u][1] * h1[1] + b2[u]) for u in range(2)]
+                h1 = [hid(w1[u][0] * s[0] + w1[u][1] * s[1] + b1[u]) for u in range(2)]
+                h2 = [hid(w2[u][0] * h1[0] + w2[u][1] * h1[1] + b2[u]) for u in range(2)]
                 act = math.tanh(w3[0] * h2[0] + w3[1] * h2[1] + b3)
                 total += 1.0 - (s[0] ** 2 + s[1] ** 2) / 2.0 - float(np.float32(0.01)) * act * act
                 s = [math.tanh(float(a_mat[k, 0]) * s[0] + float(a_mat[k, 1]) * s[1] + float(b_mat[k, 0]) * act)
@@ -172,8 +177,10 @@ def test_two_individual_enumeration_pure_python():
             assert abs(fit[i] - total) < 1e-6
 
 
-def test_bf16_mode_one_step_against_library_rounding():
-    w = replace(W, dtype=1, noise_dtype=1, horizon=2, done_thresh=math.inf)
+@pytest.mark.parametrize("hidden_act", [0, 1])
+def test_bf16_mode_one_step_against_library_rounding(hidden_act):
+    hid = (lambda z: np.maximum(z, 0.0)) if hidden_act else np.tanh
+    w = replace(W, dtype=1, noise_dtype=1, horizon=2, done_thresh=math.inf, hidden_act=hidden_act)
     a_mat, b_mat, theta = make_inputs(w)
     eps = oracle.sample_population(w, 0)
     ret, _, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
@@ -191,8 +198,8 @@ def test_bf16_mode_one_step_against_library_rounding():
             total = 0.0
             for _ in range(w.horizon):
                 x = q(s)
-                h1 = q(np.tanh(w1 @ x + b1))
-                h2 = q(np.tanh(w2 @ h1 + b2))
+                h1 = q(hid(w1 @ x + b1))
+                h2 = q(hid(w2 @ h1 + b2))
                 act = np.tanh(w3 @ h2 + b3)
                 total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
                 s = np.tanh(aq @ x + bq @ q(act))
@@ -208,3 +215,33 @@ def test_subrange_and_binary32_probe():
         assert np.array_equal(x[2:5], y)
     probe = oracle.rollout(W, 2, theta, eps, a_mat, b_mat, arith=1)
     assert np.allclose(probe[0], full[0], rtol=1e-5) and np.array_equal(probe[1], full[1])
+
+
+def test_relu_closed_forms():
+    """ReLU hidden layers (paper App. B).  (i) All-negative first-layer weights on a positive state
+    switch every hidden unit off: the action is tanh(b3) whatever W2, W3 are.  (ii) Positive
+    weights on a positive state make ReLU the identity: the action is tanh of a plain matrix chain."""
+    w = replace(W, hidden_act=1, horizon=1, sigma=0.0, pop=2, envs=2)
+    rng = np.random.default_rng(0)
+    a_mat, b_mat, _ = make_inputs(w)
+    shapes = layer_shapes(w)
+    s0 = [oracle.reset(w, 0, e).astype(np.float64) for e in range(w.envs)]
+    # make the initial state positive by flipping signs through the first layer instead: use |s0| via W1 = -|.| sign(s0)
+    for mode in ("off", "identity"):
+        parts = [np.abs(rng.standard_normal(shp)) * 0.3 for shp in shapes]
+        if mode == "off":
+            parts[1] = -np.abs(parts[1]) - 0.05         # b1 < 0 and W1 s <= 0 below
+        eps = np.zeros((w.noise_rows, w.n_params), dtype=np.float32)
+        for e in range(w.envs):
+            sgn = np.sign(s0[e])
+            p = [x.copy() for x in parts]
+            p[0] = p[0] * sgn[None, :] * (-1.0 if mode == "off" else 1.0)      # W1 s = -/+ |W1| |s|
+            theta = np.concatenate([x.ravel() for x in p]).astype(np.float32)
+            ret, _, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+            w1, b1, w2, b2, w3, b3 = _unpack(w, theta)
+            if mode == "off":
+                act = np.tanh(w3 @ np.maximum(b2, 0.0) + b3)                   # h1 = 0, h2 = relu(b2)
+            else:
+                act = np.tanh(w3 @ (w2 @ (w1 @ s0[e] + b1) + b2) + b3)          # every pre-activation is positive
+            want = 1.0 - np.dot(s0[e], s0[e]) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+            assert abs(ret[0, e] - want) < 1e-6 and abs(ret[1, e] - want) < 1e-6
