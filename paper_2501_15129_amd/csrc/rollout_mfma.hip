@@ -220,30 +220,41 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
     // four consecutive columns per thread: 16-byte parameter loads, 8/16-byte noise loads, 8-byte LDS stores
     constexpr int C4 = COLS / 4;
     const int total = rows_p * C4;
-#pragma unroll 4
-    for (int q = threadIdx.x; q < total; q += (int)blockDim.x) {
+    auto body = [&](int q, auto fetch) {
       const int r = q / C4, c = (q % C4) * 4, k = kbase + c;
       f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
       if (r < rows && k < cols) {
         const uint32_t idx = off + (uint32_t)r * (uint32_t)cols + (uint32_t)k;
         v = *reinterpret_cast<const f32x4*>(src + idx);
         if (PERTURB) {
-          f32x4 e;
-          if (nz.mode >= 2u) {
-            float z[4];
-            noise_regen4(nz.row, idx, nz.gen, nz.k0, nz.k1, nz.mode == 3u, z);
-            e = f32x4{z[0], z[1], z[2], z[3]};
-          } else if (nz.mode == 1u) {
-            const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(nz.ptr) + idx);
-            e = f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
-                      __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
-          } else {
-            e = *reinterpret_cast<const f32x4*>(static_cast<const float*>(nz.ptr) + idx);
-          }
+          const f32x4 e = fetch(idx);
           v = f32x4{__fmaf_rn(scale, e.x, v.x), __fmaf_rn(scale, e.y, v.y), __fmaf_rn(scale, e.z, v.z), __fmaf_rn(scale, e.w, v.w)};
         }
       }
       *reinterpret_cast<u32x2*>(dst + r * pitch + c) = pack_bf16x4(v.x, v.y, v.z, v.w);
+    };
+    // one loop per storage mode, chosen outside it (the mode is uniform); the regenerating loop is not
+    // unrolled: its body is two hundred instructions, and the staging code should stay in the instruction cache
+    if (PERTURB && nz.mode >= 2u) {
+#pragma unroll 1
+      for (int q = threadIdx.x; q < total; q += (int)blockDim.x)
+        body(q, [&](uint32_t idx) {
+          float z[4];
+          noise_regen4(nz.row, idx, nz.gen, nz.k0, nz.k1, nz.mode == 3u, z);
+          return f32x4{z[0], z[1], z[2], z[3]};
+        });
+    } else if (PERTURB && nz.mode == 1u) {
+#pragma unroll 4
+      for (int q = threadIdx.x; q < total; q += (int)blockDim.x)
+        body(q, [&](uint32_t idx) {
+          const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(nz.ptr) + idx);
+          return f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
+                       __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
+        });
+    } else {
+#pragma unroll 4
+      for (int q = threadIdx.x; q < total; q += (int)blockDim.x)
+        body(q, [&](uint32_t idx) { return PERTURB ? *reinterpret_cast<const f32x4*>(static_cast<const float*>(nz.ptr) + idx) : f32x4{0.f, 0.f, 0.f, 0.f}; });
     }
     return;
   }
