@@ -135,9 +135,12 @@ def reset(w, gen: int, e: int) -> np.ndarray:
     return out
 
 
-def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: int = 0, noise_row0: int = 0):
+def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: int = 0, noise_row0: int = 0,
+            obs_norm=None):
     """Evaluate individuals ``(i0, i1)`` (default all).  ``noise`` holds the dense rows from
     ``noise_row0`` on (the full matrix by default); it must cover the rows of these individuals.
+
+    ``obs_norm = (mean [obs], inv_std [obs])``: frozen observation statistics for the policy's input.
 
     Returns ``(returns [n,E] f32, ep_len [n,E] i32, fitness [n] f32, margin [n,E] f32)``.
     """
@@ -152,10 +155,17 @@ def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: in
     ln = np.empty((n, w.envs), dtype=np.int32)
     fit = np.empty(n, dtype=np.float32)
     mar = np.empty((n, w.envs), dtype=np.float32)
-    lib().orc_rollout(C.byref(c), C.c_uint64(gen), _p(theta, C.c_float), _p(noise, C.c_float),
-                      C.c_uint32(noise_row0), _p(a_mat, C.c_float), _p(b_mat, C.c_float), C.c_uint32(i0), C.c_uint32(i1),
-                      C.c_int(arith), _p(ret, C.c_float), _p(ln, C.c_int32), _p(fit, C.c_float),
-                      _p(mar, C.c_float))
+    null = C.POINTER(C.c_float)()
+    mean = inv = None
+    if obs_norm is not None:
+        mean, inv = _f32(obs_norm[0]), _f32(obs_norm[1])
+        assert mean.shape == (w.obs,) and inv.shape == (w.obs,)
+    lib().orc_rollout_norm(C.byref(c), C.c_uint64(gen), _p(theta, C.c_float), _p(noise, C.c_float),
+                           C.c_uint32(noise_row0), _p(a_mat, C.c_float), _p(b_mat, C.c_float),
+                           null if mean is None else _p(mean, C.c_float), null if inv is None else _p(inv, C.c_float),
+                           C.c_uint32(i0), C.c_uint32(i1),
+                           C.c_int(arith), _p(ret, C.c_float), _p(ln, C.c_int32), _p(fit, C.c_float),
+                           _p(mar, C.c_float))
     return ret, ln, fit, mar
 
 

@@ -255,10 +255,13 @@ static double q_operand(const orc_config *cfg, double x) {
  *   (how close the termination test came to flipping; +inf when the rule is off).
  * noise holds the rows from noise_row0 on (dense, D per row): row r of the matrix is at
  * noise + (r - noise_row0) * D.
- * arith = 0: binary64 (the reference); 1: binary32 (sensitivity probe). */
-void orc_rollout(const orc_config *cfg, uint64_t gen, const float *theta, const float *noise,
-                 uint32_t noise_row0, const float *A, const float *B, uint32_t i0, uint32_t i1, int arith,
-                 float *returns, int32_t *ep_len, float *fitness, float *margin) {
+ * arith = 0: binary64 (the reference); 1: binary32 (sensitivity probe).
+ * obs_mean, obs_inv_std [obs] (both or neither): frozen observation statistics; the policy's input is
+ * (s - mean) * inv_std (paper App. B), reward, termination and environment use the raw state. */
+void orc_rollout_norm(const orc_config *cfg, uint64_t gen, const float *theta, const float *noise,
+                      uint32_t noise_row0, const float *A, const float *B, const float *obs_mean,
+                      const float *obs_inv_std, uint32_t i0, uint32_t i1, int arith,
+                      float *returns, int32_t *ep_len, float *fitness, float *margin) {
   size_t D = orc_param_count(cfg);
   uint32_t E = cfg->envs, no = cfg->obs, na = cfg->act;
   /* environment matrices as the rollout sees them */
@@ -277,8 +280,8 @@ void orc_rollout(const orc_config *cfg, uint64_t gen, const float *theta, const 
       double ret, mar;
       int32_t len;
       orc_reset(cfg, gen, e, s0);
-      if (arith == 0) rollout_pair_f64(cfg, theta_i, Ae, Be, s0, &ret, &len, &mar);
-      else rollout_pair_f32(cfg, theta_i, Ae, Be, s0, &ret, &len, &mar);
+      if (arith == 0) rollout_pair_f64(cfg, theta_i, Ae, Be, obs_mean, obs_inv_std, s0, &ret, &len, &mar);
+      else rollout_pair_f32(cfg, theta_i, Ae, Be, obs_mean, obs_inv_std, s0, &ret, &len, &mar);
       size_t o = (size_t)(i - i0) * E + e;
       returns[o] = (float)ret;
       ep_len[o] = len;
@@ -291,6 +294,13 @@ void orc_rollout(const orc_config *cfg, uint64_t gen, const float *theta, const 
   }
   free(Ae);
   free(Be);
+}
+
+/* Without observation statistics (obs_mean = obs_inv_std = NULL in orc_rollout_norm: the policy sees the raw state). */
+void orc_rollout(const orc_config *cfg, uint64_t gen, const float *theta, const float *noise,
+                 uint32_t noise_row0, const float *A, const float *B, uint32_t i0, uint32_t i1, int arith,
+                 float *returns, int32_t *ep_len, float *fitness, float *margin) {
+  orc_rollout_norm(cfg, gen, theta, noise, noise_row0, A, B, NULL, NULL, i0, i1, arith, returns, ep_len, fitness, margin);
 }
 
 /* ------------------------------------------------------------------ */

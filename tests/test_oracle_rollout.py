@@ -245,3 +245,77 @@ def test_relu_closed_forms():
                 act = np.tanh(w3 @ (w2 @ (w1 @ s0[e] + b1) + b2) + b3)          # every pre-activation is positive
             want = 1.0 - np.dot(s0[e], s0[e]) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
             assert abs(ret[0, e] - want) < 1e-6 and abs(ret[1, e] - want) < 1e-6
+
+
+# ---- frozen observation normalisation (paper App. B: virtual batch normalisation, statistics kept fixed) ----
+def _stats(w, seed=9):
+    rng = np.random.default_rng(seed)
+    mean = (rng.standard_normal(w.obs) * 0.05).astype(np.float32)
+    inv = (1.0 / (0.05 + rng.random(w.obs) * 0.3)).astype(np.float32)
+    return mean, inv
+
+
+@pytest.mark.parametrize("hidden_act", [0, 1])
+def test_obs_norm_multi_step_against_library_forward(hidden_act):
+    """The policy sees (s - mean) * inv_std; reward, termination and the environment see the raw state."""
+    w = replace(W, horizon=5, done_thresh=math.inf, hidden_act=hidden_act)
+    a_mat, b_mat, theta = make_inputs(w)
+    mean, inv = _stats(w)
+    eps = oracle.sample_population(w, 1)
+    ret, ln, _, _ = oracle.rollout(w, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
+    plain, _, _, _ = oracle.rollout(w, 1, theta, eps, a_mat, b_mat)
+    assert np.max(np.abs(ret - plain)) > 1e-3                     # the statistics do matter
+    a64, b64 = a_mat.astype(np.float64), b_mat.astype(np.float64)
+    for i in (0, 3):
+        th = oracle.perturb(w, theta, eps, i)
+        for e in range(w.envs):
+            s = oracle.reset(w, 1, e).astype(np.float64)
+            total = 0.0
+            for _ in range(w.horizon):
+                act = _policy_torch(w, th, (s - mean.astype(np.float64)) * inv.astype(np.float64))
+                total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+                s = np.tanh(a64 @ s + b64 @ act)
+            assert abs(ret[i, e] - total) < 1e-5 and ln[i, e] == w.horizon
+
+
+def test_obs_norm_identity_statistics_change_nothing():
+    a_mat, b_mat, theta = make_inputs(W)
+    eps = oracle.sample_population(W, 0)
+    plain = oracle.rollout(W, 0, theta, eps, a_mat, b_mat)
+    same = oracle.rollout(W, 0, theta, eps, a_mat, b_mat, obs_norm=(np.zeros(W.obs, np.float32), np.ones(W.obs, np.float32)))
+    for x, y in zip(plain, same):
+        assert np.array_equal(x, y)
+
+
+def test_obs_norm_equals_affine_change_of_the_first_layer():
+    """W1 ((s - mean) inv) + b1 = (W1 diag(inv)) s + (b1 - W1 diag(inv) mean): a normalised policy is an
+    un-normalised one with a folded first layer (an identity of the mathematics, not of the code)."""
+    w = replace(W, sigma=0.0, horizon=6, done_thresh=math.inf)
+    a_mat, b_mat, theta = make_inputs(w)
+    theta = (theta + np.random.default_rng(3).standard_normal(theta.size) * 0.05).astype(np.float32)   # non-zero biases
+    mean, inv = _stats(w, seed=4)
+    eps = np.zeros((w.noise_rows, w.n_params), dtype=np.float32)
+    normed, _, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
+    w1, b1 = (x.copy() for x in _unpack(w, theta)[:2])
+    w1f = w1 * inv.astype(np.float64)[None, :]
+    b1f = b1 - w1f @ mean.astype(np.float64)
+    folded = theta.astype(np.float64).copy()
+    folded[:w1.size] = w1f.ravel()
+    folded[w1.size:w1.size + b1.size] = b1f
+    plain, _, _, _ = oracle.rollout(w, 0, folded.astype(np.float32), eps, a_mat, b_mat)
+    assert np.allclose(normed, plain, rtol=0, atol=2e-5)          # the folded parameters are rounded to binary32
+    assert np.max(np.abs(normed - oracle.rollout(w, 0, theta, eps, a_mat, b_mat)[0])) > 1e-3
+
+
+def test_obs_norm_zero_scale_blinds_the_policy():
+    """inv_std = 0: the policy's input is 0 whatever the state, so the action is the same at every step."""
+    w = replace(W, sigma=0.0, horizon=1, pop=2)
+    a_mat, b_mat, theta = make_inputs(w)
+    theta = (theta + np.random.default_rng(5).standard_normal(theta.size) * 0.05).astype(np.float32)
+    eps = np.zeros((w.noise_rows, w.n_params), dtype=np.float32)
+    ret, _, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat, obs_norm=(np.zeros(w.obs, np.float32), np.zeros(w.obs, np.float32)))
+    act = _policy_torch(w, theta, np.zeros(w.obs))
+    for e in range(w.envs):
+        s0 = oracle.reset(w, 0, e).astype(np.float64)
+        want = 1.0 - np.dot(s0, s0) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+        assert abs(ret[0, e] - want) < 1e-6
