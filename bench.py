@@ -82,7 +82,7 @@ def run_generations(torch, ctx, w, bufs, steps, warmup, gen0=0):
     return wall, stage, live
 
 
-def cpu_baseline(w, budget_s=12.0):
+def cpu_baseline(w, budget_s=12.0, obs_norm=None):
     """The CPU checker, as it stands, on a bounded sample of the same workload (host cores of this machine)."""
     import numpy as np
     import oracle
@@ -95,7 +95,7 @@ def cpu_baseline(w, budget_s=12.0):
         ws = replace(w, pop=n_ind, noise_dtype=w.noise_dtype & 1)     # the checker's noise values do not depend on storage
         t0 = time.perf_counter()
         eps = oracle.sample_population(ws, 0)
-        ret, ln, fit, _ = oracle.rollout(ws, 0, theta, eps, a_mat, b_mat)
+        ret, ln, fit, _ = oracle.rollout(ws, 0, theta, eps, a_mat, b_mat, obs_norm=obs_norm)
         if ws.algorithm == 1:
             b = max(1, min(ws.num_elites, n_ind // 2))
             oracle.update_ars(ws, b, eps, oracle.rank_ars(fit, b)[1], theta)
@@ -133,6 +133,8 @@ def main() -> int:
                          "(the ratio of App. B Table 5) and use that table's step sizes")
     ap.add_argument("--hidden-act", choices=["tanh", "relu"], default="tanh",
                     help="hidden-layer activation (the paper's EA experiments use ReLU MLPs, App. B)")
+    ap.add_argument("--obs-norm", action="store_true",
+                    help="frozen observation statistics for the policy input (paper App. B); synthetic: mean N(0, 0.05^2), std U[0.33, 1]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -174,10 +176,18 @@ def main() -> int:
     w = base if args.done_rule else base.fixed_length()
     a_mat, b_mat, theta = make_inputs(w)
 
+    obs_stats = None
+    if args.obs_norm:
+        rng = np.random.default_rng([base.seed, 77])
+        obs_stats = ((rng.standard_normal(base.obs) * 0.05).astype(np.float32),
+                     (1.0 / (0.33 + rng.random(base.obs) * 0.67)).astype(np.float32))
+
     def setup(wl):
         ctx = EsContext(wl)
         d = ctx.param_count
         dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        if obs_stats is not None:
+            ctx.set_obs_norm(dev(obs_stats[0]), dev(obs_stats[1]))
         bufs = dict(noise=ctx.alloc_noise(), ws=ctx.alloc_workspace(), theta=dev(theta), A=dev(a_mat), B=dev(b_mat),
                     m=torch.zeros(d, device="cuda"), v=torch.zeros(d, device="cuda"),
                     ret=torch.empty((wl.pop, wl.envs), device="cuda"),
@@ -206,7 +216,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" else None) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
@@ -232,7 +242,7 @@ def main() -> int:
                    "population": w.pop, "envs_per_individual": w.envs, "horizon": w.horizon, "params": w.n_params,
                    "noise": {0: "binary32 matrix", 1: "bf16 matrix", 2: "regenerated (binary32 values), no matrix",
                              3: "regenerated (bf16-rounded values), no matrix"}[w.noise_dtype],
-                   "rollout_kernel": ctx.rollout_kernel},
+                   "obs_norm": bool(args.obs_norm), "rollout_kernel": ctx.rollout_kernel},
         "generations_per_s": args.steps / wall,
         "env_steps_per_generation": executed,
         "stage_ms": {k: mean(v) for k, v in stage.items()},
@@ -250,7 +260,7 @@ def main() -> int:
                                         "stage_ms": {k: mean(v) for k, v in stage2.items()}}
         del ctx2, bufs2
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, obs_norm=obs_stats)
         out["cpu_baseline"]["host_cpus_visible"] = os.cpu_count()
     print(json.dumps(out))
     return 0

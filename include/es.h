@@ -112,6 +112,18 @@ const char* es_strerror(int status);
 const char* es_last_error(const es_ctx* ctx);
 
 /*
+ * Frozen observation normalisation (paper App. B: virtual batch normalisation - mean and
+ * standard deviation of the observations computed once from random timesteps and kept fixed
+ * for the whole run).  With statistics set, the policy of every later es_rollout sees
+ * (s - mean) * inv_std, computed in binary32 (and rounded to bf16 as a matrix operand when
+ * dtype = 1); reward, termination test and the environment keep the raw state.
+ * mean_d, inv_std_d: [obs_dim] f32 device arrays owned by the caller; they are read by
+ * es_rollout, not copied, and must stay valid until replaced.  Both NULL (the default)
+ * switches normalisation off; exactly one NULL is ES_EINVAL.  Host-side only: no device work.
+ */
+int es_set_obs_norm(es_ctx* ctx, const float* mean_d, const float* inv_std_d);
+
+/*
  * Noise of generation `generation` (paper Sec. 5.1: perturbations are generated on the fly
  * each generation, not read from a pre-built table).  noise[j, d] for j < rows, d < D is
  * variate (d mod 4) of the Philox4x32-10 block with counter (d / 4, j, generation, 1) and

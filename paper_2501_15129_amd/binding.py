@@ -56,6 +56,7 @@ def load_library() -> C.CDLL:
     lib.es_strerror.restype = C.c_char_p
     lib.es_last_error.argtypes = [vp]
     lib.es_last_error.restype = C.c_char_p
+    lib.es_set_obs_norm.argtypes = [vp, vp, vp]
     lib.es_sample_population.argtypes = [vp, u64, vp, vp]
     lib.es_rollout.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.es_rank.argtypes = [vp, vp, vp, vp, vp]
@@ -136,6 +137,13 @@ class EsContext:
 
     def _noise_ptr(self, noise, n):
         return None if self.noise_regenerated else _ptr(noise, self.noise_torch_dtype, n, "noise")
+
+    def set_obs_norm(self, mean, inv_std):
+        """Frozen observation statistics ([obs] float32 device tensors, kept alive here), or ``None, None``."""
+        n = self.cfg.obs_dim
+        self._obs_norm = (mean, inv_std)
+        self._check(_lib.es_set_obs_norm(self._h, _ptr(mean, torch.float32, n, "mean"),
+                                         _ptr(inv_std, torch.float32, n, "inv_std")))
 
     # -- the four hot calls ---------------------------------------------------------
     def sample_population(self, generation: int, noise):

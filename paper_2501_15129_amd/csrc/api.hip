@@ -102,6 +102,8 @@ int es_create(const es_config* cfg, es_ctx** out) {
     ctx->rollout_kind = ROLLOUT_WAVE_LDS;
     ctx->kernel_name = c.dtype == 1 ? "rollout_wave_lds_bf16" : "rollout_wave_lds_f32";
   }
+  ctx->obs_mean = nullptr;
+  ctx->obs_inv_std = nullptr;
   ctx->regen_generation = 0;
   ctx->regen_valid = false;
   ctx->upd_chunks = c.noise_dtype >= 2 ? update_chunks_regen(s.rows, s.D) : update_chunks(s.rows, s.ld, c.noise_dtype == 1);
@@ -128,6 +130,15 @@ const char* es_update_kernel(const es_ctx* ctx) {
   if (!ctx) return "";
   if (ctx->cfg.noise_dtype >= 2) return "grad_regen_kernel+adam_kernel";
   return ctx->upd_chunks == 1 ? "update_single_pass_kernel" : "grad_partial_kernel+adam_kernel";
+}
+
+int es_set_obs_norm(es_ctx* ctx, const float* mean_d, const float* inv_std_d) {
+  if (!ctx) return ES_EINVAL;
+  if ((mean_d == nullptr) != (inv_std_d == nullptr))
+    return fail(ctx, ES_EINVAL, "es_set_obs_norm: mean_d and inv_std_d must both be set or both be null");
+  ctx->obs_mean = mean_d;
+  ctx->obs_inv_std = inv_std_d;
+  return ES_OK;
 }
 
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {

@@ -36,6 +36,8 @@ struct es_ctx {
   uint32_t upd_chunks;       // row chunks of the update reduction
   uint32_t regen_generation; // regenerated noise: the generation named by the last es_sample_population call
   bool regen_valid;          // ... and whether there has been one
+  const float* obs_mean;     // frozen observation statistics (device pointers of the caller), or null
+  const float* obs_inv_std;
   size_t workspace_bytes;
   int lds_limit;             // LDS bytes per workgroup on the device seen at es_create
   int num_cus;               // compute units of that device

@@ -33,6 +33,8 @@ struct MfmaArgs {
   const void* noise;
   const float* A;
   const float* B;
+  const float* obs_mean;     // frozen observation statistics (paper App. B), or null
+  const float* obs_inv;
   float* returns;
   int32_t* ep_len;
   float* fitness;
@@ -96,7 +98,13 @@ struct Variant {
   static constexpr int OFF_B3 = OFF_B2 + 4 * NHP;
   static constexpr int OFF_X0 = OFF_B3 + 4 * 16 * MT3;
   static constexpr int OFF_SS0 = OFF_X0 + 2 * NC * PX;
-  static constexpr int LDS_BYTES = OFF_SS0 + 4 * 16;
+  // only used with observation statistics: the normalised state (the policy's operand), its cached
+  // initial value, and the statistics themselves
+  static constexpr int OFF_XP = OFF_SS0 + 4 * 16;
+  static constexpr int OFF_X0P = OFF_XP + 2 * NC * PX;
+  static constexpr int OFF_MU = OFF_X0P + 2 * NC * PX;
+  static constexpr int OFF_IV = OFF_MU + 4 * NOP;
+  static constexpr int LDS_BYTES = OFF_IV + 4 * NOP;
   static_assert(ENV_ROWS >= NOP, "the wavefronts must cover the padded state");
   static_assert(ENV_ROWS <= 256, "staging window rows");
   static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
@@ -273,7 +281,7 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
   }
 }
 
-template <class V, bool RELU>
+template <class V, bool RELU, bool NORM>
 __global__ __launch_bounds__(V::NT) __attribute__((amdgpu_waves_per_eu(V::OCC * V::NW / 4, V::OCC * V::NW / 4)))
 void rollout_mfma_kernel(const MfmaArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -294,8 +302,17 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   float* b3s = reinterpret_cast<float*>(lds + V::OFF_B3);
   uint16_t* x0s = reinterpret_cast<uint16_t*>(lds + V::OFF_X0);
   float* ss0s = reinterpret_cast<float*>(lds + V::OFF_SS0);
+  uint16_t* x0ps = reinterpret_cast<uint16_t*>(lds + V::OFF_X0P);
+  float* mus = reinterpret_cast<float*>(lds + V::OFF_MU);
+  float* ivs = reinterpret_cast<float*>(lds + V::OFF_IV);
   const int no = (int)a.no, nh = (int)a.nh, na = (int)a.na;
 
+  if (NORM) {     // padded rows get scale 0: their normalised value stays 0
+    for (int k = tid; k < V::NOP; k += NT) {
+      mus[k] = k < no ? a.obs_mean[k] : 0.0f;
+      ivs[k] = k < no ? a.obs_inv[k] : 0.0f;
+    }
+  }
   // ---------------- environment matrices -> registers / LDS (once per workgroup) ----------------
   constexpr int KTAR = V::KTAR, KTAL = V::KTAL, PAL = V::PAL;
   bf16x8 Ar[MTE][KTAR > 0 ? KTAR : 1], Br[MTE][KTA];
@@ -400,6 +417,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             if (k < no && e0 < a.E) v = reset_value((uint32_t)k, e0, a.gen, a.k0, a.k1);
             part = __fmaf_rn(v, v, part);
             x0s[n0 * PX + k] = (uint16_t)bf16_bits(v);
+            if (NORM) x0ps[n0 * PX + k] = (uint16_t)bf16_bits((v - mus[k]) * ivs[k]);
           }
           float* scratch = reinterpret_cast<float*>(lds + V::OFF_SCR);   // KG x NC partial norms
           scratch[kq * NC + n0] = part;
@@ -417,6 +435,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           const uint32_t* src = reinterpret_cast<const uint32_t*>(x0s);
           uint32_t* dst = reinterpret_cast<uint32_t*>(lds + V::OFF_X);
           for (int r = tid; r < NC * PX / 2; r += NT) dst[r] = src[r];
+          if (NORM) {
+            const uint32_t* srcp = reinterpret_cast<const uint32_t*>(x0ps);
+            uint32_t* dstp = reinterpret_cast<uint32_t*>(lds + V::OFF_XP);
+            for (int r = tid; r < NC * PX / 2; r += NT) dstp[r] = srcp[r];
+          }
           uint32_t* qz = reinterpret_cast<uint32_t*>(lds + V::OFF_QA);
           for (int r = tid; r < NW * NC * PA / 2; r += NT) qz[r] = 0u;
         }
@@ -457,16 +480,27 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           // W1 stream: the B operand (state tiles) runs two stages ahead of the MFMAs
           bf16x8 bx[KA1 > 0 ? KA1 : 1], bxr[3];     // tiles < KA1 are kept for A x below; the rest pass through a ring
           auto xload = [&](int kt) { return lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * kt + 8 * g)); };
+          // with observation statistics the policy reads the normalised state and A x the raw one
+          auto xfetch = [&](int kt) {
+            if (NORM) {
+              bxr[kt % 3] = lds_tile(lds, V::OFF_XP + 2 * (col * PX + 32 * kt + 8 * g));
+              if (kt < KA1) bx[kt < KA1 ? kt : 0] = xload(kt);
+            } else if (kt < KA1) {
+              bx[kt < KA1 ? kt : 0] = xload(kt);
+            } else {
+              bxr[kt % 3] = xload(kt);
+            }
+          };
 #pragma unroll
-          for (int kt = 0; kt < 2 && kt < KT1; ++kt) { if (kt < KA1) bx[kt] = xload(kt); else bxr[kt % 3] = xload(kt); }
+          for (int kt = 0; kt < 2 && kt < KT1; ++kt) xfetch(kt);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int kt = 0; kt < KT1; ++kt) {
-            if (kt + 2 < KT1) { if (kt + 2 < KA1) bx[kt + 2] = xload(kt + 2); else bxr[(kt + 2) % 3] = xload(kt + 2); }
+            if (kt + 2 < KT1) xfetch(kt + 2);
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
               if (V::OCC == 1) pin_agpr(W1r[tt][kt]);    // with two workgroups per CU only the 256x256 layer fits the accumulation half
-              acc[tt] = mfma16(W1r[tt][kt], kt < KA1 ? bx[kt < KA1 ? kt : 0] : bxr[kt % 3], acc[tt]);
+              acc[tt] = mfma16(W1r[tt][kt], (!NORM && kt < KA1) ? bx[kt < KA1 ? kt : 0] : bxr[kt % 3], acc[tt]);
             }
             __builtin_amdgcn_sched_barrier(0);
           }
@@ -652,6 +686,10 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               ssp = __fmaf_rn(sn.y, sn.y, ssp); ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
               mxp = umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w)));
               *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
+              if (NORM) {
+                const f32x4 xn = (sn - *reinterpret_cast<const f32x4*>(mus + 16 * tile + 4 * g)) * *reinterpret_cast<const f32x4*>(ivs + 16 * tile + 4 * g);
+                *reinterpret_cast<u32x2*>(lds + V::OFF_XP + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(xn.x, xn.y, xn.z, xn.w);
+              }
             }
             ssp = row_bank_sum(ssp);
             mxp = row_bank_umax(mxp);
@@ -671,6 +709,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
                 ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
                 mxp = umax(mxp, umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w))));
                 *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (n * PX + 16 * (w * MTE + tt) + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
+                if (NORM) {
+                  const int r0 = 16 * (w * MTE + tt) + 4 * g;
+                  const f32x4 xn = (sn - *reinterpret_cast<const f32x4*>(mus + r0)) * *reinterpret_cast<const f32x4*>(ivs + r0);
+                  *reinterpret_cast<u32x2*>(lds + V::OFF_XP + 2 * (n * PX + r0)) = pack_bf16x4(xn.x, xn.y, xn.z, xn.w);
+                }
               }
             }
           }
@@ -728,20 +771,22 @@ int mfma_variant_for(const es_config& c) {
 
 const char* mfma_variant_name(int v) { return (v >= 0 && v < 4) ? kVariants[v].name : "none"; }
 
-template <class V, bool RELU>
+template <class V, bool RELU, bool NORM>
 static int launch_variant_act(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStream_t st) {
-  const void* fn = reinterpret_cast<const void*>(rollout_mfma_kernel<V, RELU>);
+  const void* fn = reinterpret_cast<const void*>(rollout_mfma_kernel<V, RELU, NORM>);
   hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, V::LDS_BYTES);
   if (err != hipSuccess) return fail(ctx, ES_EHIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(err));
   // persistent grid: as many workgroups as the chip holds at once (register- and LDS-limited)
   const int per_cu = std::min(V::OCC, std::max(1, ctx->lds_limit / V::LDS_BYTES));
   const uint32_t grid = std::min<uint32_t>(units, (uint32_t)(std::max(1, ctx->num_cus) * per_cu));
-  hipLaunchKernelGGL((rollout_mfma_kernel<V, RELU>), dim3(grid), dim3(V::NT), V::LDS_BYTES, st, a);
+  hipLaunchKernelGGL((rollout_mfma_kernel<V, RELU, NORM>), dim3(grid), dim3(V::NT), V::LDS_BYTES, st, a);
   return check_launch(ctx, "es_rollout (MFMA)");
 }
 template <class V>
 static int launch_variant(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStream_t st) {
-  return ctx->cfg.hidden_act == 1 ? launch_variant_act<V, true>(ctx, a, units, st) : launch_variant_act<V, false>(ctx, a, units, st);
+  const bool relu = ctx->cfg.hidden_act == 1, norm = ctx->obs_mean != nullptr;
+  if (relu) return norm ? launch_variant_act<V, true, true>(ctx, a, units, st) : launch_variant_act<V, true, false>(ctx, a, units, st);
+  return norm ? launch_variant_act<V, false, true>(ctx, a, units, st) : launch_variant_act<V, false, false>(ctx, a, units, st);
 }
 
 int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,
@@ -750,7 +795,7 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   MfmaArgs a;
-  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.returns = returns; a.ep_len = ep_len; a.fitness = fitness;
+  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len; a.fitness = fitness;
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.ld = s.ld;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);

@@ -22,6 +22,8 @@ struct WaveArgs {
   const void* noise;
   const float* A;
   const float* B;
+  const float* obs_mean;     // frozen observation statistics, or null
+  const float* obs_inv;
   float* returns;
   int32_t* ep_len;
   uint32_t N, E, T, no, nh, na, D, ld;
@@ -52,7 +54,7 @@ __host__ __device__ inline uint32_t odd_pitch(uint32_t n) { return n | 1u; }
 struct WaveLayout {
   uint32_t p_h, p_a, p_o;                   // pitches
   size_t w1, w2, w3, at, bt, wcount;        // matrix offsets (weight elements)
-  size_t b1, b2, b3, s, x, h1, h2, a, qa, fcount;   // float offsets
+  size_t b1, b2, b3, s, x, xp, mu, iv, h1, h2, a, qa, fcount;   // float offsets
 };
 __host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint32_t na) {
   WaveLayout L;
@@ -66,7 +68,7 @@ __host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint
   L.wcount = (o + 1) & ~(size_t)1;
   size_t f = 0;
   L.b1 = f; f += nh; L.b2 = f; f += nh; L.b3 = f; f += na;
-  L.s = f; f += no; L.x = f; f += no; L.h1 = f; f += nh; L.h2 = f; f += nh;
+  L.s = f; f += no; L.x = f; f += no; L.xp = f; f += no; L.mu = f; f += no; L.iv = f; f += no; L.h1 = f; f += nh; L.h2 = f; f += nh;
   L.a = f; f += na; L.qa = f; f += na;
   L.fcount = f;
   return L;
@@ -126,7 +128,11 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     if (BF16) v = bf16_round(v);
     wt[L.bt + (size_t)c * L.p_o + k] = WS::put(v);
   }
-  for (uint32_t k = lane; k < no; k += 64u) fl[L.s + k] = reset_value(k, e, a.gen, a.k0, a.k1);
+  for (uint32_t k = lane; k < no; k += 64u) {
+    fl[L.s + k] = reset_value(k, e, a.gen, a.k0, a.k1);
+    fl[L.mu + k] = a.obs_mean ? a.obs_mean[k] : 0.0f;        // identity statistics when none are set
+    fl[L.iv + k] = a.obs_mean ? a.obs_inv[k] : 1.0f;
+  }
   __syncthreads();
 
   float R = 0.0f;
@@ -138,11 +144,13 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
       const float sv = fl[L.s + k];
       ss = __fmaf_rn(sv, sv, ss);
       fl[L.x + k] = BF16 ? bf16_round(sv) : sv;
+      const float pv = (sv - fl[L.mu + k]) * fl[L.iv + k];   // the policy's input (paper App. B: fixed statistics)
+      fl[L.xp + k] = BF16 ? bf16_round(pv) : pv;
     }
     __syncthreads();
     for (uint32_t u = lane; u < nh; u += 64u) {
       float acc = fl[L.b1 + u];
-      for (uint32_t k = 0; k < no; ++k) acc = __fmaf_rn(WS::get(wt[L.w1 + (size_t)k * L.p_h + u]), fl[L.x + k], acc);
+      for (uint32_t k = 0; k < no; ++k) acc = __fmaf_rn(WS::get(wt[L.w1 + (size_t)k * L.p_h + u]), fl[L.xp + k], acc);
       const float h = a.hidden_relu ? fmaxf(acc, 0.0f) : tanh_accurate(acc);
       fl[L.h1 + u] = BF16 ? bf16_round(h) : h;
     }
@@ -208,7 +216,7 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   WaveArgs a;
-  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.returns = returns; a.ep_len = ep_len;
+  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.D = s.D; a.ld = s.ld;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);

@@ -21,6 +21,8 @@ struct RegArgs {
   const void* noise;
   const float* A;
   const float* B;
+  const float* obs_mean;     // frozen observation statistics, or null
+  const float* obs_inv;
   float* returns;
   int32_t* ep_len;
   uint32_t N, E, T, ld;
@@ -87,6 +89,9 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
 #pragma unroll
   for (int c = 0; c < NA; ++c) br[c] = obs ? a.B[u * NA + c] : 0.f;
 
+  // frozen observation statistics of lane k's state element (identity when none are set: (s - 0) * 1 = s exactly)
+  const float mu = (obs && a.obs_mean) ? a.obs_mean[u] : 0.f;
+  const float iv = (obs && a.obs_mean) ? a.obs_inv[u] : 1.f;
   float s = obs ? reset_value((uint32_t)u, e, a.gen, a.k0, a.k1) : 0.f;     // lane k holds s[k]
   float R = 0.f;
   int32_t len = 0;
@@ -94,10 +99,11 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
 
   for (uint32_t t = 0; t < a.T; ++t) {
     // h1 = tanh(W1 s + b1): two accumulation chains
+    const float xp = (s - mu) * iv;      // the policy's input (paper App. B: fixed normalisation statistics)
     float acc0 = b1, acc1 = 0.f;
 #pragma unroll
     for (int k = 0; k < NO; ++k) {
-      const float sk = lane_value(s, k);
+      const float sk = lane_value(xp, k);
       if (k & 1) acc1 = __fmaf_rn(w1[k], sk, acc1); else acc0 = __fmaf_rn(w1[k], sk, acc0);
     }
     const float h1 = hid ? (a.hidden_relu ? fmaxf(acc0 + acc1, 0.f) : tanh_accurate(acc0 + acc1)) : 0.f;
@@ -163,7 +169,7 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   RegArgs a;
-  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.returns = returns; a.ep_len = ep_len;
+  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype; a.hidden_relu = c.hidden_act == 1;

@@ -89,3 +89,60 @@ def test_rollout_relu_full_size_bf16_configs(es, idx):
     flips, worst, sens, chaotic = compare_rollout(w, cat(subs), cat(refs), w.name, cat(probes))
     print(f"[{w.name}] worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
     assert not chaotic
+
+
+# ---- frozen observation normalisation (paper App. B) ----
+def _stats(w, seed=9):
+    rng = np.random.default_rng(seed)
+    mean = (rng.standard_normal(w.obs) * 0.05).astype(np.float32)
+    inv = (1.0 / (0.33 + rng.random(w.obs) * 0.67)).astype(np.float32)      # standard deviations of 0.33 .. 1
+    return mean, inv
+
+
+NORM_CASES = [
+    Workload("norm-odd", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=22),
+    Workload("norm-odd-bf16", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=22),
+    replace(CONFIGS[0], name="norm-cfg0"),
+    replace(CONFIGS[1], name="norm-cfg1-T40-relu", horizon=40, hidden_act=1),
+    Workload("norm-mfma32", pop=6, envs=16, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=31),
+    Workload("norm-mfma32-narrow-relu", pop=4, envs=3, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=32, hidden_act=1),
+    Workload("norm-mfma64", pop=4, envs=16, horizon=30, obs=60, hid=256, act=10, dtype=1, noise_dtype=1, seed=35),
+    Workload("norm-mfma128", pop=4, envs=16, horizon=30, obs=100, hid=200, act=20, dtype=1, noise_dtype=1, seed=33),
+    Workload("norm-mfma256", pop=4, envs=4, horizon=16, obs=244, hid=256, act=17, dtype=1, noise_dtype=1, seed=34, done_thresh=math.inf),
+    Workload("norm-mfma256-wide-regen", pop=4, envs=16, horizon=16, obs=244, hid=256, act=17, dtype=1, noise_dtype=3, seed=36,
+             done_thresh=math.inf),
+]
+
+
+@pytest.mark.parametrize("w", NORM_CASES, ids=lambda w: w.name)
+def test_rollout_with_observation_statistics(es, w):
+    from gpu_util import dev
+    ws = replace(w, noise_dtype=w.noise_dtype & 1)
+    a_mat, b_mat, theta = make_inputs(w)
+    mean, inv = _stats(w)
+    ctx = es.EsContext(w)
+    eps = oracle.sample_population(ws, 1)
+    noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
+    plain = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
+    ctx.set_obs_norm(dev(mean), dev(inv))
+    got = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
+    ref = oracle.rollout(ws, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
+    probe = oracle.rollout(ws, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
+    assert not chaotic
+    assert np.max(np.abs(got[0] - plain[0])) > 1e-3                     # the statistics were used
+    # identity statistics and switching off both give back the plain result, bit for bit
+    ctx.set_obs_norm(dev(np.zeros(w.obs, np.float32)), dev(np.ones(w.obs, np.float32)))
+    ident = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
+    ctx.set_obs_norm(None, None)
+    off = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
+    for x, y, z in zip(plain, ident, off):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32)) and np.array_equal(x.view(np.uint32), z.view(np.uint32))
+
+
+def test_obs_norm_needs_both_arrays(es):
+    from gpu_util import dev
+    ctx = es.EsContext(CONFIGS[0])
+    with pytest.raises(es.EsError):
+        ctx.set_obs_norm(dev(np.zeros(CONFIGS[0].obs, np.float32)), None)
