@@ -153,8 +153,9 @@ __device__ __forceinline__ float tanh_accurate(float x) {
   return ax < 0.3f ? small : big;
 }
 
-// tanh for values that are rounded to bf16 right afterwards (relative error ~1e-6 for
-// |x| > 1e-2, absolute ~1e-7 below): 1 - 2/(2^{c x} + 1), two transcendental issues.
+// tanh as 1 - 2/(2^{c x} + 1), two transcendental issues: absolute error ~1e-7 everywhere (relative
+// ~1e-6 for |x| > 1e-2; near zero the result has the absolute accuracy of 1 - (1 - 2x), which is
+// what the sums it feeds need).  Used by the register-resident kernels, binary32 and bf16.
 __device__ __forceinline__ float tanh_fast(float x) {
   const float ex = __builtin_amdgcn_exp2f(x * 2.88539008f);     // 2 log2(e)
   const float r = __builtin_amdgcn_rcpf(ex + 1.0f);

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
       const float sk = lane_value(xp, k);
       if (k & 1) acc1 = __fmaf_rn(w1[k], sk, acc1); else acc0 = __fmaf_rn(w1[k], sk, acc0);
     }
-    const float h1 = hid ? (a.hidden_relu ? fmaxf(acc0 + acc1, 0.f) : tanh_accurate(acc0 + acc1)) : 0.f;
+    const float h1 = hid ? (a.hidden_relu ? fmaxf(acc0 + acc1, 0.f) : tanh_fast(acc0 + acc1)) : 0.f;
     // h2 = tanh(W2 h1 + b2): four chains
     float c0 = b2, c1 = 0.f, c2 = 0.f, c3 = 0.f;
 #pragma unroll
@@ -116,14 +116,22 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
       if (k + 2 < NH) c2 = __fmaf_rn(w2[k + 2], lane_value(h1, k + 2), c2);
       if (k + 3 < NH) c3 = __fmaf_rn(w2[k + 3], lane_value(h1, k + 3), c3);
     }
-    const float h2 = hid ? (a.hidden_relu ? fmaxf((c0 + c1) + (c2 + c3), 0.f) : tanh_accurate((c0 + c1) + (c2 + c3))) : 0.f;
+    const float h2 = hid ? (a.hidden_relu ? fmaxf((c0 + c1) + (c2 + c3), 0.f) : tanh_fast((c0 + c1) + (c2 + c3))) : 0.f;
     // a = tanh(W3 h2 + b3): per-lane products, wavefront reductions, results as uniform scalars
+    // the NA totals are gathered into lanes 0..NA-1 (lane c also holds b3[c]) so that one tanh serves all of them
+    float pv = 0.f;
+#pragma unroll
+    for (int c = 0; c < NA; ++c) {
+      const float tot = wave_total(w3[c] * h2);
+      pv = (u == c) ? tot : pv;
+    }
+    pv = pv + b3;
+    const float tv = a.out_tanh ? tanh_fast(pv) : pv;
     float act[NA];
     float aa = 0.f;
 #pragma unroll
     for (int c = 0; c < NA; ++c) {
-      const float pre = wave_total(w3[c] * h2) + lane_value(b3, c);
-      act[c] = a.out_tanh ? tanh_accurate(pre) : pre;
+      act[c] = lane_value(tv, c);
       aa = __fmaf_rn(act[c], act[c], aa);
     }
     // reward from the pre-step state
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     }
 #pragma unroll
     for (int c = 0; c < NA; ++c) e0 = __fmaf_rn(br[c], act[c], e0);
-    s = obs ? tanh_accurate(e0 + e1) : 0.f;
+    s = obs ? tanh_fast(e0 + e1) : 0.f;
     const float mx = wave_total_max(fabsf(s));
     if (mx > a.done_thresh) break;       // uniform: mx is a scalar
   }
