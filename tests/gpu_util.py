@@ -5,7 +5,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-# Tolerances (the benchmark spec): episode returns within 1e-4 relative in fp32 and 2e-2 in bf16;
+# Target tolerances: episode returns within 1e-4 relative in fp32 and 2e-2 in bf16;
 # updated parameters within 1e-5 relative (+1e-7 absolute for parameters near zero).
 RET_RTOL = {0: 1e-4, 1: 2e-2}
 # |max|s| - done_thresh| below this at any executed step marks an episode whose termination

@@ -20,7 +20,7 @@ def es():
     return pkg
 
 
-class GpuRun:
+class GpuChain:
     def __init__(self, es, w, theta, a_mat, b_mat):
         self.w, self.ctx = w, es.EsContext(w)
         d = self.ctx.param_count
@@ -50,7 +50,7 @@ class GpuRun:
                                         noise_dtype=1, seed=7)], ids=lambda w: w.name)
 def test_three_generations_chained(es, w):
     a_mat, b_mat, theta = make_inputs(w)
-    run = GpuRun(es, w, theta, a_mat, b_mat)
+    run = GpuChain(es, w, theta, a_mat, b_mat)
     th, m, v = theta.copy(), np.zeros_like(theta), np.zeros_like(theta)
     for g in range(3):
         run.generation(g)
@@ -82,20 +82,20 @@ def test_rerun_and_resume_are_bit_identical(es):
     four generations in one go equal two generations, a saved state, and two more."""
     w = CONFIGS[0]
     a_mat, b_mat, theta = make_inputs(w)
-    full = GpuRun(es, w, theta, a_mat, b_mat)
+    full = GpuChain(es, w, theta, a_mat, b_mat)
     for g in range(4):
         full.generation(g)
     want = full.state()
-    again = GpuRun(es, w, theta, a_mat, b_mat)
+    again = GpuChain(es, w, theta, a_mat, b_mat)
     for g in range(4):
         again.generation(g)
     for x, y in zip(want, again.state()):
         assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
-    first = GpuRun(es, w, theta, a_mat, b_mat)
+    first = GpuChain(es, w, theta, a_mat, b_mat)
     for g in range(2):
         first.generation(g)
     saved = first.state()
-    second = GpuRun(es, w, saved[0], a_mat, b_mat)
+    second = GpuChain(es, w, saved[0], a_mat, b_mat)
     second.m.copy_(dev(saved[1]))
     second.v.copy_(dev(saved[2]))
     for g in range(2, 4):
