@@ -239,3 +239,19 @@ def test_rollout_register_resident_f32(es, w):
 def test_rollout_register_resident_sigma_zero(es):
     got, _ = _case(es, replace(REG, sigma=0.0))
     assert np.all(got[2].view(np.uint32) == got[2].view(np.uint32)[0])
+
+
+def test_rollout_largest_register_resident_shape_and_one_past_it(es):
+    """obs 256 / hidden 256 / act 32 is the largest policy the MFMA kernel places on chip; one more
+    observation and no kernel of this build can hold the individual: a clean error, not a fault."""
+    w = Workload("mfma-max", pop=2, envs=3, horizon=10, obs=256, hid=256, act=32, dtype=1, noise_dtype=1, seed=51,
+                 done_thresh=math.inf)
+    ctx = es.EsContext(w)
+    assert "obs256" in ctx.rollout_kernel
+    _case(es, w, gen=0)
+    big = replace(w, name="past-max", obs=257)
+    ctx = es.EsContext(big)
+    a_mat, b_mat, theta = make_inputs(big)
+    with pytest.raises(es.EsError) as err:
+        run_rollout(ctx, big, 0, theta, ctx.alloc_noise(), a_mat, b_mat)
+    assert err.value.status == -2                      # ES_EUNSUPPORTED
