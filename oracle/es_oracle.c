@@ -54,6 +54,7 @@ typedef struct orc_config {
   float done_thresh, act_cost;
   uint64_t seed;
   uint32_t hidden_act;   /* hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B: the EA experiments use ReLU MLPs) */
+  uint32_t num_hidden;   /* m hidden layers of width hid (paper Sec. 5.1 varies m; the base case is 2); 0 means 2 */
 } orc_config;
 
 enum { STREAM_NOISE = 1, STREAM_RESET = 2 };
@@ -162,9 +163,12 @@ void orc_gauss_pair(uint32_t xa, uint32_t xb, float z[2]) {
 
 static uint32_t noise_rows(const orc_config *cfg) { return cfg->antithetic ? cfg->pop / 2 : cfg->pop; }
 
+static uint32_t hidden_layers(const orc_config *cfg) { return cfg->num_hidden ? cfg->num_hidden : 2u; }
+
+/* obs -> hid, (m - 1) x (hid -> hid), hid -> act, every layer with a bias. */
 size_t orc_param_count(const orc_config *cfg) {
-  size_t o = cfg->obs, h = cfg->hid, a = cfg->act;
-  return (o + 1) * h + (h + 1) * h + (h + 1) * a;
+  size_t o = cfg->obs, h = cfg->hid, a = cfg->act, m = hidden_layers(cfg);
+  return (o + 1) * h + (m - 1) * (h + 1) * h + (h + 1) * a;
 }
 
 /* Noise matrix eps[j, d], j < rows, d < D, dense row-major binary32.

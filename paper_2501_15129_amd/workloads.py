@@ -45,11 +45,12 @@ class Workload:
     algorithm: int = 0  # 0 OpenES ; 1 ARS ; 2 VanillaES (paper Sec. 4.2)
     num_elites: int = 0 # ARS: directions kept ; VanillaES: parents
     hidden_act: int = 0 # hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B)
+    num_hidden: int = 2 # m hidden layers of width hid (paper Sec. 5.1 varies m; base case 2)
 
     @property
     def n_params(self) -> int:
-        o, h, a = self.obs, self.hid, self.act
-        return (o + 1) * h + (h + 1) * h + (h + 1) * a
+        o, h, a, m = self.obs, self.hid, self.act, self.num_hidden
+        return (o + 1) * h + (m - 1) * (h + 1) * h + (h + 1) * a
 
     @property
     def noise_rows(self) -> int:
@@ -74,9 +75,10 @@ CONFIGS = (
 
 
 def layer_shapes(w: Workload):
-    """(rows, cols) of W1, b1, W2, b2, W3, b3 in flat-parameter order; matrices are [out, in] row-major."""
+    """Shapes of W1, b1, (W_l, b_l for the further hidden layers), W3, b3 in flat-parameter order;
+    matrices are [out, in] row-major."""
     o, h, a = w.obs, w.hid, w.act
-    return ((h, o), (h,), (h, h), (h,), (a, h), (a,))
+    return ((h, o), (h,)) + ((h, h), (h,)) * (w.num_hidden - 1) + ((a, h), (a,))
 
 
 def make_inputs(w: Workload):

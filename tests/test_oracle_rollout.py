@@ -24,12 +24,12 @@ def _unpack(w, theta):
 
 
 def _policy_torch(w, theta, s):
-    w1, b1, w2, b2, w3, b3 = (torch.from_numpy(x) for x in _unpack(w, theta))
-    x = torch.from_numpy(np.asarray(s, dtype=np.float64))
+    parts = [torch.from_numpy(x) for x in _unpack(w, theta)]
     act = torch.relu if getattr(w, "hidden_act", 0) == 1 else torch.tanh
-    h1 = act(F.linear(x, w1, b1))
-    h2 = act(F.linear(h1, w2, b2))
-    a = F.linear(h2, w3, b3)
+    h = torch.from_numpy(np.asarray(s, dtype=np.float64))
+    for l in range(len(parts) // 2 - 1):                      # the hidden layers
+        h = act(F.linear(h, parts[2 * l], parts[2 * l + 1]))
+    a = F.linear(h, parts[-2], parts[-1])
     return (torch.tanh(a) if w.out_tanh else a).numpy()
 
 
@@ -319,3 +319,41 @@ def test_obs_norm_zero_scale_blinds_the_policy():
         s0 = oracle.reset(w, 0, e).astype(np.float64)
         want = 1.0 - np.dot(s0, s0) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
         assert abs(ret[0, e] - want) < 1e-6
+
+
+# ---- m hidden layers (paper Sec. 5.1 varies the depth; the five workloads use m = 2) ----
+@pytest.mark.parametrize("m", [1, 3, 4])
+def test_depth_parameter_count_and_library_forward(m):
+    w = replace(W, num_hidden=m, horizon=4, done_thresh=math.inf)
+    assert oracle.param_count(w) == w.n_params == (w.obs + 1) * w.hid + (m - 1) * (w.hid + 1) * w.hid + (w.hid + 1) * w.act
+    a_mat, b_mat, theta = make_inputs(w)
+    theta = (theta + np.random.default_rng(m).standard_normal(theta.size) * 0.05).astype(np.float32)   # non-zero biases
+    eps = oracle.sample_population(w, 2)
+    ret, ln, _, _ = oracle.rollout(w, 2, theta, eps, a_mat, b_mat)
+    a64, b64 = a_mat.astype(np.float64), b_mat.astype(np.float64)
+    for i in (0, 5):
+        th = oracle.perturb(w, theta, eps, i)
+        for e in range(w.envs):
+            s = oracle.reset(w, 2, e).astype(np.float64)
+            total = 0.0
+            for _ in range(w.horizon):
+                act = _policy_torch(w, th, s)
+                total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+                s = np.tanh(a64 @ s + b64 @ act)
+            assert abs(ret[i, e] - total) < 1e-5 and ln[i, e] == w.horizon
+
+
+def test_depth_identity_layer_changes_nothing():
+    """With ReLU, a further hidden layer holding the identity matrix and zero bias maps the non-negative
+    activations of the layer before it onto themselves: m = 3 with such a layer equals m = 2."""
+    w2 = replace(W, hidden_act=1, sigma=0.0, horizon=5, done_thresh=math.inf)
+    w3 = replace(w2, num_hidden=3)
+    a_mat, b_mat, theta2 = make_inputs(w2)
+    theta2 = (theta2 + np.random.default_rng(8).standard_normal(theta2.size) * 0.05).astype(np.float32)
+    p = _unpack(w2, theta2)
+    parts3 = p[:4] + [np.eye(w2.hid), np.zeros(w2.hid)] + p[4:]
+    theta3 = np.concatenate([x.ravel() for x in parts3]).astype(np.float32)
+    assert theta3.size == w3.n_params
+    r2, _, _, _ = oracle.rollout(w2, 0, theta2, np.zeros((w2.noise_rows, w2.n_params), np.float32), a_mat, b_mat)
+    r3, _, _, _ = oracle.rollout(w3, 0, theta3, np.zeros((w3.noise_rows, w3.n_params), np.float32), a_mat, b_mat)
+    assert np.array_equal(r2, r3)
