@@ -78,6 +78,10 @@ typedef struct es_config {
   uint32_t num_elites;   /* ARS: directions kept (b); VanillaES: parents (mu); else ignored  */
   uint32_t hidden_act;   /* activation of the two hidden layers: 0 tanh ; 1 ReLU (the paper's
                             EA experiments use ReLU MLPs, App. B); the action layer follows out_tanh */
+  uint32_t num_hidden;   /* m hidden layers of width hid_dim (the paper's Sec. 5.1 varies m; its base
+                            case and the default are 2; 0 means 2).  Flat parameters: W1[hid,obs], b1,
+                            then (m - 1) x (W[hid,hid], b[hid]), then W3[act,hid], b3.  The register-
+                            resident kernels serve m = 2; other depths run on the LDS kernel            */
 } es_config;
 
 /*

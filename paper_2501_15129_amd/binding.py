@@ -27,7 +27,7 @@ class EsConfig(C.Structure):
         ("adam_eps", C.c_float), ("weight_decay", C.c_float),
         ("done_thresh", C.c_float), ("act_cost", C.c_float),
         ("seed", C.c_uint64),
-        ("algorithm", C.c_uint32), ("num_elites", C.c_uint32), ("hidden_act", C.c_uint32),
+        ("algorithm", C.c_uint32), ("num_elites", C.c_uint32), ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32),
     ]
 
 
@@ -75,7 +75,7 @@ def make_config(w) -> EsConfig:
                     adam_eps=w.adam_eps, weight_decay=w.weight_decay, done_thresh=w.done_thresh,
                     act_cost=w.act_cost, seed=w.seed,
                     algorithm=getattr(w, "algorithm", 0), num_elites=getattr(w, "num_elites", 0),
-                    hidden_act=getattr(w, "hidden_act", 0))
+                    hidden_act=getattr(w, "hidden_act", 0), num_hidden=getattr(w, "num_hidden", 2))
 
 
 def _stream() -> int:

@@ -64,20 +64,24 @@ int es_create(const es_config* cfg, es_ctx** out) {
   if (!(c.beta1 >= 0.0f && c.beta1 < 1.0f) || !(c.beta2 >= 0.0f && c.beta2 < 1.0f)) return bad("betas must lie in [0, 1)");
   if (!(c.adam_eps > 0.0f)) return bad("adam_eps must be positive");
   const uint64_t o = c.obs_dim, h = c.hid_dim, a = c.act_dim;
-  const uint64_t D = (o + 1) * h + (h + 1) * h + (h + 1) * a;
+  const uint64_t m = c.num_hidden ? c.num_hidden : 2;
+  if (m > 64) return bad("num_hidden must be at most 64");
+  const uint64_t D = (o + 1) * h + (m - 1) * (h + 1) * h + (h + 1) * a;
   if (D > (1ull << 30) || (uint64_t)c.pop * c.envs_per_ind > (1ull << 30) || c.obs_dim > 65535 || c.hid_dim > 65535)
     return bad("shape too large");
 
   es_ctx* ctx = new (std::nothrow) es_ctx();
   if (!ctx) { g_create_error = "es_create: out of host memory"; return ES_EINVAL; }
   ctx->cfg = c;
+  ctx->cfg.num_hidden = (uint32_t)m;
   Shape& s = ctx->shp;
   s.N = c.pop; s.E = c.envs_per_ind; s.T = c.horizon; s.no = c.obs_dim; s.nh = c.hid_dim; s.na = c.act_dim;
   s.D = (uint32_t)D;
   s.ld = (s.D + NOISE_LD_ALIGN - 1) / NOISE_LD_ALIGN * NOISE_LD_ALIGN;
   s.rows = c.antithetic ? c.pop / 2 : c.pop;
+  s.m = (uint32_t)m;
   s.oW1 = 0; s.ob1 = (uint32_t)(h * o); s.oW2 = s.ob1 + (uint32_t)h; s.ob2 = s.oW2 + (uint32_t)(h * h);
-  s.oW3 = s.ob2 + (uint32_t)h; s.ob3 = s.oW3 + (uint32_t)(a * h);
+  s.oW3 = s.oW2 + (uint32_t)((m - 1) * (h + 1) * h); s.ob3 = s.oW3 + (uint32_t)(a * h);
 
   int dev = 0, lds = 65536, cus = 256;
   if (hipGetDevice(&dev) == hipSuccess) {

@@ -18,6 +18,7 @@ enum RolloutKind : int {
 struct Shape {
   uint32_t N, E, T, no, nh, na;
   uint32_t D;        // parameter count
+  uint32_t m;        // hidden layers (W2, b2 below are the first of the m - 1 hidden-to-hidden layers, stride (nh + 1) nh)
   uint32_t ld;       // noise row stride (elements)
   uint32_t rows;     // noise rows
   // flat offsets of W1,b1,W2,b2,W3,b3

@@ -761,7 +761,7 @@ static const VariantInfo kVariants[] = {
 };
 
 int mfma_variant_for(const es_config& c) {
-  if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP) return -1;
+  if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP || (c.num_hidden != 0 && c.num_hidden != 2)) return -1;
   // narrow policies are served better by the one-wavefront-per-episode kernel when it fits
   if (c.hid_dim < 128 && wave_rollout_lds_bytes(c) <= 160 * 1024) return -1;
   for (int v = 0; v < 4; ++v)

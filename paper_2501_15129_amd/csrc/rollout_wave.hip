@@ -26,7 +26,7 @@ struct WaveArgs {
   const float* obs_inv;
   float* returns;
   int32_t* ep_len;
-  uint32_t N, E, T, no, nh, na, D, ld;
+  uint32_t N, E, T, no, nh, na, D, ld, m;
   uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
   uint32_t antithetic, out_tanh, noise_mode, hidden_relu;
@@ -56,18 +56,18 @@ struct WaveLayout {
   size_t w1, w2, w3, at, bt, wcount;        // matrix offsets (weight elements)
   size_t b1, b2, b3, s, x, xp, mu, iv, h1, h2, a, qa, fcount;   // float offsets
 };
-__host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint32_t na) {
+__host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint32_t na, uint32_t m) {
   WaveLayout L;
   L.p_h = odd_pitch(nh); L.p_a = odd_pitch(na); L.p_o = odd_pitch(no);
   size_t o = 0;
   L.w1 = o; o += (size_t)no * L.p_h;
-  L.w2 = o; o += (size_t)nh * L.p_h;
+  L.w2 = o; o += (size_t)(m - 1) * nh * L.p_h;        // the m - 1 hidden-to-hidden matrices, one after the other
   L.w3 = o; o += (size_t)nh * L.p_a;
   L.at = o; o += (size_t)no * L.p_o;
   L.bt = o; o += (size_t)na * L.p_o;
   L.wcount = (o + 1) & ~(size_t)1;
   size_t f = 0;
-  L.b1 = f; f += nh; L.b2 = f; f += nh; L.b3 = f; f += na;
+  L.b1 = f; f += nh; L.b2 = f; f += (size_t)(m - 1) * nh; L.b3 = f; f += na;
   L.s = f; f += no; L.x = f; f += no; L.xp = f; f += no; L.mu = f; f += no; L.iv = f; f += no; L.h1 = f; f += nh; L.h2 = f; f += nh;
   L.a = f; f += na; L.qa = f; f += na;
   L.fcount = f;
@@ -75,7 +75,7 @@ __host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint
 }
 
 size_t wave_rollout_lds_bytes(const es_config& c) {
-  const WaveLayout L = wave_layout(c.obs_dim, c.hid_dim, c.act_dim);
+  const WaveLayout L = wave_layout(c.obs_dim, c.hid_dim, c.act_dim, c.num_hidden ? c.num_hidden : 2);
   return L.fcount * 4 + L.wcount * (c.dtype == 1 ? 2 : 4);
 }
 
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
   using WS = WStore<BF16>;
   using WT = typename WS::T;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const WaveLayout L = wave_layout(a.no, a.nh, a.na);
+  const WaveLayout L = wave_layout(a.no, a.nh, a.na, a.m);
   float* fl = reinterpret_cast<float*>(lds_raw);
   WT* wt = reinterpret_cast<WT*>(lds_raw + L.fcount * 4);
 
@@ -100,8 +100,11 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     if (BF16) v = bf16_round(v);
     if (d < a.ob1) { const uint32_t u = d / no, k = d - u * no; wt[L.w1 + (size_t)k * L.p_h + u] = WS::put(v); }
     else if (d < a.oW2) fl[L.b1 + (d - a.ob1)] = v;
-    else if (d < a.ob2) { const uint32_t q = d - a.oW2, u = q / nh, k = q - u * nh; wt[L.w2 + (size_t)k * L.p_h + u] = WS::put(v); }
-    else if (d < a.oW3) fl[L.b2 + (d - a.ob2)] = v;
+    else if (d < a.oW3) {          // hidden layer l + 2: matrix [nh, nh], then its bias
+      const uint32_t per = (nh + 1u) * nh, q = d - a.oW2, l = q / per, r = q - l * per;
+      if (r < nh * nh) { const uint32_t u = r / nh, k = r - u * nh; wt[L.w2 + ((size_t)l * nh + k) * L.p_h + u] = WS::put(v); }
+      else fl[L.b2 + (size_t)l * nh + (r - nh * nh)] = v;
+    }
     else if (d < a.ob3) { const uint32_t q = d - a.oW3, u = q / nh, k = q - u * nh; wt[L.w3 + (size_t)k * L.p_a + u] = WS::put(v); }
     else fl[L.b3 + (d - a.ob3)] = v;
   };
@@ -155,17 +158,21 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
       fl[L.h1 + u] = BF16 ? bf16_round(h) : h;
     }
     __syncthreads();
-    for (uint32_t u = lane; u < nh; u += 64u) {
-      float acc = fl[L.b2 + u];
-      for (uint32_t k = 0; k < nh; ++k) acc = __fmaf_rn(WS::get(wt[L.w2 + (size_t)k * L.p_h + u]), fl[L.h1 + k], acc);
-      const float h = a.hidden_relu ? fmaxf(acc, 0.0f) : tanh_accurate(acc);
-      fl[L.h2 + u] = BF16 ? bf16_round(h) : h;
+    size_t hin = L.h1, hout = L.h2;       // the further hidden layers alternate between the two buffers
+    for (uint32_t l = 0; l + 1 < a.m; ++l) {
+      for (uint32_t u = lane; u < nh; u += 64u) {
+        float acc = fl[L.b2 + (size_t)l * nh + u];
+        for (uint32_t k = 0; k < nh; ++k) acc = __fmaf_rn(WS::get(wt[L.w2 + ((size_t)l * nh + k) * L.p_h + u]), fl[hin + k], acc);
+        const float h = a.hidden_relu ? fmaxf(acc, 0.0f) : tanh_accurate(acc);
+        fl[hout + u] = BF16 ? bf16_round(h) : h;
+      }
+      __syncthreads();
+      const size_t tmp = hin; hin = hout; hout = tmp;
     }
-    __syncthreads();
     float aa = 0.0f;
     for (uint32_t c = lane; c < na; c += 64u) {
       float acc = fl[L.b3 + c];
-      for (uint32_t k = 0; k < nh; ++k) acc = __fmaf_rn(WS::get(wt[L.w3 + (size_t)k * L.p_a + c]), fl[L.h2 + k], acc);
+      for (uint32_t k = 0; k < nh; ++k) acc = __fmaf_rn(WS::get(wt[L.w3 + (size_t)k * L.p_a + c]), fl[hin + k], acc);
       const float av = a.out_tanh ? tanh_accurate(acc) : acc;
       aa = __fmaf_rn(av, av, aa);
       fl[L.qa + c] = BF16 ? bf16_round(av) : av;
@@ -217,7 +224,7 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   const es_config& c = ctx->cfg;
   WaveArgs a;
   a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
-  a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.D = s.D; a.ld = s.ld;
+  a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.D = s.D; a.ld = s.ld; a.m = s.m;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype; a.hidden_relu = c.hidden_act == 1;

@@ -164,7 +164,7 @@ static const RegShape kRegShapes[] = {
 };
 
 int reg_variant_for(const es_config& c) {
-  if (c.dtype != 0) return -1;
+  if (c.dtype != 0 || (c.num_hidden != 0 && c.num_hidden != 2)) return -1;
   for (int v = 0; v < 2; ++v)
     if (c.obs_dim == kRegShapes[v].no && c.hid_dim == kRegShapes[v].nh && c.act_dim == kRegShapes[v].na) return v;
   return -1;

@@ -146,3 +146,65 @@ def test_obs_norm_needs_both_arrays(es):
     ctx = es.EsContext(CONFIGS[0])
     with pytest.raises(es.EsError):
         ctx.set_obs_norm(dev(np.zeros(CONFIGS[0].obs, np.float32)), None)
+
+
+# ---- m hidden layers (paper Sec. 5.1 varies the depth of the policy) ----
+DEPTH_CASES = [
+    Workload("depth1", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=61, num_hidden=1),
+    Workload("depth3", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=62, num_hidden=3),
+    Workload("depth4-relu-bf16", pop=6, envs=3, horizon=40, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=63, num_hidden=4,
+             hidden_act=1),
+    Workload("depth3-regen-noanti", pop=7, envs=2, horizon=40, obs=17, hid=64, act=6, dtype=0, noise_dtype=2, seed=64, num_hidden=3,
+             antithetic=0),
+    Workload("depth1-cfg1-shape", pop=6, envs=4, horizon=50, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=65, num_hidden=1),
+    Workload("depth3-hid256-bf16", pop=2, envs=2, horizon=12, obs=8, hid=160, act=2, dtype=1, noise_dtype=1, seed=66, num_hidden=3,
+             done_thresh=math.inf),
+]
+
+
+@pytest.mark.parametrize("w", DEPTH_CASES, ids=lambda w: w.name)
+def test_rollout_other_depths(es, w):
+    ws = replace(w, noise_dtype=w.noise_dtype & 1)
+    a_mat, b_mat, theta = make_inputs(w)
+    theta = (theta + np.random.default_rng(w.seed).standard_normal(theta.size) * 0.02).astype(np.float32)   # non-zero biases
+    ctx = es.EsContext(w)
+    assert ctx.param_count == w.n_params and "wave_lds" in ctx.rollout_kernel
+    eps = oracle.sample_population(ws, 2)
+    noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
+    got = run_rollout(ctx, w, 2, theta, noise, a_mat, b_mat)
+    ref = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat)
+    probe = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat, arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} D={ctx.param_count} worst {worst:.2e} flips {flips} sensitive {sens}")
+    assert not chaotic
+
+
+def test_generation_with_three_hidden_layers(es):
+    """One whole generation at depth 3 through the four calls (the update runs over the longer parameter vector)."""
+    from gpu_util import assert_params_close, dev
+    w = Workload("depth3-gen", pop=16, envs=2, horizon=30, obs=8, hid=48, act=2, dtype=0, noise_dtype=0, seed=67, num_hidden=3)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    d = ctx.param_count
+    assert d == (8 + 1) * 48 + 2 * 49 * 48 + 49 * 2
+    noise, ws = ctx.alloc_noise(), ctx.alloc_workspace()
+    th, m, v = dev(theta), torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda")
+    ret = torch.empty((w.pop, w.envs), device="cuda")
+    ln = torch.empty((w.pop, w.envs), dtype=torch.int32, device="cuda")
+    fit = torch.empty(w.pop, device="cuda")
+    rk = torch.empty(w.pop, dtype=torch.int32, device="cuda")
+    sh = torch.empty(w.pop, device="cuda")
+    ctx.sample_population(0, noise)
+    ctx.rollout(0, th, noise, dev(a_mat), dev(b_mat), ret, ln, fit, ws)
+    ctx.rank(fit, rk, sh)
+    ctx.update(1, noise, sh, th, m, v, None, ws)
+    torch.cuda.synchronize()
+    eps = oracle.sample_population(w, 0)
+    assert np.array_equal(noise[:, :d].cpu().numpy().view(np.uint32), eps.view(np.uint32))
+    _, _, f_ref, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
+    f_gpu = fit.cpu().numpy()
+    assert np.max(np.abs(f_gpu - f_ref) / np.maximum(np.abs(f_ref), 1e-3)) <= 1e-4
+    r_rank, r_shaped = oracle.rank(f_gpu)
+    assert np.array_equal(rk.cpu().numpy(), r_rank)
+    want = oracle.update(w, 1, eps, r_shaped, theta, np.zeros(d, np.float32), np.zeros(d, np.float32))
+    assert_params_close(th.cpu().numpy(), want[0], "depth-3 theta")
