@@ -229,3 +229,29 @@ def update_vanilla(w, noise, shaped, theta):
     g = np.empty(param_count(w), dtype=np.float32)
     lib().orc_update_vanilla(C.byref(c), _p(noise, C.c_float), _p(shaped, C.c_float), _p(th, C.c_float), _p(g, C.c_float))
     return th, g
+
+
+def table_slice(w, t0: int, t1: int, round_bf16: bool) -> np.ndarray:
+    """Entries ``t0 <= t < t1`` of the shared noise table (float32)."""
+    c = config(w)
+    out = np.empty(t1 - t0, dtype=np.float32)
+    lib().orc_table_slice(C.byref(c), C.c_uint64(t0), C.c_uint64(t1), C.c_int(1 if round_bf16 else 0), _p(out, C.c_float))
+    return out
+
+
+def table_offsets(w, gen: int, table_len: int, span: int) -> np.ndarray:
+    """Start of every noise row of generation ``gen`` in a table of ``table_len`` entries (uint32, multiples of 8)."""
+    c = config(w)
+    out = np.empty(w.noise_rows, dtype=np.uint32)
+    lib().orc_table_offsets(C.byref(c), C.c_uint64(gen), C.c_uint64(table_len), C.c_uint64(span), C.c_uint32(w.noise_rows),
+                            _p(out, C.c_uint32))
+    return out
+
+
+def table_rows(w, gen: int, table_len: int, span: int, round_bf16: bool, table=None) -> np.ndarray:
+    """Dense ``[rows, D]`` noise matrix of generation ``gen`` read out of the table (for the stages that take a matrix)."""
+    d = param_count(w)
+    offs = table_offsets(w, gen, table_len, span)
+    if table is None:
+        table = table_slice(w, 0, table_len, round_bf16)
+    return np.stack([table[int(o):int(o) + d] for o in offs]).astype(np.float32)

@@ -57,7 +57,7 @@ typedef struct orc_config {
   uint32_t num_hidden;   /* m hidden layers of width hid (paper Sec. 5.1 varies m; the base case is 2); 0 means 2 */
 } orc_config;
 
-enum { STREAM_NOISE = 1, STREAM_RESET = 2 };
+enum { STREAM_NOISE = 1, STREAM_RESET = 2, STREAM_TABLE = 3, STREAM_OFFSET = 4 };
 
 /* ------------------------------------------------------------------ */
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: */
@@ -191,6 +191,38 @@ void orc_sample_rows(const orc_config *cfg, uint64_t gen, uint32_t j0, uint32_t 
       if (cfg->noise_dtype == 1) v = orc_bf16_round(v);
       noise[(size_t)(j - j0) * D + d] = v;
     }
+  }
+}
+
+/* Pre-built shared noise table (paper Sec. 5.1: the variant with a noise table built once at
+ * the start of training, after Salimans et al. 2017; the RLlib baseline works this way).
+ * table[t], t < len: variate (t mod 4) of the Philox block with counter (t / 4, 0, 0, STREAM_TABLE),
+ * same Gaussian transform as the noise matrix; rounded to bf16 when round_bf16 is set.
+ * orc_table_slice writes entries t0 <= t < t1 (output indexed from t0). */
+void orc_table_slice(const orc_config *cfg, uint64_t t0, uint64_t t1, int round_bf16, float *table) {
+#pragma omp parallel for schedule(static)
+  for (uint64_t t = t0; t < t1; ++t) {
+    uint32_t w[4];
+    float z[2];
+    stream_block(cfg, (uint32_t)(t / 4), 0, 0, STREAM_TABLE, w);
+    uint32_t q = (uint32_t)(t % 4);
+    orc_gauss_pair(w[q & 2u], w[(q & 2u) + 1], z);
+    float v = z[q & 1u];
+    table[t - t0] = round_bf16 ? orc_bf16_round(v) : v;
+  }
+}
+
+/* Where noise row j of generation gen starts in a table of `len` entries when rows are read with
+ * stride-free length `span` (the padded row length): 8 * (x mod M), M = (len - span) / 8 + 1,
+ * x = word 0 of the Philox block with counter (j, gen, 0, STREAM_OFFSET).  Offsets are multiples
+ * of 8 entries so that rows stay 16-byte aligned; integer work, bit-exact. */
+void orc_table_offsets(const orc_config *cfg, uint64_t gen, uint64_t len, uint64_t span, uint32_t rows,
+                       uint32_t *offsets) {
+  uint64_t M = (len - span) / 8 + 1;
+  for (uint32_t j = 0; j < rows; ++j) {
+    uint32_t w[4];
+    stream_block(cfg, j, (uint32_t)gen, 0, STREAM_OFFSET, w);
+    offsets[j] = (uint32_t)(8u * (uint64_t)(w[0] % M));
   }
 }
 

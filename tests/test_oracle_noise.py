@@ -168,3 +168,58 @@ def test_reset_is_uniform_and_keyed():
 def test_param_count_matches_shapes():
     for w, d in zip(CONFIGS, (1539, 5702, 5702, 75016, 132881)):
         assert oracle.param_count(w) == d == w.n_params
+
+
+# ---- pre-built shared noise table (paper Sec. 5.1: the noise-table variant, after Salimans et al. 2017) ----
+def test_table_entries_are_the_pinned_generator_and_transform_on_stream_three():
+    import torch
+    w = CONFIGS[1]
+    key = [w.seed & 0xFFFFFFFF, w.seed >> 32]
+    t0, t1 = 1000, 1064
+    tab = oracle.table_slice(w, t0, t1, False)
+    for t in range(t0, t1):
+        words = oracle.philox4x32_10([t // 4, 0, 0, 3], key)
+        za, zb = oracle.gauss_pair(words[2 * ((t % 4) // 2)], words[2 * ((t % 4) // 2) + 1])
+        want = np.float32(zb if t % 2 else za)
+        assert tab[t - t0].view(np.uint32) == want.view(np.uint32)
+    rounded = oracle.table_slice(w, t0, t1, True)
+    lib = torch.from_numpy(tab).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(rounded.view(np.uint32), lib.view(np.uint32))
+    # slices agree with one another and differ from the per-generation noise stream
+    assert np.array_equal(oracle.table_slice(w, 0, 2048, False)[t0:t1], tab)
+    assert not np.array_equal(oracle.sample_population(w, 0, rows=(0, 1))[0, :64], oracle.table_slice(w, 0, 64, False))
+
+
+def test_table_moments():
+    tab = oracle.table_slice(CONFIGS[0], 0, 1 << 18, False).astype(np.float64)
+    n = tab.size
+    assert abs(tab.mean()) < 5 / np.sqrt(n) and abs(tab.var() - 1) < 5 * np.sqrt(2 / n)
+    assert abs(np.mean(tab ** 3)) < 5 * np.sqrt(15 / n) and abs(np.mean(tab ** 4) - 3) < 5 * np.sqrt(96 / n)
+    assert abs(np.corrcoef(tab[:-1], tab[1:])[0, 1]) < 5 / np.sqrt(n)
+
+
+def test_table_offsets_are_aligned_in_range_and_follow_their_counter():
+    w = CONFIGS[3]
+    key = [w.seed & 0xFFFFFFFF, w.seed >> 32]
+    length, span = 1 << 22, 75264
+    offs = oracle.table_offsets(w, 5, length, span)
+    assert offs.size == w.noise_rows and np.all(offs % 8 == 0) and np.all(offs.astype(np.int64) + span <= length)
+    m = (length - span) // 8 + 1
+    for j in (0, 1, 17, w.noise_rows - 1):
+        assert int(offs[j]) == 8 * (oracle.philox4x32_10([j, 5, 0, 4], key)[0] % m)
+    assert not np.array_equal(offs, oracle.table_offsets(w, 6, length, span))
+    # spread over the table: the offsets of 512 rows fall into all eight eighths of the range
+    assert len(set((offs.astype(np.int64) * 8 // (length - span + 8)).tolist())) == 8
+    # the smallest admissible table has a single place for a row
+    assert np.all(oracle.table_offsets(w, 5, span, span) == 0)
+
+
+def test_table_rows_are_slices_of_the_table():
+    w = CONFIGS[0]
+    length = 8192
+    tab = oracle.table_slice(w, 0, length, False)
+    offs = oracle.table_offsets(w, 2, length, 2048)
+    rows = oracle.table_rows(w, 2, length, 2048, False)
+    assert rows.shape == (w.noise_rows, w.n_params)
+    for j in range(w.noise_rows):
+        assert np.array_equal(rows[j], tab[offs[j]:offs[j] + w.n_params])
