@@ -37,7 +37,7 @@ def flop_per_env_step(w) -> int:
 
 def update_bytes(w, ctx) -> int:
     """Algorithmic bytes of es_update: the noise matrix once, theta/m/v read and written, the weights."""
-    elt = 2 if w.noise_dtype == 1 else 4
+    elt = 2 if w.noise_dtype in (1, 5) else 4
     return w.noise_rows * w.n_params * elt + 24 * w.n_params + 4 * w.pop
 
 
@@ -92,7 +92,7 @@ def cpu_baseline(w, budget_s=12.0, obs_norm=None):
     a_mat, b_mat, theta = make_inputs(w)
 
     def timed(n_ind):
-        ws = replace(w, pop=n_ind, noise_dtype=w.noise_dtype & 1)     # the checker's noise values do not depend on storage
+        ws = replace(w, pop=n_ind, noise_dtype=w.noise_dtype & 1)     # the checker's arithmetic does not depend on where the noise is kept
         t0 = time.perf_counter()
         eps = oracle.sample_population(ws, 0)
         ret, ln, fit, _ = oracle.rollout(ws, 0, theta, eps, a_mat, b_mat, obs_norm=obs_norm)
@@ -125,9 +125,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="index into the five workloads (default: the largest)")
     ap.add_argument("--done-rule", action="store_true", help="time the workload with its termination rule on")
-    ap.add_argument("--noise-dtype", type=int, default=None, choices=[0, 1, 2, 3],
+    ap.add_argument("--noise-dtype", type=int, default=None, choices=[0, 1, 2, 3, 4, 5],
                     help="override the workload's noise storage: 0/1 stored binary32/bf16 matrix, 2/3 no matrix, values "
-                         "regenerated from the counter stream in es_rollout and es_update")
+                         "regenerated from the counter stream in es_rollout and es_update, 4/5 rows read from a shared "
+                         "binary32/bf16 table built once (paper Sec. 5.1)")
+    ap.add_argument("--table-len", type=int, default=1 << 26, help="entries of the shared noise table (--noise-dtype 4, 5)")
     ap.add_argument("--algorithm", choices=["openes", "ars", "vanilla"], default="openes",
                     help="strategy of es_rank / es_update (paper Sec. 4.2); ars and vanilla keep pop/8 elites "
                          "(the ratio of App. B Table 5) and use that table's step sizes")
@@ -166,7 +168,7 @@ def main() -> int:
         return 0
     base = CONFIGS[args.config]
     if args.noise_dtype is not None:
-        base = replace(base, noise_dtype=args.noise_dtype)
+        base = replace(base, noise_dtype=args.noise_dtype, noise_table_len=args.table_len if args.noise_dtype >= 4 else 0)
     if args.hidden_act == "relu":
         base = replace(base, name=base.name + "-relu", hidden_act=1)
     if args.algorithm == "ars":
@@ -188,7 +190,10 @@ def main() -> int:
         dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
         if obs_stats is not None:
             ctx.set_obs_norm(dev(obs_stats[0]), dev(obs_stats[1]))
-        bufs = dict(noise=ctx.alloc_noise(), ws=ctx.alloc_workspace(), theta=dev(theta), A=dev(a_mat), B=dev(b_mat),
+        noise = ctx.alloc_noise()
+        if ctx.noise_table:
+            ctx.build_noise_table(noise)          # once, outside the timed region (the table does not depend on the generation)
+        bufs = dict(noise=noise, ws=ctx.alloc_workspace(), theta=dev(theta), A=dev(a_mat), B=dev(b_mat),
                     m=torch.zeros(d, device="cuda"), v=torch.zeros(d, device="cuda"),
                     ret=torch.empty((wl.pop, wl.envs), device="cuda"),
                     len=torch.empty((wl.pop, wl.envs), dtype=torch.int32, device="cuda"),
@@ -224,7 +229,7 @@ def main() -> int:
                        "unit": "GB/s", "frac": ugbs / HBM_PEAK_GBS, "traffic": traffic.get("update_bytes_per_launch"),
                        "bytes_per_launch": ub,
                        "avg_launch_ms": upd_ms}
-    if w.noise_dtype >= 2:      # no noise matrix: the update recomputes every value and is bound by the vector ALUs
+    if w.noise_dtype in (2, 3):      # no noise matrix: the update recomputes every value and is bound by the vector ALUs
         ops = w.noise_rows * ((w.n_params + 3) // 4) * REGEN_VALU_OPS_PER_BLOCK
         tops = ops / (upd_ms * 1e-3) / 1e12
         roofline_update = {"kernel": ctx.update_kernel, "bound": "alu", "achieved": tops, "peak": VALU_PEAK_TLANEOPS,
@@ -241,7 +246,9 @@ def main() -> int:
                                f"{'termination rule on (live env-steps counted)' if args.done_rule else 'fixed-length episodes (paper Sec. 5.1 protocol)'}",
                    "population": w.pop, "envs_per_individual": w.envs, "horizon": w.horizon, "params": w.n_params,
                    "noise": {0: "binary32 matrix", 1: "bf16 matrix", 2: "regenerated (binary32 values), no matrix",
-                             3: "regenerated (bf16-rounded values), no matrix"}[w.noise_dtype],
+                             3: "regenerated (bf16-rounded values), no matrix",
+                             4: "rows of a shared binary32 table of %d entries" % w.noise_table_len,
+                             5: "rows of a shared bf16 table of %d entries" % w.noise_table_len}[w.noise_dtype],
                    "obs_norm": bool(args.obs_norm), "rollout_kernel": ctx.rollout_kernel},
         "generations_per_s": args.steps / wall,
         "env_steps_per_generation": executed,

@@ -36,6 +36,13 @@
  * es_rollout / es_update recompute each value from the counter stream where they need it.
  * Mode 2 uses the binary32 values (the results of noise_dtype 0), mode 3 rounds them to bf16
  * (the results of noise_dtype 1), bit for bit.
+ *
+ * Shared noise table (noise_dtype 4: binary32 entries, 5: bf16 entries; the paper's Sec. 5.1
+ * variant with a table built once at the start of training, after Salimans et al. 2017): the
+ * noise buffer is [table: noise_table_len entries | row offsets: es_noise_rows() uint32].
+ * es_build_noise_table fills the table once; es_sample_population only draws, for every noise
+ * row of the generation, where in the table the row starts (a multiple of 8 entries, so rows
+ * stay 16-byte aligned), and es_rollout / es_update read row j at table + offset[j].
  */
 #ifndef ES_H_
 #define ES_H_
@@ -64,7 +71,8 @@ typedef struct es_config {
                             hidden activations and action as inputs of the next product) is
                             rounded to bf16; accumulation, tanh, reward, return are binary32 */
   uint32_t noise_dtype;  /* 0: binary32 noise matrix ; 1: bf16 noise matrix ;
-                            2 / 3: no matrix, values regenerated (binary32 / bf16-rounded)   */
+                            2 / 3: no matrix, values regenerated (binary32 / bf16-rounded) ;
+                            4 / 5: rows read from a shared table (binary32 / bf16 entries)   */
   uint32_t antithetic;   /* 1: individuals 2j and 2j+1 use +eps_j and -eps_j                 */
   uint32_t out_tanh;     /* 1: tanh on the action layer as well                              */
   float sigma;           /* noise std (paper App. B Table 5b: 0.02)                          */
@@ -82,6 +90,8 @@ typedef struct es_config {
                             case and the default are 2; 0 means 2).  Flat parameters: W1[hid,obs], b1,
                             then (m - 1) x (W[hid,hid], b[hid]), then W3[act,hid], b3.  The register-
                             resident kernels serve m = 2; other depths run on the LDS kernel            */
+  uint64_t noise_table_len; /* entries of the shared noise table (noise_dtype 4, 5 only): a multiple
+                            of 8, at least es_noise_ld(), below 2^32                                    */
 } es_config;
 
 /*
@@ -128,6 +138,14 @@ const char* es_last_error(const es_ctx* ctx);
 int es_set_obs_norm(es_ctx* ctx, const float* mean_d, const float* inv_std_d);
 
 /*
+ * Fills the shared noise table (noise_dtype 4, 5; ES_EINVAL otherwise): entry t < noise_table_len is
+ * variate (t mod 4) of the Philox4x32-10 block with counter (t / 4, 0, 0, 3) and key (seed low,
+ * seed high), through the same binary32 Box-Muller sequence as the noise matrix, rounded to bf16
+ * in mode 5.  Called once; the table does not depend on the generation.
+ */
+int es_build_noise_table(es_ctx* ctx, void* noise_d, void* stream);
+
+/*
  * Noise of generation `generation` (paper Sec. 5.1: perturbations are generated on the fly
  * each generation, not read from a pre-built table).  noise[j, d] for j < rows, d < D is
  * variate (d mod 4) of the Philox4x32-10 block with counter (d / 4, j, generation, 1) and
@@ -135,6 +153,9 @@ int es_set_obs_norm(es_ctx* ctx, const float* mean_d, const float* inv_std_d);
  * rounded to bf16 (nearest-even) when noise_dtype = 1.  generation < 2^32.
  * Writes rows * ld elements to noise_d.  With regenerated noise (noise_dtype 2, 3) nothing is
  * written: the call records `generation` in the context for the next es_update.
+ * With a shared table (noise_dtype 4, 5) it writes the row offsets of this generation behind the
+ * table: offset[j] = 8 * (x mod M), M = (noise_table_len - ld) / 8 + 1, x = word 0 of the Philox
+ * block with counter (j, generation, 0, 4).
  */
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream);
 

@@ -28,6 +28,7 @@ class EsConfig(C.Structure):
         ("done_thresh", C.c_float), ("act_cost", C.c_float),
         ("seed", C.c_uint64),
         ("algorithm", C.c_uint32), ("num_elites", C.c_uint32), ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32),
+        ("noise_table_len", C.c_uint64),
     ]
 
 
@@ -57,6 +58,7 @@ def load_library() -> C.CDLL:
     lib.es_last_error.argtypes = [vp]
     lib.es_last_error.restype = C.c_char_p
     lib.es_set_obs_norm.argtypes = [vp, vp, vp]
+    lib.es_build_noise_table.argtypes = [vp, vp, vp]
     lib.es_sample_population.argtypes = [vp, u64, vp, vp]
     lib.es_rollout.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.es_rank.argtypes = [vp, vp, vp, vp, vp]
@@ -75,7 +77,8 @@ def make_config(w) -> EsConfig:
                     adam_eps=w.adam_eps, weight_decay=w.weight_decay, done_thresh=w.done_thresh,
                     act_cost=w.act_cost, seed=w.seed,
                     algorithm=getattr(w, "algorithm", 0), num_elites=getattr(w, "num_elites", 0),
-                    hidden_act=getattr(w, "hidden_act", 0), num_hidden=getattr(w, "num_hidden", 2))
+                    hidden_act=getattr(w, "hidden_act", 0), num_hidden=getattr(w, "num_hidden", 2),
+                    noise_table_len=getattr(w, "noise_table_len", 0))
 
 
 def _stream() -> int:
@@ -112,7 +115,8 @@ class EsContext:
         self.rollout_kernel = _lib.es_rollout_kernel(h).decode()
         self.update_kernel = _lib.es_update_kernel(h).decode()
         self.noise_torch_dtype = torch.bfloat16 if self.cfg.noise_dtype == 1 else torch.float32
-        self.noise_regenerated = self.cfg.noise_dtype >= 2      # no matrix: every `noise` argument is None
+        self.noise_regenerated = self.cfg.noise_dtype in (2, 3)     # no matrix: every `noise` argument is None
+        self.noise_table = self.cfg.noise_dtype >= 4                # `noise` is a raw byte buffer: table | row offsets
 
     def close(self):
         if getattr(self, "_h", None):
@@ -130,13 +134,23 @@ class EsContext:
     def alloc_noise(self, device="cuda"):
         if self.noise_regenerated:
             return None
+        if self.noise_table:
+            return torch.empty(self.noise_bytes, dtype=torch.uint8, device=device)
         return torch.empty((self.noise_rows, self.noise_ld), dtype=self.noise_torch_dtype, device=device)
 
     def alloc_workspace(self, device="cuda"):
         return torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
 
     def _noise_ptr(self, noise, n):
-        return None if self.noise_regenerated else _ptr(noise, self.noise_torch_dtype, n, "noise")
+        if self.noise_regenerated:
+            return None
+        if self.noise_table:
+            return _ptr(noise, torch.uint8, self.noise_bytes, "noise")
+        return _ptr(noise, self.noise_torch_dtype, n, "noise")
+
+    def build_noise_table(self, noise):
+        """Fill the shared noise table (noise_dtype 4, 5) once; ``noise`` comes from ``alloc_noise()``."""
+        self._check(_lib.es_build_noise_table(self._h, _ptr(noise, torch.uint8, self.noise_bytes, "noise"), _stream()))
 
     def set_obs_norm(self, mean, inv_std):
         """Frozen observation statistics ([obs] float32 device tensors, kept alive here), or ``None, None``."""

@@ -48,7 +48,7 @@ int es_create(const es_config* cfg, es_ctx** out) {
   if (c.pop == 0 || c.envs_per_ind == 0 || c.horizon == 0) return bad("pop, envs_per_ind and horizon must be positive");
   if (c.obs_dim == 0 || c.hid_dim == 0 || c.act_dim == 0) return bad("layer widths must be positive");
   if (c.dtype > 1) return bad("dtype must be 0 or 1");
-  if (c.noise_dtype > 3) return bad("noise_dtype must be 0..3");
+  if (c.noise_dtype > 5) return bad("noise_dtype must be 0..5");
   if (c.antithetic > 1 || c.out_tanh > 1) return bad("antithetic and out_tanh must be 0 or 1");
   if (c.antithetic && (c.pop & 1u)) return bad("pop must be even with mirrored sampling");
   if (c.hidden_act > 1) return bad("hidden_act must be 0 (tanh) or 1 (ReLU)");
@@ -106,11 +106,16 @@ int es_create(const es_config* cfg, es_ctx** out) {
     ctx->rollout_kind = ROLLOUT_WAVE_LDS;
     ctx->kernel_name = c.dtype == 1 ? "rollout_wave_lds_bf16" : "rollout_wave_lds_f32";
   }
+  if (c.noise_dtype >= 4 && (c.noise_table_len % 8 != 0 || c.noise_table_len < s.ld || c.noise_table_len >= (1ull << 32))) {
+    delete ctx;
+    return bad("noise_table_len must be a multiple of 8, at least the padded row length, and below 2^32");
+  }
   ctx->obs_mean = nullptr;
   ctx->obs_inv_std = nullptr;
   ctx->regen_generation = 0;
   ctx->regen_valid = false;
-  ctx->upd_chunks = c.noise_dtype >= 2 ? update_chunks_regen(s.rows, s.D) : update_chunks(s.rows, s.ld, c.noise_dtype == 1);
+  const bool regen = c.noise_dtype == 2 || c.noise_dtype == 3, bf16_noise = c.noise_dtype == 1 || c.noise_dtype == 5;
+  ctx->upd_chunks = regen ? update_chunks_regen(s.rows, s.D) : update_chunks(s.rows, s.ld, bf16_noise);
   ctx->workspace_bytes = std::max<size_t>(256, (size_t)ctx->upd_chunks * s.ld * sizeof(double));
   *out = ctx;
   return ES_OK;
@@ -125,14 +130,17 @@ size_t es_param_count(const es_ctx* ctx) { return ctx ? ctx->shp.D : 0; }
 size_t es_noise_rows(const es_ctx* ctx) { return ctx ? ctx->shp.rows : 0; }
 size_t es_noise_ld(const es_ctx* ctx) { return ctx ? ctx->shp.ld : 0; }
 size_t es_noise_bytes(const es_ctx* ctx) {
-  if (!ctx || ctx->cfg.noise_dtype >= 2) return 0;       // regenerated noise is never stored
-  return (size_t)ctx->shp.rows * ctx->shp.ld * (ctx->cfg.noise_dtype == 1 ? 2 : 4);
+  if (!ctx) return 0;
+  const uint32_t nd = ctx->cfg.noise_dtype;
+  if (nd == 2 || nd == 3) return 0;                       // regenerated noise is never stored
+  if (nd >= 4) return (size_t)ctx->cfg.noise_table_len * (nd == 5 ? 2 : 4) + (size_t)ctx->shp.rows * 4;   // table | row offsets
+  return (size_t)ctx->shp.rows * ctx->shp.ld * (nd == 1 ? 2 : 4);
 }
 size_t es_workspace_bytes(const es_ctx* ctx) { return ctx ? ctx->workspace_bytes : 0; }
 const char* es_rollout_kernel(const es_ctx* ctx) { return ctx ? ctx->kernel_name.c_str() : ""; }
 const char* es_update_kernel(const es_ctx* ctx) {
   if (!ctx) return "";
-  if (ctx->cfg.noise_dtype >= 2) return "grad_regen_kernel+adam_kernel";
+  if (ctx->cfg.noise_dtype == 2 || ctx->cfg.noise_dtype == 3) return "grad_regen_kernel+adam_kernel";
   return ctx->upd_chunks == 1 ? "update_single_pass_kernel" : "grad_partial_kernel+adam_kernel";
 }
 
@@ -145,15 +153,24 @@ int es_set_obs_norm(es_ctx* ctx, const float* mean_d, const float* inv_std_d) {
   return ES_OK;
 }
 
+int es_build_noise_table(es_ctx* ctx, void* noise_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (ctx->cfg.noise_dtype < 4) return fail(ctx, ES_EINVAL, "es_build_noise_table: this context does not use a noise table");
+  if (!noise_d) return fail(ctx, ES_EINVAL, "es_build_noise_table: noise_d is null");
+  return launch_table(ctx, noise_d, static_cast<hipStream_t>(stream));
+}
+
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {
   if (!ctx) return ES_EINVAL;
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_sample_population: generation must be < 2^32");
-  if (ctx->cfg.noise_dtype >= 2) {     // nothing to store: remember which generation es_update regenerates
+  if (ctx->cfg.noise_dtype == 2 || ctx->cfg.noise_dtype == 3) {     // nothing to store: remember which generation es_update regenerates
     ctx->regen_generation = (uint32_t)generation;
     ctx->regen_valid = true;
     return ES_OK;
   }
   if (!noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
+  if (ctx->cfg.noise_dtype >= 4)
+    return launch_table_offsets(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
   return launch_sample(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
 }
 
@@ -162,7 +179,7 @@ int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const voi
                void* stream) {
   if (!ctx) return ES_EINVAL;
   if (!theta_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d ||
-      (!noise_d && ctx->cfg.noise_dtype < 2))
+      (!noise_d && ctx->cfg.noise_dtype != 2 && ctx->cfg.noise_dtype != 3))
     return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -189,10 +206,10 @@ int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_
 int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, float* theta_d,
               float* m_d, float* v_d, float* grad_d, void* workspace_d, void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!shaped_d || !theta_d || !workspace_d || (!noise_d && ctx->cfg.noise_dtype < 2) ||
+  if (!shaped_d || !theta_d || !workspace_d || (!noise_d && ctx->cfg.noise_dtype != 2 && ctx->cfg.noise_dtype != 3) ||
       ((!m_d || !v_d) && ctx->cfg.algorithm == ES_OPENES))
     return fail(ctx, ES_EINVAL, "es_update: null device pointer");
-  if (ctx->cfg.noise_dtype >= 2 && !ctx->regen_valid)
+  if ((ctx->cfg.noise_dtype == 2 || ctx->cfg.noise_dtype == 3) && !ctx->regen_valid)
     return fail(ctx, ES_EINVAL, "es_update: with regenerated noise, es_sample_population must name the generation first");
   if (adam_step < 1 && ctx->cfg.algorithm == ES_OPENES) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
   if (!(ctx->cfg.sigma > 0.0f)) return fail(ctx, ES_EINVAL, "es_update: sigma must be > 0");

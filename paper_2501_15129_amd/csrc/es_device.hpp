@@ -129,6 +129,14 @@ __device__ __forceinline__ float noise_value(uint32_t mode, const void* base, ui
   return static_cast<const float*>(base)[(size_t)row * ld + d];
 }
 
+// With a shared noise table, row `row` starts at base + offs[row] elements; returns that row's base
+// (to be indexed as row 0) for the stored element type of `mode` (0 binary32, 1 bf16).
+__device__ __forceinline__ const void* table_row_base(uint32_t mode, const void* base, const uint32_t* offs, uint32_t row) {
+  const uint32_t o = offs[row];
+  return mode == 1u ? static_cast<const void*>(static_cast<const uint16_t*>(base) + o)
+                    : static_cast<const void*>(static_cast<const float*>(base) + o);
+}
+
 // Initial state element k of environment copy e: uniform on [-0.1, 0.1).
 __device__ __forceinline__ float reset_value(uint32_t k, uint32_t e, uint32_t gen, uint32_t k0, uint32_t k1) {
   const Words4 w = philox4x32_10(k >> 2, e, gen, 2u, k0, k1);

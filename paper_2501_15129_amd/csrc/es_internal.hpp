@@ -51,12 +51,35 @@ namespace es {
 constexpr uint32_t NOISE_LD_ALIGN = 512;   // elements
 constexpr uint32_t STREAM_NOISE = 1u;
 constexpr uint32_t STREAM_RESET = 2u;
+constexpr uint32_t STREAM_TABLE = 3u;
+constexpr uint32_t STREAM_OFFSET = 4u;
 
 int fail(es_ctx* ctx, int code, const std::string& what);
+
+// Noise storage modes of es_config.noise_dtype as the kernels see them: `mode` 0 / 1 = binary32 / bf16
+// elements behind a pointer, 2 / 3 = regenerated; `offs` non-null = rows start at base + offs[row]
+// (shared table) instead of base + row * ld.
+struct NoiseView {
+  const void* base;
+  const uint32_t* offs;
+  uint32_t mode;
+};
+inline NoiseView noise_view(const es_ctx* ctx, const void* noise) {
+  NoiseView v;
+  v.base = noise; v.offs = nullptr; v.mode = ctx->cfg.noise_dtype;
+  if (ctx->cfg.noise_dtype >= 4) {
+    v.mode = ctx->cfg.noise_dtype - 4;
+    const size_t table_bytes = (size_t)ctx->cfg.noise_table_len * (v.mode == 1 ? 2 : 4);
+    v.offs = reinterpret_cast<const uint32_t*>(static_cast<const char*>(noise) + table_bytes);
+  }
+  return v;
+}
 int check_launch(es_ctx* ctx, const char* what);
 
 // stage launchers (each validates nothing: the API layer has done so)
 int launch_sample(es_ctx* ctx, uint32_t gen, void* noise, hipStream_t st);
+int launch_table(es_ctx* ctx, void* noise, hipStream_t st);
+int launch_table_offsets(es_ctx* ctx, uint32_t gen, void* noise, hipStream_t st);
 int launch_rank(es_ctx* ctx, const float* fit, int32_t* rank, float* shaped, hipStream_t st);
 int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* shaped, float* theta,
                   float* m, float* v, float* grad, void* ws, hipStream_t st);

@@ -31,6 +31,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 struct MfmaArgs {
   const float* theta;
   const void* noise;
+  const uint32_t* noise_offs;   // shared noise table: start of every row, else null
   const float* A;
   const float* B;
   const float* obs_mean;     // frozen observation statistics (paper App. B), or null
@@ -352,7 +353,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       NoiseRow nz;
       nz.mode = a.noise_mode; nz.row = unit; nz.gen = a.gen; nz.k0 = a.k0; nz.k1 = a.k1;
       nz.ptr = nullptr;           // regenerated noise has no buffer
-      if (a.noise_mode == 1u) nz.ptr = static_cast<const uint16_t*>(a.noise) + (size_t)unit * a.ld;
+      if (a.noise_offs) nz.ptr = table_row_base(a.noise_mode, a.noise, a.noise_offs, unit);
+      else if (a.noise_mode == 1u) nz.ptr = static_cast<const uint16_t*>(a.noise) + (size_t)unit * a.ld;
       else if (a.noise_mode == 0u) nz.ptr = static_cast<const float*>(a.noise) + (size_t)unit * a.ld;
 
       // ---------------- perturbed policy weights -> registers ----------------
@@ -795,11 +797,12 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   MfmaArgs a;
-  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len; a.fitness = fitness;
+  const NoiseView nv = noise_view(ctx, noise);
+  a.theta = theta; a.noise = nv.base; a.noise_offs = nv.offs; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len; a.fitness = fitness;
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.ld = s.ld;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   if ((int)V256<16, 4>::LDS_BYTES > ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");

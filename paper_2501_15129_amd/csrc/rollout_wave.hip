@@ -20,6 +20,7 @@ namespace es {
 struct WaveArgs {
   const float* theta;
   const void* noise;
+  const uint32_t* noise_offs;   // shared noise table: start of every row, else null
   const float* A;
   const float* B;
   const float* obs_mean;     // frozen observation statistics, or null
@@ -95,6 +96,9 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
   const uint32_t no = a.no, nh = a.nh, na = a.na;
 
   // ---- stage the perturbed parameters of individual i (fused perturbation) ----
+  const void* nbase = a.noise;      // shared table: this individual's row, addressed as row 0
+  uint32_t nrow = row;
+  if (a.noise_offs) { nbase = table_row_base(a.noise_mode, a.noise, a.noise_offs, row); nrow = 0u; }
   auto place = [&](uint32_t d, float eps) {
     float v = __fmaf_rn(scale, eps, a.theta[d]);
     if (BF16) v = bf16_round(v);
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
         if (d0 + k < a.D) place(d0 + k, z[k]);
     }
   } else {
-    for (uint32_t d = lane; d < a.D; d += 64u) place(d, noise_value(a.noise_mode, a.noise, a.ld, row, d, a.gen, a.k0, a.k1));
+    for (uint32_t d = lane; d < a.D; d += 64u) place(d, noise_value(a.noise_mode, nbase, a.ld, nrow, d, a.gen, a.k0, a.k1));
   }
   for (uint32_t q = lane; q < no * no; q += 64u) {
     const uint32_t k = q / no, j = q - k * no;
@@ -223,11 +227,12 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   WaveArgs a;
-  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
+  const NoiseView nv = noise_view(ctx, noise);
+  a.theta = theta; a.noise = nv.base; a.noise_offs = nv.offs; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.D = s.D; a.ld = s.ld; a.m = s.m;
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype; a.hidden_relu = c.hidden_act == 1;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode; a.hidden_relu = c.hidden_act == 1;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const size_t lds = ctx->lds_bytes_wave;
   hipError_t err;

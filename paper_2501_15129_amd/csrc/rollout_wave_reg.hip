@@ -19,6 +19,7 @@ namespace es {
 struct RegArgs {
   const float* theta;
   const void* noise;
+  const uint32_t* noise_offs;   // shared noise table: start of every row, else null
   const float* A;
   const float* B;
   const float* obs_mean;     // frozen observation statistics, or null
@@ -69,8 +70,11 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   const float scale = (a.antithetic && (i & 1u)) ? -a.sigma : a.sigma;
   const bool hid = u < NH, obs = u < NO;
 
+  const void* nbase = a.noise;      // shared table: this individual's row, addressed as row 0
+  uint32_t nrow = row;
+  if (a.noise_offs) { nbase = table_row_base(a.noise_mode, a.noise, a.noise_offs, row); nrow = 0u; }
   auto param = [&](uint32_t d) -> float {     // perturbed parameter d of individual i (binary32, one rounding)
-    return __fmaf_rn(scale, noise_value(a.noise_mode, a.noise, a.ld, row, d, a.gen, a.k0, a.k1), a.theta[d]);
+    return __fmaf_rn(scale, noise_value(a.noise_mode, nbase, a.ld, nrow, d, a.gen, a.k0, a.k1), a.theta[d]);
   };
 
   // ---- this lane's weights ----
@@ -177,10 +181,11 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
   RegArgs a;
-  a.theta = theta; a.noise = noise; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
+  const NoiseView nv = noise_view(ctx, noise);
+  a.theta = theta; a.noise = nv.base; a.noise_offs = nv.offs; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = c.noise_dtype; a.hidden_relu = c.hidden_act == 1;
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode; a.hidden_relu = c.hidden_act == 1;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const dim3 grid(s.N * s.E), block(64);
   switch (ctx->reg_variant) {

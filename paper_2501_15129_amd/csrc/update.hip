@@ -57,6 +57,7 @@ struct NoiseVec<false> {
 
 template <bool BF16>
 __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restrict__ noise,
+                                                           const uint32_t* __restrict__ offs,
                                                            const float* __restrict__ shaped,
                                                            double* __restrict__ partial, uint32_t rows,
                                                            uint32_t ld, uint32_t rows_per_chunk,
@@ -65,6 +66,7 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
   constexpr int VEC = NV::VEC;
   using Raw = typename NV::Raw;
   __shared__ double coef[UPD_MAX_ROWS_PER_CHUNK];
+  __shared__ uint32_t rowoff[UPD_MAX_ROWS_PER_CHUNK];     // start of each row in Raw units (row * ld, or its place in the shared table)
   __shared__ double red[4][64 * VEC];
 
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -72,8 +74,10 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
   const uint32_t r1 = min(rows, r0 + rows_per_chunk);
   const uint32_t col0 = blockIdx.x * (64u * VEC);
 
-  for (uint32_t r = r0 + threadIdx.x; r < r1; r += 256u)
+  for (uint32_t r = r0 + threadIdx.x; r < r1; r += 256u) {
     coef[r - r0] = antithetic ? (double)shaped[2 * r] - (double)shaped[2 * r + 1] : (double)shaped[r];
+    rowoff[r - r0] = offs ? offs[r] / VEC : 0u;
+  }
   __syncthreads();
 
   double acc[VEC];
@@ -81,12 +85,13 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
   for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
 
   const Raw* base = reinterpret_cast<const Raw*>(noise) + ((size_t)col0 / VEC + lane);
-  const size_t row_stride = ld / VEC;   // in Raw units
+  const size_t row_stride = offs ? 0 : ld / VEC;   // in Raw units; table rows are placed by rowoff instead
+  auto row_at = [&](uint32_t rr) { return base + (size_t)rr * row_stride + rowoff[rr - r0]; };
   uint32_t r = r0 + wave;
   for (; r + 12u < r1; r += 16u) {      // four rows of this wavefront in flight
     Raw q[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) q[u] = __builtin_nontemporal_load(base + (size_t)(r + 4u * u) * row_stride);
+    for (int u = 0; u < 4; ++u) q[u] = offs ? *row_at(r + 4u * u) : __builtin_nontemporal_load(row_at(r + 4u * u));
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float f[VEC];
@@ -97,7 +102,7 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
     }
   }
   for (; r < r1; r += 4u) {
-    const Raw q = __builtin_nontemporal_load(base + (size_t)r * row_stride);
+    const Raw q = offs ? *row_at(r) : __builtin_nontemporal_load(row_at(r));
     float f[VEC];
     NV::unpack(q, f);
     const double c = coef[r - r0];
@@ -185,6 +190,7 @@ constexpr uint32_t UPD_COEF_ROWS = 2048;   // row weights staged in LDS per pass
 
 template <bool BF16>
 __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(const void* __restrict__ noise,
+                                                                const uint32_t* __restrict__ offs,
                                                                 const float* __restrict__ shaped, uint32_t rows,
                                                                 uint32_t ld, uint32_t D, uint32_t antithetic,
                                                                 const AdamArgs ad, float* __restrict__ theta,
@@ -194,12 +200,13 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
   using Raw = typename NQ::Raw;
   constexpr int VEC = NQ::VEC, UPD_TILE = 64 * VEC;
   __shared__ double coef[UPD_COEF_ROWS];
+  __shared__ uint32_t rowoff[UPD_COEF_ROWS];     // shared noise table: start of each row in Raw units
   __shared__ double red[UPD1_WAVES][UPD_TILE];
 
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
   const uint32_t col0 = blockIdx.x * UPD_TILE;
   const Raw* base = reinterpret_cast<const Raw*>(noise) + ((size_t)col0 / VEC + lane);
-  const size_t row_stride = ld / VEC;     // in Raw units
+  const size_t row_stride = offs ? 0 : ld / VEC;     // in Raw units; table rows are placed by rowoff instead
 
   double acc[VEC];
 #pragma unroll
@@ -207,15 +214,17 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
   for (uint32_t rb = 0; rb < rows; rb += UPD_COEF_ROWS) {
     const uint32_t rn = min(UPD_COEF_ROWS, rows - rb);
     __syncthreads();
-    for (uint32_t r = threadIdx.x; r < rn; r += 64u * UPD1_WAVES)
+    for (uint32_t r = threadIdx.x; r < rn; r += 64u * UPD1_WAVES) {
       coef[r] = antithetic ? (double)shaped[2 * (rb + r)] - (double)shaped[2 * (rb + r) + 1] : (double)shaped[rb + r];
+      rowoff[r] = offs ? offs[rb + r] / VEC : 0u;
+    }
     __syncthreads();
     uint32_t r = wave;
     for (; r + UPD1_WAVES * (UPD1_INFLIGHT - 1) < rn; r += UPD1_WAVES * UPD1_INFLIGHT) {
       Raw q[UPD1_INFLIGHT];
 #pragma unroll
       for (int u = 0; u < UPD1_INFLIGHT; ++u)
-        q[u] = __builtin_nontemporal_load(base + (size_t)(rb + r + UPD1_WAVES * u) * row_stride);
+        q[u] = __builtin_nontemporal_load(base + (size_t)(rb + r + UPD1_WAVES * u) * row_stride + rowoff[r + UPD1_WAVES * u]);
 #pragma unroll
       for (int u = 0; u < UPD1_INFLIGHT; ++u) {
         float f[VEC];
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
       }
     }
     for (; r < rn; r += UPD1_WAVES) {
-      const Raw q = __builtin_nontemporal_load(base + (size_t)(rb + r) * row_stride);
+      const Raw q = __builtin_nontemporal_load(base + (size_t)(rb + r) * row_stride + rowoff[r]);
       float f[VEC];
       NQ::unpack(q, f);
       const double c = coef[r];
@@ -288,15 +297,17 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
                   float* m, float* v, float* grad, void* ws, hipStream_t st) {
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
-  const bool bf16 = c.noise_dtype == 1;
+  const NoiseView nv = noise_view(ctx, noise);
+  const bool bf16 = nv.mode == 1;
   const uint32_t chunks = ctx->upd_chunks;
   const AdamArgs ad = step_args(ctx, step);
-  if (c.noise_dtype >= 2) {
+  noise = nv.base;
+  if (nv.mode >= 2) {
     const uint32_t rpc = (s.rows + chunks - 1) / chunks;
     double* partial = static_cast<double*>(ws);
     const dim3 grid(((s.D + 3u) / 4u + 255u) / 256u, chunks);       // one thread per group of four columns
     hipLaunchKernelGGL(grad_regen_kernel, grid, dim3(256), 0, st, shaped, partial, s.rows, s.ld, s.D, rpc, c.antithetic,
-                       c.noise_dtype == 3 ? 1u : 0u, ctx->regen_generation, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
+                       nv.mode == 3 ? 1u : 0u, ctx->regen_generation, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
     int rc = check_launch(ctx, "es_update (regenerated gradient partials)");
     if (rc != ES_OK) return rc;
     hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D, ad,
@@ -306,10 +317,10 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
   if (chunks == 1) {
     const dim3 grid1(s.ld / (64 * (bf16 ? 8 : 4))), block1(64 * UPD1_WAVES);
     if (bf16)
-      hipLaunchKernelGGL(update_single_pass_kernel<true>, grid1, block1, 0, st, noise, shaped, s.rows, s.ld, s.D,
+      hipLaunchKernelGGL(update_single_pass_kernel<true>, grid1, block1, 0, st, noise, nv.offs, shaped, s.rows, s.ld, s.D,
                          c.antithetic, ad, theta, m, v, grad);
     else
-      hipLaunchKernelGGL(update_single_pass_kernel<false>, grid1, block1, 0, st, noise, shaped, s.rows, s.ld, s.D,
+      hipLaunchKernelGGL(update_single_pass_kernel<false>, grid1, block1, 0, st, noise, nv.offs, shaped, s.rows, s.ld, s.D,
                          c.antithetic, ad, theta, m, v, grad);
     return check_launch(ctx, "es_update (single pass)");
   }
@@ -318,10 +329,10 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
   double* partial = static_cast<double*>(ws);
   dim3 grid(s.ld / tile, chunks);
   if (bf16)
-    hipLaunchKernelGGL(grad_partial_kernel<true>, grid, dim3(256), 0, st, noise, shaped, partial, s.rows,
+    hipLaunchKernelGGL(grad_partial_kernel<true>, grid, dim3(256), 0, st, noise, nv.offs, shaped, partial, s.rows,
                        s.ld, rpc, c.antithetic);
   else
-    hipLaunchKernelGGL(grad_partial_kernel<false>, grid, dim3(256), 0, st, noise, shaped, partial, s.rows,
+    hipLaunchKernelGGL(grad_partial_kernel<false>, grid, dim3(256), 0, st, noise, nv.offs, shaped, partial, s.rows,
                        s.ld, rpc, c.antithetic);
   int rc = check_launch(ctx, "es_update (gradient partials)");
   if (rc != ES_OK) return rc;

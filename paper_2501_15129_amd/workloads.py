@@ -30,7 +30,7 @@ class Workload:
     hid: int            # n_h (two hidden layers)
     act: int            # n_a
     dtype: int          # 0: fp32 ; 1: bf16 contraction operands, fp32 accumulate
-    noise_dtype: int    # 0: fp32 noise matrix ; 1: bf16 noise matrix
+    noise_dtype: int    # 0 / 1: fp32 / bf16 noise matrix ; 2 / 3: regenerated ; 4 / 5: rows of a shared fp32 / bf16 table
     seed: int
     sigma: float = 0.02
     lr: float = 0.01
@@ -46,6 +46,7 @@ class Workload:
     num_elites: int = 0 # ARS: directions kept ; VanillaES: parents
     hidden_act: int = 0 # hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B)
     num_hidden: int = 2 # m hidden layers of width hid (paper Sec. 5.1 varies m; base case 2)
+    noise_table_len: int = 0  # entries of the shared noise table (noise_dtype 4, 5; paper Sec. 5.1)
 
     @property
     def n_params(self) -> int:

@@ -38,7 +38,7 @@ def test_config_struct_matches_header(binding):
     for decl in re.findall(r"(?:uint32_t|uint64_t|float)\s+([^;]+);", struct):
         names += [n.strip() for n in decl.split(",")]
     assert names == [n for n, _ in binding.EsConfig._fields_]
-    assert C.sizeof(binding.EsConfig) == 96        # 10 u32 + 8 f32 + u64 + 4 u32
+    assert C.sizeof(binding.EsConfig) == 104       # 10 u32 + 8 f32 + u64 + 4 u32 + u64
 
 
 def test_context_queries(binding):
@@ -66,7 +66,7 @@ def test_regenerated_noise_contexts_store_nothing(binding):
 
 @pytest.mark.parametrize("bad", [
     dict(pop=7), dict(pop=0), dict(envs=0), dict(horizon=0), dict(obs=0), dict(hid=0), dict(act=0),
-    dict(dtype=2), dict(noise_dtype=4), dict(algorithm=3), dict(hidden_act=2), dict(num_hidden=65), dict(algorithm=1, num_elites=0),
+    dict(dtype=2), dict(noise_dtype=6), dict(noise_dtype=4, noise_table_len=12), dict(noise_dtype=5, noise_table_len=1024), dict(algorithm=3), dict(hidden_act=2), dict(num_hidden=65), dict(algorithm=1, num_elites=0),
     dict(algorithm=1, num_elites=5, antithetic=0), dict(algorithm=2, num_elites=4), dict(algorithm=2, antithetic=0, num_elites=10**6),
     dict(antithetic=2), dict(out_tanh=5),
     dict(sigma=-1.0), dict(sigma=math.nan), dict(beta1=1.0), dict(beta2=-0.1), dict(adam_eps=0.0),

@@ -1,0 +1,179 @@
+"""Shared noise table (noise_dtype 4 and 5; paper Sec. 5.1: the variant with a table built once at the
+start of training): table and row offsets bit-exact against the CPU checker, then rollout and update
+against the checker evaluated on the dense rows it reads out of ITS table."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs, random_fitness
+from gpu_util import assert_params_close, compare_rollout, dev, run_rollout
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def es():
+    import paper_2501_15129_amd as pkg
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return pkg
+
+
+def stored(w):
+    return replace(w, noise_dtype=w.noise_dtype & 1)
+
+
+def table_and_offsets(ctx, noise):
+    """Host views of a table-mode noise buffer: (table as float32, offsets as uint32)."""
+    raw = noise.cpu().numpy()
+    n = ctx.cfg.noise_table_len
+    if ctx.cfg.noise_dtype == 5:
+        tab = (raw[:2 * n].view(np.uint16).astype(np.uint32) << 16).view(np.float32)
+        offs = raw[2 * n:].view(np.uint32)
+    else:
+        tab = raw[:4 * n].view(np.float32)
+        offs = raw[4 * n:].view(np.uint32)
+    return tab, offs
+
+
+@pytest.mark.parametrize("w", [
+    Workload("tab-f32", pop=10, envs=1, horizon=1, obs=13, hid=29, act=7, dtype=0, noise_dtype=4, seed=71, noise_table_len=1 << 16),
+    Workload("tab-bf16", pop=34, envs=1, horizon=1, obs=13, hid=29, act=7, dtype=1, noise_dtype=5, seed=72, noise_table_len=40008),
+    Workload("tab-min", pop=6, envs=1, horizon=1, obs=3, hid=5, act=2, dtype=0, noise_dtype=4, seed=73, noise_table_len=512),
+], ids=lambda w: w.name)
+def test_table_and_offsets_bit_exact(es, w):
+    ctx = es.EsContext(w)
+    assert ctx.noise_bytes == w.noise_table_len * (2 if w.noise_dtype == 5 else 4) + 4 * ctx.noise_rows
+    noise = ctx.alloc_noise()
+    noise.zero_()
+    ctx.build_noise_table(noise)
+    for gen in (0, 7):
+        ctx.sample_population(gen, noise)
+        torch.cuda.synchronize()
+        tab, offs = table_and_offsets(ctx, noise)
+        want = oracle.table_slice(w, 0, w.noise_table_len, w.noise_dtype == 5)
+        assert np.array_equal(tab.view(np.uint32), want.view(np.uint32))
+        assert np.array_equal(offs, oracle.table_offsets(w, gen, w.noise_table_len, ctx.noise_ld))
+
+
+ROLL = [
+    Workload("tab-odd", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=4, seed=22, noise_table_len=1 << 15),
+    Workload("tab-odd-bf16-noanti", pop=7, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=1, noise_dtype=5, seed=22, antithetic=0,
+             noise_table_len=1 << 15),
+    replace(CONFIGS[0], name="tab-cfg0", noise_dtype=4, noise_table_len=1 << 14),
+    replace(CONFIGS[1], name="tab-cfg1-T120", noise_dtype=4, horizon=120, noise_table_len=1 << 16),
+    Workload("tab-mfma32", pop=6, envs=16, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=5, seed=31, noise_table_len=1 << 18),
+    Workload("tab-mfma256", pop=4, envs=4, horizon=16, obs=244, hid=256, act=17, dtype=1, noise_dtype=5, seed=34, done_thresh=math.inf,
+             noise_table_len=1 << 18),
+    Workload("tab-mfma128-f32table", pop=4, envs=16, horizon=30, obs=100, hid=200, act=20, dtype=1, noise_dtype=4, seed=33,
+             noise_table_len=1 << 18),
+]
+
+
+@pytest.mark.parametrize("w", ROLL, ids=lambda w: w.name)
+def test_rollout_reads_its_rows_from_the_table(es, w):
+    ws = stored(w)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    noise = ctx.alloc_noise()
+    ctx.build_noise_table(noise)
+    ctx.sample_population(3, noise)
+    got = run_rollout(ctx, w, 3, theta, noise, a_mat, b_mat)
+    eps = oracle.table_rows(w, 3, w.noise_table_len, ctx.noise_ld, w.noise_dtype == 5)
+    ref = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat)
+    probe = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat, arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens}")
+    assert not chaotic
+
+
+UPD = [
+    Workload("tab-upd-small", pop=6, envs=1, horizon=1, obs=3, hid=5, act=2, dtype=0, noise_dtype=4, seed=5, noise_table_len=1024),
+    Workload("tab-upd-ragged", pop=34, envs=1, horizon=1, obs=13, hid=29, act=7, dtype=0, noise_dtype=5, seed=6, noise_table_len=1 << 14),
+    Workload("tab-upd-noanti", pop=33, envs=1, horizon=1, obs=13, hid=29, act=7, dtype=0, noise_dtype=4, antithetic=0, seed=7,
+             noise_table_len=1 << 14),
+    Workload("tab-upd-mid", pop=1024, envs=1, horizon=1, obs=27, hid=64, act=8, dtype=1, noise_dtype=5, seed=8, noise_table_len=1 << 20),
+    Workload("tab-upd-ars", pop=64, envs=1, horizon=1, obs=27, hid=64, act=8, dtype=0, noise_dtype=5, seed=9, noise_table_len=1 << 17,
+             algorithm=1, num_elites=8, lr=0.02, sigma=0.03),
+]
+
+
+@pytest.mark.parametrize("w", UPD, ids=lambda w: w.name)
+def test_update_reads_its_rows_from_the_table(es, w):
+    ws = stored(w)
+    ctx = es.EsContext(w)
+    d = w.n_params
+    rng = np.random.default_rng(w.pop)
+    theta = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    m, v = np.zeros(d, np.float32), np.zeros(d, np.float32)
+    th_d, m_d, v_d = dev(theta), dev(m), dev(v)
+    g_d = torch.empty(d, dtype=torch.float32, device="cuda")
+    noise, wsp = ctx.alloc_noise(), ctx.alloc_workspace()
+    ctx.build_noise_table(noise)
+    table = oracle.table_slice(w, 0, w.noise_table_len, w.noise_dtype == 5)
+    for k in range(1, 4):
+        ctx.sample_population(k, noise)
+        eps = oracle.table_rows(w, k, w.noise_table_len, ctx.noise_ld, w.noise_dtype == 5, table=table)
+        f = random_fitness(w.pop, seed=w.pop + k, ties=True)
+        if w.algorithm == 1:
+            _, shaped = oracle.rank_ars(f, w.num_elites)
+            theta, g = oracle.update_ars(ws, w.num_elites, eps, shaped, theta)
+        else:
+            _, shaped = oracle.rank(f)
+            theta, m, v, g = oracle.update(ws, k, eps, shaped, theta, m, v)
+        ctx.update(k, noise, dev(shaped), th_d, m_d, v_d, g_d, wsp)
+        torch.cuda.synchronize()
+        assert_params_close(g_d.cpu().numpy(), g, f"{w.name} step {k} g")
+        assert_params_close(th_d.cpu().numpy(), theta, f"{w.name} step {k} theta")
+
+
+def test_generation_with_table_full_size_cfg4(es):
+    """configs[4] with a 64 M-entry bf16 table (128 MB instead of the 545 MB matrix): sampled mirrored pairs
+    of the rollout and the whole 132 881-parameter update against the checker."""
+    n = 1 << 26
+    base = CONFIGS[4]
+    w = replace(base, name="cfg4-table", noise_dtype=5, noise_table_len=n)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    assert ctx.update_kernel.startswith("grad_partial")
+    noise = ctx.alloc_noise()
+    ctx.build_noise_table(noise)
+    ctx.sample_population(1, noise)
+    got = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
+    table = oracle.table_slice(w, 0, n, True)
+    offs = oracle.table_offsets(w, 1, n, ctx.noise_ld)
+    d = w.n_params
+    refs, probes, subs = [], [], []
+    for j in (0, 901, base.pop // 2 - 1):
+        eps = table[offs[j]:offs[j] + d][None, :].copy()
+        ind = (2 * j, 2 * j + 2)
+        refs.append(oracle.rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j))
+        probes.append(oracle.rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, arith=1))
+        subs.append(tuple(x[ind[0]:ind[1]] for x in got))
+    cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
+    _, worst, _, chaotic = compare_rollout(base, cat(subs), cat(refs), w.name, cat(probes))
+    assert not chaotic
+    rng = np.random.default_rng(45)
+    th = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    m = (rng.standard_normal(d) * 0.01).astype(np.float32)
+    v = (rng.random(d) * 1e-3).astype(np.float32)
+    _, shaped = oracle.rank(got[2])
+    eps_all = np.stack([table[o:o + d] for o in offs])
+    want = oracle.update(base, 2, eps_all, shaped, th, m, v)
+    th_d, m_d, v_d = dev(th), dev(m), dev(v)
+    g_d = torch.empty(d, dtype=torch.float32, device="cuda")
+    ctx.update(2, noise, dev(shaped), th_d, m_d, v_d, g_d, ctx.alloc_workspace())
+    torch.cuda.synchronize()
+    for gpu, ref, name in ((th_d, want[0], "theta"), (m_d, want[1], "m"), (v_d, want[2], "v"), (g_d, want[3], "grad")):
+        assert_params_close(gpu.cpu().numpy(), ref, f"cfg4 table {name}")
+    del noise
+    torch.cuda.empty_cache()
+
+
+def test_table_calls_are_refused_without_a_table(es):
+    ctx = es.EsContext(CONFIGS[0])
+    with pytest.raises(es.EsError):
+        ctx._check(es.raw_library().es_build_noise_table(ctx._h, ctx.alloc_noise().data_ptr(), None))
