@@ -131,12 +131,14 @@ def main() -> int:
                          "binary32/bf16 table built once (paper Sec. 5.1)")
     ap.add_argument("--table-len", type=int, default=1 << 26, help="entries of the shared noise table (--noise-dtype 4, 5)")
     ap.add_argument("--algorithm", choices=["openes", "ars", "vanilla"], default="openes",
-                    help="strategy of es_rank / es_update (paper Sec. 4.2); ars and vanilla keep pop/8 elites "
+                    help="strategy of es_rank / es_update (paper Sec. 4); ars and vanilla keep pop/8 elites "
                          "(the ratio of App. B Table 5) and use that table's step sizes")
     ap.add_argument("--hidden-act", choices=["tanh", "relu"], default="tanh",
                     help="hidden-layer activation (the paper's EA experiments use ReLU MLPs, App. B)")
     ap.add_argument("--obs-norm", action="store_true",
                     help="frozen observation statistics for the policy input (paper App. B); synthetic: mean N(0, 0.05^2), std U[0.33, 1]")
+    ap.add_argument("--episodes-per-env", type=int, default=1,
+                    help="k episodes per environment copy (auto-reset wrapper, paper Sec. 3.1); not the default workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -175,6 +177,8 @@ def main() -> int:
         base = replace(base, name=base.name + "-ars", algorithm=1, num_elites=max(1, base.pop // 8), lr=0.02, sigma=0.03)
     elif args.algorithm == "vanilla":
         base = replace(base, name=base.name + "-vanilla", algorithm=2, num_elites=max(1, base.pop // 8), antithetic=0)
+    if args.episodes_per_env != 1:
+        base = replace(base, name=base.name + f"-k{args.episodes_per_env}", episodes=args.episodes_per_env)
     w = base if args.done_rule else base.fixed_length()
     a_mat, b_mat, theta = make_inputs(w)
 
@@ -195,8 +199,8 @@ def main() -> int:
             ctx.build_noise_table(noise)          # once, outside the timed region (the table does not depend on the generation)
         bufs = dict(noise=noise, ws=ctx.alloc_workspace(), theta=dev(theta), A=dev(a_mat), B=dev(b_mat),
                     m=torch.zeros(d, device="cuda"), v=torch.zeros(d, device="cuda"),
-                    ret=torch.empty((wl.pop, wl.envs), device="cuda"),
-                    len=torch.empty((wl.pop, wl.envs), dtype=torch.int32, device="cuda"),
+                    ret=torch.empty((wl.pop, ctx.episodes), device="cuda"),
+                    len=torch.empty((wl.pop, ctx.episodes), dtype=torch.int32, device="cuda"),
                     fit=torch.empty(wl.pop, device="cuda"), rank=torch.empty(wl.pop, dtype=torch.int32, device="cuda"),
                     shaped=torch.empty(wl.pop, device="cuda"))
         return ctx, bufs
@@ -221,7 +225,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm else None) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm and args.episodes_per_env == 1 else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
@@ -241,10 +245,10 @@ def main() -> int:
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs, T={w.horizon}, MLP {w.obs}-{w.hid}-{w.hid}-{w.act} {args.hidden_act}, "
+        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs{'' if w.episodes == 1 else ' x %d episodes each' % w.episodes}, T={w.horizon}, MLP {w.obs}-{w.hid}-{w.hid}-{w.act} {args.hidden_act}, "
                                f"{'bf16 operands / fp32 accumulate' if bf16 else 'fp32'}, "
                                f"{'termination rule on (live env-steps counted)' if args.done_rule else 'fixed-length episodes (paper Sec. 5.1 protocol)'}",
-                   "population": w.pop, "envs_per_individual": w.envs, "horizon": w.horizon, "params": w.n_params,
+                   "population": w.pop, "envs_per_individual": w.envs, "episodes_per_env": w.episodes, "horizon": w.horizon, "params": w.n_params,
                    "noise": {0: "binary32 matrix", 1: "bf16 matrix", 2: "regenerated (binary32 values), no matrix",
                              3: "regenerated (bf16-rounded values), no matrix",
                              4: "rows of a shared binary32 table of %d entries" % w.noise_table_len,

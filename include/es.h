@@ -3,7 +3,7 @@
  *
  * One generation of the evolutionary policy search of arXiv 2501.15129 is four
  * enqueues on one HIP stream, with no host synchronisation in between (the paper's
- * Workflow.step() runs as one device program: Sec. 3.1, Sec. 3.3):
+ * Workflow.step() runs as one device program: Sec. 3.1, Sec. 3.2):
  *
  *     es_sample_population -> es_rollout -> es_rank -> es_update
  *
@@ -19,7 +19,8 @@
  *     so a failing call enqueues nothing.
  *   - Determinism: no floating-point atomics; the same inputs give bit-identical
  *     outputs on every run.
- *   - N = pop, E = envs_per_ind, T = horizon, D = es_param_count().
+ *   - N = pop, E = envs_per_ind * episodes_per_env (episodes per fitness evaluation), T = horizon,
+ *     D = es_param_count().
  *
  * Flat parameter vector theta[D] (binary32): W1[hid,obs], b1[hid], W2[hid,hid], b2[hid],
  * W3[act,hid], b3[act], in this order, each matrix row-major [out,in].
@@ -63,7 +64,7 @@ typedef enum es_status {
 
 typedef struct es_config {
   uint32_t pop;          /* N; must be even when antithetic = 1                              */
-  uint32_t envs_per_ind; /* E: environment copies = episodes per fitness evaluation          */
+  uint32_t envs_per_ind; /* environment copies per individual (see episodes_per_env)          */
   uint32_t horizon;      /* T: maximum episode length                                        */
   uint32_t obs_dim, hid_dim, act_dim; /* policy MLP obs -> hid -> hid -> act                 */
   uint32_t dtype;        /* 0: binary32 everywhere.  1: every operand of a matrix product
@@ -92,10 +93,17 @@ typedef struct es_config {
                             resident kernels serve m = 2; other depths run on the LDS kernel            */
   uint64_t noise_table_len; /* entries of the shared noise table (noise_dtype 4, 5 only): a multiple
                             of 8, at least es_noise_ld(), below 2^32                                    */
+  uint32_t episodes_per_env; /* k episodes run back to back in every environment copy, the copy resetting
+                            itself in between (the auto-reset environment wrapper of the paper's Sec. 3.1);
+                            0 means 1.  Episode p of copy e starts from reset number e * k + p and its return
+                            sits at column e * k + p, so E = envs_per_ind * k episodes make up the fitness.
+                            The episodes of one copy do not depend on each other, so the kernels run all E
+                            side by side (with few copies this also fills matrix-core columns that would
+                            otherwise idle) and the results equal the sequential schedule's exactly         */
 } es_config;
 
 /*
- * The strategies of the paper's Sec. 4.2 that share this sampling and evaluation.
+ * The strategies of the paper's Sec. 4 that share this sampling and evaluation.
  * Sampling and es_rollout are the same for all; es_rank and es_update differ:
  *   ES_OPENES   centred ranks, Adam                                  (App. B Table 5b)
  *   ES_ARS      the best b mirrored directions by max(F+, F-), returns divided by the standard
@@ -160,7 +168,7 @@ int es_build_noise_table(es_ctx* ctx, void* noise_d, void* stream);
 int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream);
 
 /*
- * Population x environment evaluation (paper Sec. 3.3: all individuals at once, each on E
+ * Population x environment evaluation (paper Sec. 3.2: all individuals at once, each on E
  * parallel environment copies; Sec. 5.2: deterministic MLP policy, fitness = mean
  * undiscounted episodic return).  For individual i (noise row j = i/2, sign +/- when
  * mirrored, else j = i, +):
@@ -178,7 +186,7 @@ int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const voi
                float* fitness_d, void* workspace_d, void* stream);
 
 /*
- * Centred-rank fitness shaping (the OpenES of the paper's Sec. 4.2, after Salimans et al.):
+ * Centred-rank fitness shaping (the OpenES of the paper's Sec. 4, after Salimans et al.):
  * rank_i = position of individual i in ascending fitness order, ties broken by index
  * (-0 equals +0; NaNs sort by bit pattern, no error); shaped_i = rank_i / (N-1) - 1/2.
  * In: fitness_d [N] f32.  Out: rank_d [N] i32, shaped_d [N] f32.

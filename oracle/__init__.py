@@ -29,7 +29,7 @@ class OrcConfig(C.Structure):
         ("adam_eps", C.c_float), ("weight_decay", C.c_float),
         ("done_thresh", C.c_float), ("act_cost", C.c_float),
         ("seed", C.c_uint64),
-        ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32),
+        ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32), ("episodes", C.c_uint32),
     ]
 
 
@@ -62,7 +62,7 @@ def config(w) -> OrcConfig:
     """Build the checker's config from a workload description (any object with these fields)."""
     c = OrcConfig()
     for name, _ in OrcConfig._fields_:
-        setattr(c, name, getattr(w, name, 0) if name in ("hidden_act", "num_hidden") else getattr(w, name))
+        setattr(c, name, getattr(w, name, 0) if name in ("hidden_act", "num_hidden", "episodes") else getattr(w, name))
     return c
 
 
@@ -142,7 +142,8 @@ def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: in
 
     ``obs_norm = (mean [obs], inv_std [obs])``: frozen observation statistics for the policy's input.
 
-    Returns ``(returns [n,E] f32, ep_len [n,E] i32, fitness [n] f32, margin [n,E] f32)``.
+    Returns ``(returns [n,E*K] f32, ep_len [n,E*K] i32, fitness [n] f32, margin [n,E*K] f32)`` with ``K`` the
+    episodes per environment copy (1 unless the workload sets ``episodes``).
     """
     c = config(w)
     theta, noise, a_mat, b_mat = _f32(theta), _f32(noise), _f32(a_mat), _f32(b_mat)
@@ -151,10 +152,11 @@ def rollout(w, gen: int, theta, noise, a_mat, b_mat, individuals=None, arith: in
     first, last = (i0 // 2, (i1 - 1) // 2) if w.antithetic else (i0, i1 - 1)
     assert noise.ndim == 2 and noise.shape[1] == param_count(w)
     assert noise_row0 <= first and last < noise_row0 + noise.shape[0], "noise rows do not cover these individuals"
-    ret = np.empty((n, w.envs), dtype=np.float32)
-    ln = np.empty((n, w.envs), dtype=np.int32)
+    cols = w.envs * max(1, getattr(w, "episodes", 1))     # episodes of one environment copy sit next to each other
+    ret = np.empty((n, cols), dtype=np.float32)
+    ln = np.empty((n, cols), dtype=np.int32)
     fit = np.empty(n, dtype=np.float32)
-    mar = np.empty((n, w.envs), dtype=np.float32)
+    mar = np.empty((n, cols), dtype=np.float32)
     null = C.POINTER(C.c_float)()
     mean = inv = None
     if obs_norm is not None:

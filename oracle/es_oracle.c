@@ -9,7 +9,7 @@
  * CPU-baseline leg may load it.
  *
  * What it follows (paper = arXiv 2501.15129):
- *   - Sec. 3.3 "Computation model": every individual of the population is
+ *   - Sec. 3.2 "Computation model": every individual of the population is
  *     evaluated at once, each on several parallel environment copies
  *     (two-level vectorisation: agents x environments).
  *   - Sec. 5.2: deterministic two-hidden-layer MLP policy; fitness = mean
@@ -55,6 +55,8 @@ typedef struct orc_config {
   uint64_t seed;
   uint32_t hidden_act;   /* hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B: the EA experiments use ReLU MLPs) */
   uint32_t num_hidden;   /* m hidden layers of width hid (paper Sec. 5.1 varies m; the base case is 2); 0 means 2 */
+  uint32_t episodes;     /* episodes run one after the other in every environment copy, the environment resetting
+                            itself in between (paper Sec. 3.1: the auto-reset wrapper); 0 means 1 */
 } orc_config;
 
 enum { STREAM_NOISE = 1, STREAM_RESET = 2, STREAM_TABLE = 3, STREAM_OFFSET = 4 };
@@ -246,6 +248,8 @@ void orc_perturb(const orc_config *cfg, const float *theta, const float *eps_row
 
 /* Initial state of environment copy e in generation gen: uniform on [-0.1, 0.1),
  * the same for every individual. */
+static uint32_t episodes_per_env(const orc_config *cfg) { return cfg->episodes ? cfg->episodes : 1u; }
+
 void orc_reset(const orc_config *cfg, uint64_t gen, uint32_t e, float *s0) {
   for (uint32_t k = 0; k < cfg->obs; ++k) {
     uint32_t w[4];
@@ -286,8 +290,9 @@ static double q_operand(const orc_config *cfg, double x) {
 #undef ROLLOUT_FN
 
 /* Evaluate individuals i0 <= i < i1 (outputs indexed from i0):
- *   returns[(i-i0)*E + e], ep_len[(i-i0)*E + e], fitness[i-i0] = mean_e returns,
- *   margin[(i-i0)*E + e] = min over executed steps of | max_k|s_{t+1,k}| - done_thresh |
+ *   returns[((i-i0)*E + e)*K + p], ep_len[same], fitness[i-i0] = mean over the E*K episodes
+ *   (K = episodes per environment copy, 1 unless configured),
+ *   margin[same index] = min over executed steps of | max_k|s_{t+1,k}| - done_thresh |
  *   (how close the termination test came to flipping; +inf when the rule is off).
  * noise holds the rows from noise_row0 on (dense, D per row): row r of the matrix is at
  * noise + (r - noise_row0) * D.
@@ -299,7 +304,7 @@ void orc_rollout_norm(const orc_config *cfg, uint64_t gen, const float *theta, c
                       const float *obs_inv_std, uint32_t i0, uint32_t i1, int arith,
                       float *returns, int32_t *ep_len, float *fitness, float *margin) {
   size_t D = orc_param_count(cfg);
-  uint32_t E = cfg->envs, no = cfg->obs, na = cfg->act;
+  uint32_t E = cfg->envs, no = cfg->obs, na = cfg->act, K = episodes_per_env(cfg);
   /* environment matrices as the rollout sees them */
   float *Ae = (float *)malloc(sizeof(float) * no * no);
   float *Be = (float *)malloc(sizeof(float) * no * na);
@@ -313,18 +318,21 @@ void orc_rollout_norm(const orc_config *cfg, uint64_t gen, const float *theta, c
     orc_perturb(cfg, theta, noise + (size_t)(row - noise_row0) * D, i, theta_i);
     double fit = 0.0;
     for (uint32_t e = 0; e < E; ++e) {
-      double ret, mar;
-      int32_t len;
-      orc_reset(cfg, gen, e, s0);
-      if (arith == 0) rollout_pair_f64(cfg, theta_i, Ae, Be, obs_mean, obs_inv_std, s0, &ret, &len, &mar);
-      else rollout_pair_f32(cfg, theta_i, Ae, Be, obs_mean, obs_inv_std, s0, &ret, &len, &mar);
-      size_t o = (size_t)(i - i0) * E + e;
-      returns[o] = (float)ret;
-      ep_len[o] = len;
-      if (margin) margin[o] = (float)mar;
-      fit += ret;
+      /* K episodes one after the other in this environment copy; episode p starts from reset number e * K + p */
+      for (uint32_t p = 0; p < K; ++p) {
+        double ret, mar;
+        int32_t len;
+        orc_reset(cfg, gen, e * K + p, s0);
+        if (arith == 0) rollout_pair_f64(cfg, theta_i, Ae, Be, obs_mean, obs_inv_std, s0, &ret, &len, &mar);
+        else rollout_pair_f32(cfg, theta_i, Ae, Be, obs_mean, obs_inv_std, s0, &ret, &len, &mar);
+        size_t o = ((size_t)(i - i0) * E + e) * K + p;
+        returns[o] = (float)ret;
+        ep_len[o] = len;
+        if (margin) margin[o] = (float)mar;
+        fit += ret;
+      }
     }
-    fitness[i - i0] = (float)(fit / (double)E);
+    fitness[i - i0] = (float)(fit / ((double)E * (double)K));
     free(theta_i);
     free(s0);
   }
@@ -405,7 +413,7 @@ void orc_update(const orc_config *cfg, uint64_t adam_step, const float *noise, c
 
 /* ------------------------------------------------------------------ */
 /* Sibling evolution strategies on the same sampling and evaluation     */
-/* (paper Sec. 4.2 lists ARS and VanillaES beside OpenES; App. B        */
+/* (paper Sec. 4 lists ARS and VanillaES beside OpenES; App. B        */
 /* Table 5(a): ARS, 16 elites, SGD, learning rate 0.02, noise std 0.03; */
 /* Table 5(c): VanillaES, 16 elites, noise std 0.02).  The paper        */
 /* delegates both algorithms to their publications; what is written     */

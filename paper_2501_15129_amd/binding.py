@@ -29,6 +29,7 @@ class EsConfig(C.Structure):
         ("seed", C.c_uint64),
         ("algorithm", C.c_uint32), ("num_elites", C.c_uint32), ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32),
         ("noise_table_len", C.c_uint64),
+        ("episodes_per_env", C.c_uint32),
     ]
 
 
@@ -78,7 +79,8 @@ def make_config(w) -> EsConfig:
                     act_cost=w.act_cost, seed=w.seed,
                     algorithm=getattr(w, "algorithm", 0), num_elites=getattr(w, "num_elites", 0),
                     hidden_act=getattr(w, "hidden_act", 0), num_hidden=getattr(w, "num_hidden", 2),
-                    noise_table_len=getattr(w, "noise_table_len", 0))
+                    noise_table_len=getattr(w, "noise_table_len", 0),
+                    episodes_per_env=getattr(w, "episodes", 1))
 
 
 def _stream() -> int:
@@ -117,6 +119,7 @@ class EsContext:
         self.noise_torch_dtype = torch.bfloat16 if self.cfg.noise_dtype == 1 else torch.float32
         self.noise_regenerated = self.cfg.noise_dtype in (2, 3)     # no matrix: every `noise` argument is None
         self.noise_table = self.cfg.noise_dtype >= 4                # `noise` is a raw byte buffer: table | row offsets
+        self.episodes = self.cfg.envs_per_ind * max(1, self.cfg.episodes_per_env)   # E: columns of returns / ep_len
 
     def close(self):
         if getattr(self, "_h", None):
@@ -172,8 +175,8 @@ class EsContext:
             self._h, generation, _ptr(theta, f32, self.param_count, "theta"),
             self._noise_ptr(noise, n),
             _ptr(a_mat, f32, c.obs_dim * c.obs_dim, "A"), _ptr(b_mat, f32, c.obs_dim * c.act_dim, "B"),
-            _ptr(returns, f32, c.pop * c.envs_per_ind, "returns"),
-            _ptr(ep_len, torch.int32, c.pop * c.envs_per_ind, "ep_len"),
+            _ptr(returns, f32, c.pop * self.episodes, "returns"),
+            _ptr(ep_len, torch.int32, c.pop * self.episodes, "ep_len"),
             _ptr(fitness, f32, c.pop, "fitness"),
             _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
 

@@ -67,7 +67,8 @@ int es_create(const es_config* cfg, es_ctx** out) {
   const uint64_t m = c.num_hidden ? c.num_hidden : 2;
   if (m > 64) return bad("num_hidden must be at most 64");
   const uint64_t D = (o + 1) * h + (m - 1) * (h + 1) * h + (h + 1) * a;
-  if (D > (1ull << 30) || (uint64_t)c.pop * c.envs_per_ind > (1ull << 30) || c.obs_dim > 65535 || c.hid_dim > 65535)
+  const uint64_t episodes = (uint64_t)c.envs_per_ind * (c.episodes_per_env ? c.episodes_per_env : 1u);
+  if (D > (1ull << 30) || (uint64_t)c.pop * episodes > (1ull << 30) || c.obs_dim > 65535 || c.hid_dim > 65535)
     return bad("shape too large");
 
   es_ctx* ctx = new (std::nothrow) es_ctx();
@@ -75,7 +76,7 @@ int es_create(const es_config* cfg, es_ctx** out) {
   ctx->cfg = c;
   ctx->cfg.num_hidden = (uint32_t)m;
   Shape& s = ctx->shp;
-  s.N = c.pop; s.E = c.envs_per_ind; s.T = c.horizon; s.no = c.obs_dim; s.nh = c.hid_dim; s.na = c.act_dim;
+  s.N = c.pop; s.E = (uint32_t)episodes; s.T = c.horizon; s.no = c.obs_dim; s.nh = c.hid_dim; s.na = c.act_dim;
   s.D = (uint32_t)D;
   s.ld = (s.D + NOISE_LD_ALIGN - 1) / NOISE_LD_ALIGN * NOISE_LD_ALIGN;
   s.rows = c.antithetic ? c.pop / 2 : c.pop;

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void rank_kernel(const float* __restrict__ fit
   }
 }
 
-// ---- selection steps of the sibling strategies (paper Sec. 4.2; App. B Tables 5a, 5c) ----
+// ---- selection steps of the sibling strategies (paper Sec. 4; App. B Tables 5a, 5c) ----
 // Populations of these strategies are small (the paper uses 128), so one workgroup does the
 // whole step: keys in LDS, each thread ranks its own entries against all others (integer
 // compares, bit-exact), binary64 sums are reduced through LDS in a fixed tree order.

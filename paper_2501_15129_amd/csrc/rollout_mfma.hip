@@ -1,6 +1,6 @@
 // es_rollout, register-resident MFMA variant for bf16 policies with a wide hidden layer.
 //
-// Paper Sec. 3.3 (population x environment-copy evaluation) and Sec. 5.1/5.2 (two hidden
+// Paper Sec. 3.2 (population x environment-copy evaluation) and Sec. 5.1/5.2 (two hidden
 // layers of 256 units, fitness = mean undiscounted return).  One workgroup of four
 // wavefronts evaluates one individual at a time on up to 16 environment copies per pass:
 //

@@ -1,6 +1,6 @@
 // es_rollout, general variant: one wavefront per (individual, environment copy).
 //
-// Paper Sec. 3.3: every individual of the population is evaluated at once, each on several
+// Paper Sec. 3.2: every individual of the population is evaluated at once, each on several
 // parallel environment copies; Sec. 5.2: deterministic two-hidden-layer MLP policy, fitness
 // = mean undiscounted episodic return.  This variant handles any layer widths whose
 // perturbed weights fit in LDS (binary32, or bf16 bit patterns in bf16 mode): the

@@ -1,6 +1,6 @@
 // es_rollout, register-resident binary32 variant for narrow policies (hidden width <= 64).
 //
-// Paper Sec. 3.3 / 5.2: population x environment-copy evaluation of a deterministic
+// Paper Sec. 3.2 / 5.2: population x environment-copy evaluation of a deterministic
 // two-hidden-layer MLP policy, fitness = mean undiscounted return.  One wavefront runs one
 // (individual, environment copy) episode; lane u owns hidden unit u.  The individual's
 // perturbed weights (theta + sign*sigma*eps, fused into the load) and the environment

@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void grad_regen_kernel(const float* __restrict
   for (int k = 0; k < 4; ++k) out[k] = acc[k];
 }
 
-// The parameter step that follows the noise reduction, per strategy (paper Sec. 4.2, App. B Table 5):
+// The parameter step that follows the noise reduction, per strategy (paper Sec. 4, App. B Table 5):
 // OpenES = Adam on -g + weight_decay * theta; ARS and VanillaES = theta + step * g, no optimiser state.
 struct AdamArgs {
   double inv_scale;      // the reduced sum is divided by this: N sigma (OpenES), b (ARS), 1 / sigma (VanillaES)

@@ -21,7 +21,7 @@ import numpy as np
 
 @dataclass(frozen=True)
 class Workload:
-    """Static description of one OpenES generation (paper Sec. 3.3, 5.1, App. B Table 5b)."""
+    """Static description of one OpenES generation (paper Sec. 3.2, 5.1, App. B Table 5b)."""
     name: str
     pop: int            # N, population size
     envs: int           # E, environment copies (episodes) per individual
@@ -42,11 +42,12 @@ class Workload:
     act_cost: float = 0.01
     antithetic: int = 1
     out_tanh: int = 1
-    algorithm: int = 0  # 0 OpenES ; 1 ARS ; 2 VanillaES (paper Sec. 4.2)
+    algorithm: int = 0  # 0 OpenES ; 1 ARS ; 2 VanillaES (paper Sec. 4)
     num_elites: int = 0 # ARS: directions kept ; VanillaES: parents
     hidden_act: int = 0 # hidden-layer activation: 0 tanh ; 1 ReLU (paper App. B)
     num_hidden: int = 2 # m hidden layers of width hid (paper Sec. 5.1 varies m; base case 2)
     noise_table_len: int = 0  # entries of the shared noise table (noise_dtype 4, 5; paper Sec. 5.1)
+    episodes: int = 1   # episodes run back to back in every environment copy (auto-reset; paper Sec. 3.1)
 
     @property
     def n_params(self) -> int:
@@ -59,7 +60,7 @@ class Workload:
 
     @property
     def env_steps(self) -> int:
-        return self.pop * self.envs * self.horizon
+        return self.pop * self.envs * self.episodes * self.horizon
 
     def fixed_length(self) -> "Workload":
         """Same workload with the termination rule switched off (every episode runs T steps)."""

@@ -41,8 +41,8 @@ def dev(x, dtype=None):
 
 
 def run_rollout(ctx, w, gen, theta, noise_dev, a_mat, b_mat):
-    ret = torch.full((w.pop, w.envs), float("nan"), dtype=torch.float32, device="cuda")
-    ln = torch.full((w.pop, w.envs), -1, dtype=torch.int32, device="cuda")
+    ret = torch.full((w.pop, ctx.episodes), float("nan"), dtype=torch.float32, device="cuda")
+    ln = torch.full((w.pop, ctx.episodes), -1, dtype=torch.int32, device="cuda")
     fit = torch.full((w.pop,), float("nan"), dtype=torch.float32, device="cuda")
     ws = ctx.alloc_workspace()
     ctx.rollout(gen, dev(theta), noise_dev, dev(a_mat), dev(b_mat), ret, ln, fit, ws)

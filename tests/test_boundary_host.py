@@ -38,7 +38,7 @@ def test_config_struct_matches_header(binding):
     for decl in re.findall(r"(?:uint32_t|uint64_t|float)\s+([^;]+);", struct):
         names += [n.strip() for n in decl.split(",")]
     assert names == [n for n, _ in binding.EsConfig._fields_]
-    assert C.sizeof(binding.EsConfig) == 104       # 10 u32 + 8 f32 + u64 + 4 u32 + u64
+    assert C.sizeof(binding.EsConfig) == 112       # 10 u32 + 8 f32 + u64 + 4 u32 + u64 + u32 + padding
 
 
 def test_context_queries(binding):

@@ -357,3 +357,44 @@ def test_depth_identity_layer_changes_nothing():
     r2, _, _, _ = oracle.rollout(w2, 0, theta2, np.zeros((w2.noise_rows, w2.n_params), np.float32), a_mat, b_mat)
     r3, _, _, _ = oracle.rollout(w3, 0, theta3, np.zeros((w3.noise_rows, w3.n_params), np.float32), a_mat, b_mat)
     assert np.array_equal(r2, r3)
+
+
+# ---- k episodes per environment copy (the auto-reset wrapper of the paper's Sec. 3.1) ----
+def test_episodes_per_env_library_forward_order_and_mean():
+    k = 3
+    w = replace(W, horizon=12, done_thresh=0.6, episodes=k)
+    a_mat, b_mat, theta = make_inputs(w)
+    a_mat = (2.0 * a_mat).astype(np.float32)              # lively dynamics: episodes end at different lengths
+    eps = oracle.sample_population(w, 2)
+    ret, ln, fit, _ = oracle.rollout(w, 2, theta, eps, a_mat, b_mat)
+    assert ret.shape == (w.pop, w.envs * k) and ln.shape == ret.shape
+    a64, b64 = a_mat.astype(np.float64), b_mat.astype(np.float64)
+    for i in (1, 4):
+        th = oracle.perturb(w, theta, eps, i)
+        for e in range(w.envs):
+            for p in range(k):                             # every episode of the copy starts from a reset of its own
+                s = oracle.reset(w, 2, e * k + p).astype(np.float64)
+                total, t = 0.0, 0
+                while True:
+                    act = _policy_torch(w, th, s)
+                    total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
+                    s = np.tanh(a64 @ s + b64 @ act)
+                    t += 1
+                    if np.max(np.abs(s)) > np.float32(w.done_thresh) or t == w.horizon:
+                        break
+                assert ln[i, e * k + p] == t and abs(ret[i, e * k + p] - total) < 1e-5
+    assert len(np.unique(ln)) > 2                          # the rule did cut episodes, at different steps
+    np.testing.assert_allclose(fit, ret.astype(np.float64).mean(axis=1), rtol=1e-6)
+
+
+def test_episodes_per_env_equals_that_many_copies():
+    # the episodes of a copy share nothing but the copy's slot, so k episodes in E copies are E * k copies
+    a_mat, b_mat, theta = make_inputs(W)
+    eps = oracle.sample_population(W, 0)
+    seq = oracle.rollout(replace(W, envs=2, episodes=3), 0, theta, eps, a_mat, b_mat)
+    par = oracle.rollout(replace(W, envs=6, episodes=1), 0, theta, eps, a_mat, b_mat)
+    for x, y in zip(seq, par):
+        assert np.array_equal(x, y)
+    one = oracle.rollout(replace(W, episodes=0), 0, theta, eps, a_mat, b_mat)      # 0 means 1
+    for x, y in zip(one, oracle.rollout(W, 0, theta, eps, a_mat, b_mat)):
+        assert np.array_equal(x, y)

@@ -1,4 +1,4 @@
-"""Pins for the checker's ARS and VanillaES steps (paper Sec. 4.2, App. B Tables 5(a) and 5(c);
+"""Pins for the checker's ARS and VanillaES steps (paper Sec. 4, App. B Tables 5(a) and 5(c);
 algorithms as published by Mania et al. 2018 and Chrabaszcz et al. 2018).  Each test ties the
 checker to something other than itself: a hand-worked example, an invariance the mathematics
 fixes, a matrix closed form evaluated with a library product, or a direct evaluation of the
