@@ -218,6 +218,22 @@ int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float*
               float* theta_d, float* m_d, float* v_d, float* grad_d, void* workspace_d,
               void* stream);
 
+/*
+ * One whole generation - the four calls above in their order, es_sample_population(generation),
+ * es_rollout(generation), es_rank, es_update(adam_step), enqueued on `stream` by one call: the
+ * counterpart of the paper's Workflow.step() running as one device program (Sec. 3.1, 3.2).
+ * Arguments mean what they mean in the stage calls (noise_d NULL with regenerated noise; m_d, v_d
+ * NULL allowed for ES_ARS / ES_VANILLA; grad_d optional); results are bit-identical to the four
+ * separate calls.  All arguments of all stages are checked before the first launch, so a failing
+ * call enqueues nothing.  The call neither allocates nor synchronises nor clears memory with
+ * memset nodes, so a caller may record it into a HIP graph (stream capture) and replay it; a
+ * replay repeats the recorded generation and adam_step numbers.
+ */
+int es_generation(es_ctx* ctx, uint64_t generation, uint64_t adam_step, void* noise_d,
+                  const float* A_d, const float* B_d, float* theta_d, float* m_d, float* v_d,
+                  float* returns_d, int32_t* ep_len_d, float* fitness_d, int32_t* rank_d,
+                  float* shaped_d, float* grad_d, void* workspace_d, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -64,6 +64,7 @@ def load_library() -> C.CDLL:
     lib.es_rollout.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.es_rank.argtypes = [vp, vp, vp, vp, vp]
     lib.es_update.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.es_generation.argtypes = [vp, u64, u64] + [vp] * 14
     return lib
 
 
@@ -193,6 +194,18 @@ class EsContext:
             _ptr(shaped, f32, self.cfg.pop, "shaped"), _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"),
             _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"),      # m, v may be None for ARS / VanillaES
             _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
+
+    def generation(self, generation: int, adam_step: int, noise, a_mat, b_mat, theta, m, v, returns, ep_len, fitness,
+                   rank, shaped, grad, workspace):
+        c = self.cfg
+        f32, i32, d, n = torch.float32, torch.int32, self.param_count, self.noise_rows * self.noise_ld
+        self._check(_lib.es_generation(
+            self._h, generation, adam_step, self._noise_ptr(noise, n),
+            _ptr(a_mat, f32, c.obs_dim * c.obs_dim, "A"), _ptr(b_mat, f32, c.obs_dim * c.act_dim, "B"),
+            _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"), _ptr(v, f32, d, "v"),
+            _ptr(returns, f32, c.pop * self.episodes, "returns"), _ptr(ep_len, i32, c.pop * self.episodes, "ep_len"),
+            _ptr(fitness, f32, c.pop, "fitness"), _ptr(rank, i32, c.pop, "rank"), _ptr(shaped, f32, c.pop, "shaped"),
+            _ptr(grad, f32, d, "grad"), _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
 
 
 def raw_library() -> C.CDLL:

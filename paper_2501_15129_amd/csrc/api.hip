@@ -161,61 +161,109 @@ int es_build_noise_table(es_ctx* ctx, void* noise_d, void* stream) {
   return launch_table(ctx, noise_d, static_cast<hipStream_t>(stream));
 }
 
-int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {
-  if (!ctx) return ES_EINVAL;
+// Argument checks of the four stages, shared by the stage calls and es_generation (which must
+// reject a bad argument of a later stage before it has enqueued an earlier one).
+static bool regenerated(const es_ctx* ctx) { return ctx->cfg.noise_dtype == 2 || ctx->cfg.noise_dtype == 3; }
+
+static int check_sample(es_ctx* ctx, uint64_t generation, const void* noise_d) {
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_sample_population: generation must be < 2^32");
-  if (ctx->cfg.noise_dtype == 2 || ctx->cfg.noise_dtype == 3) {     // nothing to store: remember which generation es_update regenerates
-    ctx->regen_generation = (uint32_t)generation;
+  if (!regenerated(ctx) && !noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
+  return ES_OK;
+}
+
+static int check_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const void* noise_d, const float* A_d,
+                         const float* B_d, const float* returns_d, const int32_t* ep_len_d, const float* fitness_d,
+                         const void* workspace_d) {
+  if (!theta_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d || (!noise_d && !regenerated(ctx)))
+    return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
+  if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
+  if (ctx->rollout_kind == ROLLOUT_WAVE_LDS && ctx->lds_bytes_wave > (size_t)ctx->lds_limit)
+    return fail(ctx, ES_EUNSUPPORTED, "es_rollout: perturbed parameters of one individual (" +
+                                          std::to_string(ctx->lds_bytes_wave) + " B) exceed the LDS of a workgroup (" +
+                                          std::to_string(ctx->lds_limit) + " B) and no register-resident kernel is built for this shape");
+  return ES_OK;
+}
+
+static int check_rank(es_ctx* ctx, const float* fitness_d, const int32_t* rank_d, const float* shaped_d) {
+  if (!fitness_d || !rank_d || !shaped_d) return fail(ctx, ES_EINVAL, "es_rank: null device pointer");
+  return ES_OK;
+}
+
+static int check_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, const float* theta_d,
+                        const float* m_d, const float* v_d, const void* workspace_d, bool sampled) {
+  if (!shaped_d || !theta_d || !workspace_d || (!noise_d && !regenerated(ctx)) ||
+      ((!m_d || !v_d) && ctx->cfg.algorithm == ES_OPENES))
+    return fail(ctx, ES_EINVAL, "es_update: null device pointer");
+  if (regenerated(ctx) && !sampled)
+    return fail(ctx, ES_EINVAL, "es_update: with regenerated noise, es_sample_population must name the generation first");
+  if (adam_step < 1 && ctx->cfg.algorithm == ES_OPENES) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
+  if (!(ctx->cfg.sigma > 0.0f)) return fail(ctx, ES_EINVAL, "es_update: sigma must be > 0");
+  return ES_OK;
+}
+
+static int enqueue_sample(es_ctx* ctx, uint32_t generation, void* noise_d, hipStream_t st) {
+  if (regenerated(ctx)) {            // nothing to store: remember which generation es_update regenerates
+    ctx->regen_generation = generation;
     ctx->regen_valid = true;
     return ES_OK;
   }
-  if (!noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
-  if (ctx->cfg.noise_dtype >= 4)
-    return launch_table_offsets(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
-  return launch_sample(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
+  if (ctx->cfg.noise_dtype >= 4) return launch_table_offsets(ctx, generation, noise_d, st);
+  return launch_sample(ctx, generation, noise_d, st);
+}
+
+static int enqueue_rollout(es_ctx* ctx, uint32_t generation, const float* theta_d, const void* noise_d, const float* A_d,
+                           const float* B_d, float* returns_d, int32_t* ep_len_d, float* fitness_d, void* workspace_d,
+                           hipStream_t st) {
+  if (ctx->rollout_kind == ROLLOUT_WAVE_REG)
+    return launch_rollout_reg(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);
+  if (ctx->rollout_kind == ROLLOUT_MFMA_REG)
+    return launch_rollout_mfma(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);
+  return launch_rollout_wave(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);
+}
+
+int es_sample_population(es_ctx* ctx, uint64_t generation, void* noise_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (int rc = check_sample(ctx, generation, noise_d)) return rc;
+  return enqueue_sample(ctx, (uint32_t)generation, noise_d, static_cast<hipStream_t>(stream));
 }
 
 int es_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d, const void* noise_d, const float* A_d,
                const float* B_d, float* returns_d, int32_t* ep_len_d, float* fitness_d, void* workspace_d,
                void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!theta_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d ||
-      (!noise_d && ctx->cfg.noise_dtype != 2 && ctx->cfg.noise_dtype != 3))
-    return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
-  if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (ctx->rollout_kind == ROLLOUT_WAVE_REG)
-    return launch_rollout_reg(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
-                              fitness_d, workspace_d, st);
-  if (ctx->rollout_kind == ROLLOUT_MFMA_REG)
-    return launch_rollout_mfma(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
-                               fitness_d, workspace_d, st);
-  if (ctx->lds_bytes_wave > (size_t)ctx->lds_limit)
-    return fail(ctx, ES_EUNSUPPORTED, "es_rollout: perturbed parameters of one individual (" +
-                                          std::to_string(ctx->lds_bytes_wave) + " B) exceed the LDS of a workgroup (" +
-                                          std::to_string(ctx->lds_limit) + " B) and no register-resident kernel is built for this shape");
-  return launch_rollout_wave(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d,
-                             fitness_d, workspace_d, st);
+  if (int rc = check_rollout(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d)) return rc;
+  return enqueue_rollout(ctx, (uint32_t)generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d,
+                         static_cast<hipStream_t>(stream));
 }
 
 int es_rank(es_ctx* ctx, const float* fitness_d, int32_t* rank_d, float* shaped_d, void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!fitness_d || !rank_d || !shaped_d) return fail(ctx, ES_EINVAL, "es_rank: null device pointer");
+  if (int rc = check_rank(ctx, fitness_d, rank_d, shaped_d)) return rc;
   return launch_rank(ctx, fitness_d, rank_d, shaped_d, static_cast<hipStream_t>(stream));
 }
 
 int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, float* theta_d,
               float* m_d, float* v_d, float* grad_d, void* workspace_d, void* stream) {
   if (!ctx) return ES_EINVAL;
-  if (!shaped_d || !theta_d || !workspace_d || (!noise_d && ctx->cfg.noise_dtype != 2 && ctx->cfg.noise_dtype != 3) ||
-      ((!m_d || !v_d) && ctx->cfg.algorithm == ES_OPENES))
-    return fail(ctx, ES_EINVAL, "es_update: null device pointer");
-  if ((ctx->cfg.noise_dtype == 2 || ctx->cfg.noise_dtype == 3) && !ctx->regen_valid)
-    return fail(ctx, ES_EINVAL, "es_update: with regenerated noise, es_sample_population must name the generation first");
-  if (adam_step < 1 && ctx->cfg.algorithm == ES_OPENES) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");
-  if (!(ctx->cfg.sigma > 0.0f)) return fail(ctx, ES_EINVAL, "es_update: sigma must be > 0");
+  if (int rc = check_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, workspace_d, ctx->regen_valid)) return rc;
   return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, workspace_d,
                        static_cast<hipStream_t>(stream));
+}
+
+int es_generation(es_ctx* ctx, uint64_t generation, uint64_t adam_step, void* noise_d, const float* A_d, const float* B_d,
+                  float* theta_d, float* m_d, float* v_d, float* returns_d, int32_t* ep_len_d, float* fitness_d,
+                  int32_t* rank_d, float* shaped_d, float* grad_d, void* workspace_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (int rc = check_sample(ctx, generation, noise_d)) return rc;
+  if (int rc = check_rollout(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d)) return rc;
+  if (int rc = check_rank(ctx, fitness_d, rank_d, shaped_d)) return rc;
+  if (int rc = check_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, workspace_d, true)) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const uint32_t gen = (uint32_t)generation;
+  if (int rc = enqueue_sample(ctx, gen, noise_d, st)) return rc;
+  if (int rc = enqueue_rollout(ctx, gen, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st)) return rc;
+  if (int rc = launch_rank(ctx, fitness_d, rank_d, shaped_d, st)) return rc;
+  return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, workspace_d, st);
 }
 
 }  // extern "C"

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol(binding):
     header = (ROOT / "include" / "es.h").read_text()
     body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(es_[a-z_]+)\s*\(", body))
-    assert {"es_create", "es_destroy", "es_sample_population", "es_rollout", "es_rank", "es_update"} <= declared
+    assert {"es_create", "es_destroy", "es_sample_population", "es_rollout", "es_rank", "es_update", "es_generation"} <= declared
     lib = binding.raw_library()
     for name in sorted(declared):
         assert hasattr(lib, name), f"libes_hip.so does not export {name}"

@@ -27,8 +27,8 @@ class GpuChain:
         self.noise, self.ws = self.ctx.alloc_noise(), self.ctx.alloc_workspace()
         self.theta, self.m, self.v = dev(theta), torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda")
         self.a, self.b = dev(a_mat), dev(b_mat)
-        self.ret = torch.empty((w.pop, w.envs), device="cuda")
-        self.len = torch.empty((w.pop, w.envs), dtype=torch.int32, device="cuda")
+        self.ret = torch.empty((w.pop, self.ctx.episodes), device="cuda")
+        self.len = torch.empty((w.pop, self.ctx.episodes), dtype=torch.int32, device="cuda")
         self.fit = torch.empty(w.pop, device="cuda")
         self.rank = torch.empty(w.pop, dtype=torch.int32, device="cuda")
         self.shaped = torch.empty(w.pop, device="cuda")
@@ -39,6 +39,10 @@ class GpuChain:
         c.rollout(g, self.theta, self.noise, self.a, self.b, self.ret, self.len, self.fit, self.ws)
         c.rank(self.fit, self.rank, self.shaped)
         c.update(g + 1, self.noise, self.shaped, self.theta, self.m, self.v, None, self.ws)
+
+    def generation_one_call(self, g):
+        self.ctx.generation(g, g + 1, self.noise, self.a, self.b, self.theta, self.m, self.v, self.ret, self.len,
+                            self.fit, self.rank, self.shaped, None, self.ws)
 
     def state(self):
         torch.cuda.synchronize()
@@ -102,3 +106,78 @@ def test_rerun_and_resume_are_bit_identical(es):
         second.generation(g)
     for x, y in zip(want, second.state()):
         assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
+ONE_CALL = [
+    CONFIGS[0],
+    replace(CONFIGS[0], name="cfg0-k2", episodes=2),
+    replace(CONFIGS[0], name="cfg0-regen", noise_dtype=2),
+    replace(CONFIGS[0], name="cfg0-table", noise_dtype=4, noise_table_len=1 << 16),
+    replace(CONFIGS[0], name="cfg0-ars", algorithm=1, num_elites=2, lr=0.02, sigma=0.03),
+    replace(CONFIGS[0], name="cfg0-vanilla", algorithm=2, num_elites=3, antithetic=0),
+    Workload("one-bf16", pop=8, envs=4, horizon=30, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=7),
+    Workload("one-depth3", pop=6, envs=2, horizon=30, obs=11, hid=24, act=3, dtype=0, noise_dtype=0, seed=8, num_hidden=3),
+]
+
+
+@pytest.mark.parametrize("w", ONE_CALL, ids=lambda w: w.name)
+def test_generation_in_one_call_equals_the_four_calls(es, w):
+    a_mat, b_mat, theta = make_inputs(w)
+    four, one = GpuChain(es, w, theta, a_mat, b_mat), GpuChain(es, w, theta, a_mat, b_mat)
+    for c in (four, one):
+        if c.ctx.noise_table:
+            c.ctx.build_noise_table(c.noise)
+    for g in range(3):
+        four.generation(g)
+        one.generation_one_call(g)
+    torch.cuda.synchronize()
+    for name in ("theta", "m", "v", "ret", "len", "fit", "rank", "shaped"):
+        x, y = getattr(four, name).cpu().numpy(), getattr(one, name).cpu().numpy()
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), name
+    assert not np.array_equal(one.theta.cpu().numpy(), theta)
+
+
+def test_generation_call_checks_every_stage_before_launching(es):
+    w = CONFIGS[0]
+    a_mat, b_mat, theta = make_inputs(w)
+    run = GpuChain(es, w, theta, a_mat, b_mat)
+    run.fit.fill_(-7.0)
+    torch.cuda.synchronize()
+    with pytest.raises(es.EsError, match="adam_step"):          # the last stage's argument is wrong: nothing may run
+        run.ctx.generation(0, 0, run.noise, run.a, run.b, run.theta, run.m, run.v, run.ret, run.len, run.fit, run.rank,
+                           run.shaped, None, run.ws)
+    with pytest.raises(es.EsError, match="es_rank"):
+        run.ctx.generation(0, 1, run.noise, run.a, run.b, run.theta, run.m, run.v, run.ret, run.len, run.fit, None,
+                           run.shaped, None, run.ws)
+    torch.cuda.synchronize()
+    assert np.all(run.fit.cpu().numpy() == -7.0) and np.array_equal(run.theta.cpu().numpy(), theta)
+
+
+@pytest.mark.parametrize("w", [CONFIGS[0], Workload("graph-bf16", pop=8, envs=4, horizon=30, obs=27, hid=256, act=8, dtype=1,
+                                                    noise_dtype=1, seed=7)], ids=lambda w: w.name)
+def test_generation_call_recorded_in_a_graph_replays_exactly(es, w):
+    """The one-call generation under stream capture: every replay, with eager work and synchronisation in
+    between, must reproduce the eager result of the recorded generation."""
+    a_mat, b_mat, theta = make_inputs(w)
+    eager = GpuChain(es, w, theta, a_mat, b_mat)
+    eager.generation_one_call(5)
+    want = eager.state()
+    run = GpuChain(es, w, theta, a_mat, b_mat)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run.generation_one_call(5)              # first launch outside the capture (one-time kernel attributes)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run.generation_one_call(5)
+    for replay in range(4):
+        run.theta.copy_(dev(theta)); run.m.zero_(); run.v.zero_()
+        run.fit.fill_(float("nan")); run.ret.fill_(float("nan")); run.noise.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = run.state()
+        for x, y in zip(want, got):
+            assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), f"replay {replay}"
+        eager.generation_one_call(6 + replay)   # the program's own eager work between replays
+        torch.cuda.synchronize()
