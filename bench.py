@@ -32,7 +32,7 @@ REGEN_VALU_OPS_PER_BLOCK = 245  # vector instructions per Philox block + two Gau
 def flop_per_env_step(w) -> int:
     """Multiply-add flops of one policy forward plus one environment step (2 flop per MAC)."""
     o, h, a = w.obs, w.hid, w.act
-    return 2 * (o * h + h * h + h * a) + 2 * (o * o + o * a)
+    return 2 * (o * h + (w.num_hidden - 1) * h * h + h * a) + 2 * (o * o + o * a)
 
 
 def update_bytes(w, ctx) -> int:
@@ -137,6 +137,7 @@ def main() -> int:
                     help="hidden-layer activation (the paper's EA experiments use ReLU MLPs, App. B)")
     ap.add_argument("--obs-norm", action="store_true",
                     help="frozen observation statistics for the policy input (paper App. B); synthetic: mean N(0, 0.05^2), std U[0.33, 1]")
+    ap.add_argument("--num-hidden", type=int, default=2, help="m hidden layers (paper Sec. 5.1 varies m); not the default workload")
     ap.add_argument("--episodes-per-env", type=int, default=1,
                     help="k episodes per environment copy (auto-reset wrapper, paper Sec. 3.1); not the default workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -177,6 +178,8 @@ def main() -> int:
         base = replace(base, name=base.name + "-ars", algorithm=1, num_elites=max(1, base.pop // 8), lr=0.02, sigma=0.03)
     elif args.algorithm == "vanilla":
         base = replace(base, name=base.name + "-vanilla", algorithm=2, num_elites=max(1, base.pop // 8), antithetic=0)
+    if args.num_hidden != 2:
+        base = replace(base, name=base.name + f"-m{args.num_hidden}", num_hidden=args.num_hidden)
     if args.episodes_per_env != 1:
         base = replace(base, name=base.name + f"-k{args.episodes_per_env}", episodes=args.episodes_per_env)
     w = base if args.done_rule else base.fixed_length()
@@ -225,7 +228,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm and args.episodes_per_env == 1 else None) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm and args.episodes_per_env == 1 and args.num_hidden == 2 else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
@@ -245,7 +248,7 @@ def main() -> int:
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs{'' if w.episodes == 1 else ' x %d episodes each' % w.episodes}, T={w.horizon}, MLP {w.obs}-{w.hid}-{w.hid}-{w.act} {args.hidden_act}, "
+        "config": {"workload": f"{base.name}: pop {w.pop} x {w.envs} envs{'' if w.episodes == 1 else ' x %d episodes each' % w.episodes}, T={w.horizon}, MLP {w.obs}-{'-'.join([str(w.hid)] * w.num_hidden)}-{w.act} {args.hidden_act}, "
                                f"{'bf16 operands / fp32 accumulate' if bf16 else 'fp32'}, "
                                f"{'termination rule on (live env-steps counted)' if args.done_rule else 'fixed-length episodes (paper Sec. 5.1 protocol)'}",
                    "population": w.pop, "envs_per_individual": w.envs, "episodes_per_env": w.episodes, "horizon": w.horizon, "params": w.n_params,

@@ -103,6 +103,7 @@ int es_create(const es_config* cfg, es_ctx** out) {
   } else if (ctx->mfma_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_MFMA_REG;
     ctx->kernel_name = mfma_variant_name(ctx->mfma_variant);
+    if (m != 2) ctx->kernel_name += ",depth" + std::to_string(m);
   } else {
     ctx->rollout_kind = ROLLOUT_WAVE_LDS;
     ctx->kernel_name = c.dtype == 1 ? "rollout_wave_lds_bf16" : "rollout_wave_lds_f32";

@@ -57,8 +57,9 @@ constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activ
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
-template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_, int NW_, int OCC_ = 1>
+template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_, int NW_, int OCC_ = 1, int ME_ = 0>
 struct Variant {
+  static constexpr int ME = ME_;              // hidden layers beyond the second (depth m = 2 + ME), each 256 x 256 in registers
   static constexpr int OCC = OCC_;            // workgroups per CU the register budget is sized for (1 or 2)
   static constexpr int NW = NW_;              // wavefronts per workgroup: 4 (one per SIMD) or 8 (two per SIMD)
   static constexpr int NT = 64 * NW;          // threads per workgroup
@@ -101,7 +102,9 @@ struct Variant {
   static constexpr int OFF_SS0 = OFF_X0 + 2 * NC * PX;
   // only used with observation statistics: the normalised state (the policy's operand), its cached
   // initial value, and the statistics themselves
-  static constexpr int OFF_XP = OFF_SS0 + 4 * 16;
+  static constexpr int OFF_BX = OFF_SS0 + 4 * 16;              // biases of the extra hidden layers [ME][NHP]
+  static constexpr int OFF_HL = (ME & 1) ? OFF_H1 : OFF_H2;   // the last hidden layer's activations (the layers ping-pong)
+  static constexpr int OFF_XP = OFF_BX + 4 * NHP * ME;
   static constexpr int OFF_X0P = OFF_XP + 2 * NC * PX;
   static constexpr int OFF_MU = OFF_X0P + 2 * NC * PX;
   static constexpr int OFF_IV = OFF_MU + 4 * NOP;
@@ -113,6 +116,7 @@ struct Variant {
   static_assert(NAP >= 16 * MT3 && KTA <= KC, "action K padding");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
   static_assert(NC == 4 || NC == 16, "columns per pass");
+  static_assert(ME == 0 || (OCC == 1 && KTAL == 0), "deeper policies need the whole register file of the CU");
   static_assert(MT3 <= 2 && MT3 <= 4, "action tiles: one wavefront each, partial layout holds two");
 };
 
@@ -301,6 +305,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   float* b1s = reinterpret_cast<float*>(lds + V::OFF_B1);
   float* b2s = reinterpret_cast<float*>(lds + V::OFF_B2);
   float* b3s = reinterpret_cast<float*>(lds + V::OFF_B3);
+  float* bxs = reinterpret_cast<float*>(lds + V::OFF_BX);
+  constexpr int ME = V::ME;
   uint16_t* x0s = reinterpret_cast<uint16_t*>(lds + V::OFF_X0);
   float* ss0s = reinterpret_cast<float*>(lds + V::OFF_SS0);
   uint16_t* x0ps = reinterpret_cast<uint16_t*>(lds + V::OFF_X0P);
@@ -358,7 +364,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       else if (a.noise_mode == 0u) nz.ptr = static_cast<const float*>(a.noise) + (size_t)unit * a.ld;
 
       // ---------------- perturbed policy weights -> registers ----------------
-      bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H];
+      bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H], Wxr[ME > 0 ? ME : 1][MT_H][KT_H];
       for (int u = tid; u < NHP; u += NT) {     // biases: perturbed, bf16-rounded, kept as binary32
         float v1 = 0.0f, v2 = 0.0f;
         if (u < nh) {
@@ -369,6 +375,15 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         }
         b1s[u] = v1;
         b2s[u] = v2;
+#pragma unroll
+        for (int j = 0; j < ME; ++j) {          // hidden layer 3 + j: matrix, then bias, after layer 2's
+          float vx = 0.0f;
+          if (u < nh) {
+            const uint32_t ix = a.ob2 + (uint32_t)(j + 1) * (uint32_t)(nh * nh + nh) + u;
+            vx = bf16_round(__fmaf_rn(scale, row_noise(nz, ix), a.theta[ix]));
+          }
+          bxs[j * NHP + u] = vx;
+        }
       }
       for (int c = tid; c < 16 * MT3; c += NT) {
         float v3 = 0.0f;
@@ -403,6 +418,22 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           for (int kk = 0; kk < KC; ++kk)
             W2r[t][kr * KC + kk] = lds_tile(lds, 2 * ((16 * (w * MT_H + t) + n) * PW + 32 * kk + 8 * g));
         __syncthreads();
+      }
+
+#pragma unroll
+      for (int j = 0; j < ME; ++j) {
+#pragma unroll
+        for (int kr = 0; kr < KT_H / KC; ++kr) {
+          stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, a.theta, nz, scale,
+                                    a.oW2 + (uint32_t)(j + 1) * (uint32_t)(nh * nh + nh));
+          __syncthreads();
+#pragma unroll
+          for (int t = 0; t < MT_H; ++t)
+#pragma unroll
+            for (int kk = 0; kk < KC; ++kk)
+              Wxr[j][t][kr * KC + kk] = lds_tile(lds, 2 * ((16 * (w * MT_H + t) + n) * PW + 32 * kk + 8 * g));
+          __syncthreads();
+        }
       }
 
       float fit_sum = 0.0f;
@@ -501,7 +532,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             if (kt + 2 < KT1) xfetch(kt + 2);
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
-              if (V::OCC == 1) pin_agpr(W1r[tt][kt]);    // with two workgroups per CU only the 256x256 layer fits the accumulation half
+              if (V::OCC == 1 && ME == 0) pin_agpr(W1r[tt][kt]);    // with two workgroups per CU, or deeper policies, the accumulation half belongs to the 256x256 layers
               acc[tt] = mfma16(W1r[tt][kt], (!NORM && kt < KA1) ? bx[kt < KA1 ? kt : 0] : bxr[kt % 3], acc[tt]);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -608,6 +639,39 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               }
             }
           }
+          // ---- further hidden layers (depth m > 2): the same stream, ping-ponging between the two buffers ----
+#pragma unroll
+          for (int j = 0; j < ME; ++j) {
+            const int off_in = (j & 1) ? V::OFF_H1 : V::OFF_H2, off_out = (j & 1) ? V::OFF_H2 : V::OFF_H1;
+#pragma unroll
+            for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(bxs + j * NHP + 16 * (w * MT_H + tt) + 4 * g);
+            __syncthreads();
+            bf16x8 bh[3];
+            bh[0] = lds_tile(lds, off_in + 2 * (col * PH + 8 * g));
+            bh[1] = lds_tile(lds, off_in + 2 * (col * PH + 32 + 8 * g));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kt = 0; kt < KT_H; ++kt) {
+              if (kt + 2 < KT_H) bh[(kt + 2) % 3] = lds_tile(lds, off_in + 2 * (col * PH + 32 * (kt + 2) + 8 * g));
+#pragma unroll
+              for (int tt = 0; tt < MT_H; ++tt) {
+                if (j == 0) pin_agpr(Wxr[j][tt][kt]);      // the first extra layer shares the accumulation half with layer 2
+                acc[tt] = mfma16(Wxr[j][tt][kt], bh[kt % 3], acc[tt]);
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            if (NC == 4) {
+              const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
+              if (q < MT_H)
+                *reinterpret_cast<u32x2*>(lds + off_out + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            } else {
+#pragma unroll
+              for (int tt = 0; tt < MT_H; ++tt) {
+                const f32x4 h = hidden4<RELU>(acc[tt]);
+                *reinterpret_cast<u32x2*>(lds + off_out + 2 * (n * PH + 16 * (w * MT_H + tt) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+              }
+            }
+          }
           // action-layer operands that do not depend on h2 are fetched before the barrier (split mode)
           constexpr int W3PRE = 4;       // of the KT_H weight tiles; the register file has no room for all of them
           bf16x8 w3t[V::ACT_SPLIT ? W3PRE : 1];
@@ -625,7 +689,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int kt = 0; kt < KT_H; ++kt) {
-                const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * kt + 8 * g));
+                const bf16x8 b = lds_tile(lds, V::OFF_HL + 2 * (col * PH + 32 * kt + 8 * g));
                 const bf16x8 wt = kt < W3PRE ? w3t[kt < W3PRE ? kt : 0]
                                              : lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
                 p[kt & 3] = mfma16(wt, b, p[kt & 3]);
@@ -651,7 +715,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             }
 #pragma unroll
             for (int kt = 0; kt < KT_H; ++kt) {
-              const bf16x8 b = lds_tile(lds, V::OFF_H2 + 2 * (col * PH + 32 * kt + 8 * g));
+              const bf16x8 b = lds_tile(lds, V::OFF_HL + 2 * (col * PH + 32 * kt + 8 * g));
 #pragma unroll
               for (int mt = 0; mt < MT3; ++mt) {
                 const bf16x8 wt = lds_tile(lds, V::OFF_W3 + 2 * ((16 * mt + n) * PH + 32 * kt + 8 * g));
@@ -752,6 +816,10 @@ constexpr int env_tiles(int nop, int nw) { return (nop / 16 + nw - 1) / nw > 0 ?
 template <int NC, int NW> using V32 = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2>;   // obs <= 32,  act <= 16
 template <int NC, int NW> using V64 = Variant<2, 1, env_tiles(64, NW), 2, NC, NW>;      // obs <= 64,  act <= 16
 template <int NC, int NW> using V128 = Variant<4, 2, env_tiles(128, NW), 4, NC, NW>;    // obs <= 128, act <= 32
+// Deeper policies (m = 3, 4 hidden layers) of the two narrow-observation shapes: one workgroup per CU, the
+// extra 256 x 256 layers take the registers the second workgroup would have used.
+template <int NC, int NW, int ME> using V32D = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 1, ME>;
+template <int NC, int NW, int ME> using V64D = Variant<2, 1, env_tiles(64, NW), 2, NC, NW, 1, ME>;
 template <int NC, int NW> using V256 = Variant<8, 2, env_tiles(256, NW), ES_V256_KTAR, NC, NW>;   // obs <= 256, act <= 32; part of A lives in LDS
 
 struct VariantInfo { int max_obs, max_act; const char* name; };
@@ -763,11 +831,13 @@ static const VariantInfo kVariants[] = {
 };
 
 int mfma_variant_for(const es_config& c) {
-  if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP || (c.num_hidden != 0 && c.num_hidden != 2)) return -1;
+  const uint32_t m = c.num_hidden ? c.num_hidden : 2;
+  if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP || m < 2 || m > 4) return -1;
   // narrow policies are served better by the one-wavefront-per-episode kernel when it fits
   if (c.hid_dim < 128 && wave_rollout_lds_bytes(c) <= 160 * 1024) return -1;
   for (int v = 0; v < 4; ++v)
-    if ((int)c.obs_dim <= kVariants[v].max_obs && (int)c.act_dim <= kVariants[v].max_act) return v;
+    if ((int)c.obs_dim <= kVariants[v].max_obs && (int)c.act_dim <= kVariants[v].max_act)
+      return (m > 2 && v > 1) ? -1 : v;      // three and four hidden layers: the two narrow-observation shapes only
   return -1;
 }
 
@@ -808,6 +878,14 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");
   const uint32_t units = c.antithetic ? s.N / 2 : s.N;
   const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
+  if (s.m == 3) {
+    if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32D<4, 4, 1>>(ctx, a, units, st) : launch_variant<V32D<16, 4, 1>>(ctx, a, units, st);
+    if (ctx->mfma_variant == 1) return narrow ? launch_variant<V64D<4, 4, 1>>(ctx, a, units, st) : launch_variant<V64D<16, 4, 1>>(ctx, a, units, st);
+  } else if (s.m == 4) {
+    if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32D<4, 4, 2>>(ctx, a, units, st) : launch_variant<V32D<16, 4, 2>>(ctx, a, units, st);
+    if (ctx->mfma_variant == 1) return narrow ? launch_variant<V64D<4, 4, 2>>(ctx, a, units, st) : launch_variant<V64D<16, 4, 2>>(ctx, a, units, st);
+  }
+  if (s.m != 2) return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident variant for this depth");
   switch (ctx->mfma_variant) {
     case 0: return narrow ? launch_variant<V32<4, 4>>(ctx, a, units, st) : launch_variant<V32<16, 4>>(ctx, a, units, st);
     case 1: return narrow ? launch_variant<V64<4, 4>>(ctx, a, units, st) : launch_variant<V64<16, 4>>(ctx, a, units, st);

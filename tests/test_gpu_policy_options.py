@@ -157,7 +157,7 @@ DEPTH_CASES = [
     Workload("depth3-regen-noanti", pop=7, envs=2, horizon=40, obs=17, hid=64, act=6, dtype=0, noise_dtype=2, seed=64, num_hidden=3,
              antithetic=0),
     Workload("depth1-cfg1-shape", pop=6, envs=4, horizon=50, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=65, num_hidden=1),
-    Workload("depth3-hid256-bf16", pop=2, envs=2, horizon=12, obs=8, hid=160, act=2, dtype=1, noise_dtype=1, seed=66, num_hidden=3,
+    Workload("depth3-hid160-act20-bf16", pop=2, envs=2, horizon=12, obs=8, hid=160, act=20, dtype=1, noise_dtype=1, seed=66, num_hidden=3,
              done_thresh=math.inf),
 ]
 
@@ -177,6 +177,64 @@ def test_rollout_other_depths(es, w):
     flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} D={ctx.param_count} worst {worst:.2e} flips {flips} sensitive {sens}")
     assert not chaotic
+
+
+# three and four hidden layers of the paper's width (256) in bf16: the matrix-core kernel keeps the extra layers in registers
+DEEP_MFMA_CASES = [
+    Workload("deep3-obs8", pop=4, envs=16, horizon=40, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=71, num_hidden=3),
+    Workload("deep4-obs8", pop=4, envs=16, horizon=40, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=72, num_hidden=4),
+    Workload("deep3-narrow-relu", pop=4, envs=3, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=73, num_hidden=3,
+             hidden_act=1),
+    Workload("deep4-narrow", pop=4, envs=1, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=74, num_hidden=4),
+    Workload("deep3-obs60-hid200", pop=4, envs=20, horizon=30, obs=60, hid=200, act=10, dtype=1, noise_dtype=1, seed=75, num_hidden=3),
+    Workload("deep4-obs60-relu", pop=4, envs=16, horizon=30, obs=60, hid=256, act=10, dtype=1, noise_dtype=1, seed=76, num_hidden=4,
+             hidden_act=1),
+    Workload("deep3-regen-linear-out", pop=5, envs=4, horizon=30, obs=17, hid=256, act=6, dtype=1, noise_dtype=3, seed=77, num_hidden=3,
+             antithetic=0, out_tanh=0),
+]
+
+
+@pytest.mark.parametrize("w", DEEP_MFMA_CASES, ids=lambda w: w.name)
+def test_rollout_deep_policies_on_the_matrix_core_kernel(es, w):
+    ws = replace(w, noise_dtype=w.noise_dtype & 1)
+    a_mat, b_mat, theta = make_inputs(w)
+    theta = (theta + np.random.default_rng(w.seed).standard_normal(theta.size) * 0.02).astype(np.float32)   # non-zero biases
+    ctx = es.EsContext(w)
+    assert ctx.param_count == w.n_params and "mfma" in ctx.rollout_kernel and f"depth{w.num_hidden}" in ctx.rollout_kernel
+    eps = oracle.sample_population(ws, 2)
+    noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
+    got = run_rollout(ctx, w, 2, theta, noise, a_mat, b_mat)
+    ref = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat)
+    probe = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat, arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} D={ctx.param_count} worst {worst:.2e} flips {flips} sensitive {sens}")
+    assert not chaotic
+
+
+def test_deep_policy_with_obs_norm_on_the_matrix_core_kernel(es):
+    from gpu_util import dev
+    w = Workload("deep3-norm", pop=4, envs=16, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=78, num_hidden=3)
+    a_mat, b_mat, theta = make_inputs(w)
+    rng = np.random.default_rng(78)
+    mean = (rng.standard_normal(w.obs) * 0.05).astype(np.float32)
+    inv = (1.0 / (0.33 + rng.random(w.obs) * 0.67)).astype(np.float32)
+    ctx = es.EsContext(w)
+    mean_d, inv_d = dev(mean), dev(inv)
+    ctx.set_obs_norm(mean_d, inv_d)
+    eps = oracle.sample_population(w, 1)
+    got = run_rollout(ctx, w, 1, theta, noise_to_device(ctx, eps), a_mat, b_mat)
+    ref = oracle.rollout(w, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
+    probe = oracle.rollout(w, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), arith=1)
+    flips, worst, sens, chaotic = compare_rollout(w, got, ref, w.name, probe)
+    assert not chaotic
+
+
+def test_depth_the_register_file_cannot_hold_is_refused(es):
+    w = Workload("deep5", pop=4, envs=16, horizon=10, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=79, num_hidden=5)
+    a_mat, b_mat, theta = make_inputs(w)
+    ctx = es.EsContext(w)
+    with pytest.raises(es.EsError, match="exceed the LDS"):
+        run_rollout(ctx, w, 0, theta, ctx.alloc_noise(), a_mat, b_mat)
 
 
 def test_generation_with_three_hidden_layers(es):
