@@ -55,7 +55,9 @@ struct NoiseVec<false> {
   }
 };
 
-template <bool BF16>
+// TABLE: the rows are slices of the shared noise table (their starts come from `offs`); a compile-time
+// choice, so that the plain matrix path keeps its pointer arithmetic free of LDS look-ups.
+template <bool BF16, bool TABLE>
 __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restrict__ noise,
                                                            const uint32_t* __restrict__ offs,
                                                            const float* __restrict__ shaped,
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
   constexpr int VEC = NV::VEC;
   using Raw = typename NV::Raw;
   __shared__ double coef[UPD_MAX_ROWS_PER_CHUNK];
-  __shared__ uint32_t rowoff[UPD_MAX_ROWS_PER_CHUNK];     // start of each row in Raw units (row * ld, or its place in the shared table)
+  __shared__ uint32_t rowoff[TABLE ? UPD_MAX_ROWS_PER_CHUNK : 1];     // start of each table row in Raw units
   __shared__ double red[4][64 * VEC];
 
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
 
   for (uint32_t r = r0 + threadIdx.x; r < r1; r += 256u) {
     coef[r - r0] = antithetic ? (double)shaped[2 * r] - (double)shaped[2 * r + 1] : (double)shaped[r];
-    rowoff[r - r0] = offs ? offs[r] / VEC : 0u;
+    if (TABLE) rowoff[r - r0] = offs[r] / VEC;
   }
   __syncthreads();
 
@@ -85,13 +87,17 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
   for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
 
   const Raw* base = reinterpret_cast<const Raw*>(noise) + ((size_t)col0 / VEC + lane);
-  const size_t row_stride = offs ? 0 : ld / VEC;   // in Raw units; table rows are placed by rowoff instead
-  auto row_at = [&](uint32_t rr) { return base + (size_t)rr * row_stride + rowoff[rr - r0]; };
+  const size_t row_stride = ld / VEC;   // in Raw units
+  // matrix rows are read once and never again (non-temporal); table rows overlap and may be read again (cached)
+  auto load_row = [&](uint32_t rr) {
+    if (TABLE) return base[rowoff[TABLE ? rr - r0 : 0]];
+    return __builtin_nontemporal_load(base + (size_t)rr * row_stride);
+  };
   uint32_t r = r0 + wave;
   for (; r + 12u < r1; r += 16u) {      // four rows of this wavefront in flight
     Raw q[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) q[u] = offs ? *row_at(r + 4u * u) : __builtin_nontemporal_load(row_at(r + 4u * u));
+    for (int u = 0; u < 4; ++u) q[u] = load_row(r + 4u * u);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float f[VEC];
@@ -102,7 +108,7 @@ __global__ __launch_bounds__(256) void grad_partial_kernel(const void* __restric
     }
   }
   for (; r < r1; r += 4u) {
-    const Raw q = offs ? *row_at(r) : __builtin_nontemporal_load(row_at(r));
+    const Raw q = load_row(r);
     float f[VEC];
     NV::unpack(q, f);
     const double c = coef[r - r0];
@@ -188,7 +194,7 @@ constexpr int UPD1_INFLIGHT = 8;     // ... and rows of one wavefront in flight
 constexpr uint32_t UPD_COEF_ROWS = 2048;   // row weights staged in LDS per pass
 
 
-template <bool BF16>
+template <bool BF16, bool TABLE>
 __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(const void* __restrict__ noise,
                                                                 const uint32_t* __restrict__ offs,
                                                                 const float* __restrict__ shaped, uint32_t rows,
@@ -200,13 +206,17 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
   using Raw = typename NQ::Raw;
   constexpr int VEC = NQ::VEC, UPD_TILE = 64 * VEC;
   __shared__ double coef[UPD_COEF_ROWS];
-  __shared__ uint32_t rowoff[UPD_COEF_ROWS];     // shared noise table: start of each row in Raw units
+  __shared__ uint32_t rowoff[TABLE ? UPD_COEF_ROWS : 1];     // shared noise table: start of each row in Raw units
   __shared__ double red[UPD1_WAVES][UPD_TILE];
 
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
   const uint32_t col0 = blockIdx.x * UPD_TILE;
   const Raw* base = reinterpret_cast<const Raw*>(noise) + ((size_t)col0 / VEC + lane);
-  const size_t row_stride = offs ? 0 : ld / VEC;     // in Raw units; table rows are placed by rowoff instead
+  const size_t row_stride = ld / VEC;     // in Raw units
+  auto load_row = [&](uint32_t rb, uint32_t r) {     // row rb + r; table rows are placed by rowoff instead
+    if (TABLE) return __builtin_nontemporal_load(base + rowoff[TABLE ? r : 0]);
+    return __builtin_nontemporal_load(base + (size_t)(rb + r) * row_stride);
+  };
 
   double acc[VEC];
 #pragma unroll
@@ -216,7 +226,7 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
     __syncthreads();
     for (uint32_t r = threadIdx.x; r < rn; r += 64u * UPD1_WAVES) {
       coef[r] = antithetic ? (double)shaped[2 * (rb + r)] - (double)shaped[2 * (rb + r) + 1] : (double)shaped[rb + r];
-      rowoff[r] = offs ? offs[rb + r] / VEC : 0u;
+      if (TABLE) rowoff[r] = offs[rb + r] / VEC;
     }
     __syncthreads();
     uint32_t r = wave;
@@ -224,7 +234,7 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
       Raw q[UPD1_INFLIGHT];
 #pragma unroll
       for (int u = 0; u < UPD1_INFLIGHT; ++u)
-        q[u] = __builtin_nontemporal_load(base + (size_t)(rb + r + UPD1_WAVES * u) * row_stride + rowoff[r + UPD1_WAVES * u]);
+        q[u] = load_row(rb, r + UPD1_WAVES * u);
 #pragma unroll
       for (int u = 0; u < UPD1_INFLIGHT; ++u) {
         float f[VEC];
@@ -235,7 +245,7 @@ __global__ __launch_bounds__(64 * UPD1_WAVES) void update_single_pass_kernel(con
       }
     }
     for (; r < rn; r += UPD1_WAVES) {
-      const Raw q = __builtin_nontemporal_load(base + (size_t)(rb + r) * row_stride + rowoff[r]);
+      const Raw q = load_row(rb, r);
       float f[VEC];
       NQ::unpack(q, f);
       const double c = coef[r];
@@ -314,26 +324,25 @@ int launch_update(es_ctx* ctx, uint64_t step, const void* noise, const float* sh
                        theta, m, v, grad);
     return check_launch(ctx, "es_update (parameter step)");
   }
+  const bool table = nv.offs != nullptr;
   if (chunks == 1) {
     const dim3 grid1(s.ld / (64 * (bf16 ? 8 : 4))), block1(64 * UPD1_WAVES);
-    if (bf16)
-      hipLaunchKernelGGL(update_single_pass_kernel<true>, grid1, block1, 0, st, noise, nv.offs, shaped, s.rows, s.ld, s.D,
-                         c.antithetic, ad, theta, m, v, grad);
-    else
-      hipLaunchKernelGGL(update_single_pass_kernel<false>, grid1, block1, 0, st, noise, nv.offs, shaped, s.rows, s.ld, s.D,
-                         c.antithetic, ad, theta, m, v, grad);
+    auto go = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, grid1, block1, 0, st, noise, nv.offs, shaped, s.rows, s.ld, s.D, c.antithetic, ad, theta, m, v, grad);
+    };
+    if (bf16) { if (table) go(update_single_pass_kernel<true, true>); else go(update_single_pass_kernel<true, false>); }
+    else { if (table) go(update_single_pass_kernel<false, true>); else go(update_single_pass_kernel<false, false>); }
     return check_launch(ctx, "es_update (single pass)");
   }
   const uint32_t rpc = (s.rows + chunks - 1) / chunks;
   const uint32_t tile = 64u * (bf16 ? 8u : 4u);
   double* partial = static_cast<double*>(ws);
   dim3 grid(s.ld / tile, chunks);
-  if (bf16)
-    hipLaunchKernelGGL(grad_partial_kernel<true>, grid, dim3(256), 0, st, noise, nv.offs, shaped, partial, s.rows,
-                       s.ld, rpc, c.antithetic);
-  else
-    hipLaunchKernelGGL(grad_partial_kernel<false>, grid, dim3(256), 0, st, noise, nv.offs, shaped, partial, s.rows,
-                       s.ld, rpc, c.antithetic);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, noise, nv.offs, shaped, partial, s.rows, s.ld, rpc, c.antithetic);
+  };
+  if (bf16) { if (table) go(grad_partial_kernel<true, true>); else go(grad_partial_kernel<true, false>); }
+  else { if (table) go(grad_partial_kernel<false, true>); else go(grad_partial_kernel<false, false>); }
   int rc = check_launch(ctx, "es_update (gradient partials)");
   if (rc != ES_OK) return rc;
   hipLaunchKernelGGL(adam_kernel, dim3((s.D + 255) / 256), dim3(256), 0, st, partial, chunks, s.ld, s.D, ad,
