@@ -5,10 +5,13 @@
 // (individual, environment copy) episode; lane u owns hidden unit u.  The individual's
 // perturbed weights (theta + sign*sigma*eps, fused into the load) and the environment
 // matrices live in that lane's registers for all T steps:
-//   W1 row u (obs values), W2 row u (hid), W3 column u (act), A row u and B row u (lanes < obs).
-// A matrix-vector product is a run of v_readlane (the input element becomes a scalar operand)
-// + v_fmac; the narrow action layer is act products per lane followed by DPP wavefront
-// reductions whose result is read back as a scalar.  No LDS, no barriers.
+//   W1 row u (obs values), a 16-column slice of four W2 rows (hid values) and of one W3 row,
+//   A row u and B row u (lanes < obs).
+// The obs-wide matrix-vector products are runs of v_readlane (the input element becomes a scalar
+// operand) + v_fmac.  The hid x hid layer and the action layer instead broadcast their inputs within
+// 16-lane rows by DPP (one instruction per multiply-add: the lane in row r, column c adds up the
+// inputs 16 r .. 16 r + 15 for the output units c, c + 16, ...) and add the rows' partial sums with
+// row swaps.  The reward norms are DPP wavefront reductions read back as scalars.  No LDS, no barriers.
 // Bound: the dependent instruction chain of one step times T (the workloads that use this
 // kernel have 32-256 episodes for 1024 SIMDs).
 #include "es_device.hpp"
@@ -60,9 +63,52 @@ __device__ __forceinline__ float lane_value(float v, int lane) {   // lane is a 
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
+// acc += w[j] * (lane 16*row + j of h), j = 0..15: sixteen multiply-adds whose first operand is broadcast
+// within each 16-lane row by the DPP modifier, so no input element has to travel through a scalar register.
+// The compiler's hazard checks do not look inside inline assembly: a vector ALU write of `h` must be two
+// wait states away from the first DPP read, hence the leading s_nop.
+template <int B, int N>
+__device__ __forceinline__ float row_bcast_mac16(float acc, float h, const float (&w)[N]) {
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %1, %2 row_newbcast:0 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %3 row_newbcast:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %4 row_newbcast:2 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %5 row_newbcast:3 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %6 row_newbcast:4 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %7 row_newbcast:5 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %8 row_newbcast:6 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %9 row_newbcast:7 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %10 row_newbcast:8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %11 row_newbcast:9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %12 row_newbcast:10 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %13 row_newbcast:11 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %14 row_newbcast:12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %15 row_newbcast:13 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %16 row_newbcast:14 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+      "v_fmac_f32_dpp %0, %1, %17 row_newbcast:15 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+      : "+v"(acc)
+      : "v"(h), "v"(w[B + 0]), "v"(w[B + 1]), "v"(w[B + 2]), "v"(w[B + 3]), "v"(w[B + 4]), "v"(w[B + 5]), "v"(w[B + 6]),
+        "v"(w[B + 7]), "v"(w[B + 8]), "v"(w[B + 9]), "v"(w[B + 10]), "v"(w[B + 11]), "v"(w[B + 12]), "v"(w[B + 13]),
+        "v"(w[B + 14]), "v"(w[B + 15]));
+  return acc;
+}
+// x + (the same register of the other 16-lane row of the pair / of the other half), via the row-swap instructions
+__device__ __forceinline__ float swap16_add(float x, float y) {   // rows (0,1,2,3) <- x0+y... see the caller
+  const auto p = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+  return __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
+}
+__device__ __forceinline__ float swap32_add(float x, float y) {
+  const auto p = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+  return __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
+}
+
 template <int NO, int NH, int NA>
 __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   static_assert(NH <= 64 && NO <= 64 && NA <= 64, "one lane per unit");
+  static_assert(NH == 32 || NH == 64, "the second layer is tiled over whole 16-lane rows");
+  static_assert(NA <= 16, "one 16-lane row of action units");
+  constexpr int NQ = NH / 16;      // 16-lane rows that hold hidden units
   constexpr uint32_t oW1 = 0, ob1 = NH * NO, oW2 = ob1 + NH, ob2 = oW2 + NH * NH, oW3 = ob2 + NH, ob3 = oW3 + NA * NH;
   const int u = threadIdx.x;
   const uint32_t i = blockIdx.x / a.E, e = blockIdx.x % a.E;
@@ -78,14 +124,22 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   };
 
   // ---- this lane's weights ----
-  float w1[NO], w2[NH], w3[NA], ar[NO], br[NA];
+  float w1[NO], w2[NH], w3[16], ar[NO], br[NA];
   float b1 = 0.f, b2 = 0.f, b3 = 0.f;
 #pragma unroll
   for (int k = 0; k < NO; ++k) w1[k] = hid ? param(oW1 + u * NO + k) : 0.f;
+  // second layer: the lane in row r, column c multiplies the 16 inputs of ITS row (h1[16 r + j]) into partial sums of
+  // the output units c, c + 16, ...; w2[16 q + j] = W2[c + 16 q][16 r + j]
+  const int lr = u >> 4, lc = u & 15;
 #pragma unroll
-  for (int k = 0; k < NH; ++k) w2[k] = hid ? param(oW2 + u * NH + k) : 0.f;
+  for (int qq = 0; qq < NQ; ++qq) {
+    const uint32_t d0 = oW2 + (uint32_t)(lc + 16 * qq) * NH + 16u * (uint32_t)lr;     // sixteen consecutive parameters
 #pragma unroll
-  for (int c = 0; c < NA; ++c) w3[c] = hid ? param(oW3 + c * NH + u) : 0.f;     // column u of W3
+    for (int j = 0; j < 16; ++j) w2[16 * qq + j] = hid ? param(d0 + j) : 0.f;
+  }
+  // action layer, the same scheme: w3[j] = W3[c][16 r + j] (columns c >= act are zero)
+#pragma unroll
+  for (int j = 0; j < 16; ++j) w3[j] = (hid && lc < NA) ? param(oW3 + (uint32_t)lc * NH + 16u * (uint32_t)lr + j) : 0.f;
   if (hid) { b1 = param(ob1 + u); b2 = param(ob2 + u); }
   if (u < NA) b3 = param(ob3 + u);
 #pragma unroll
@@ -111,24 +165,23 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
       if (k & 1) acc1 = __fmaf_rn(w1[k], sk, acc1); else acc0 = __fmaf_rn(w1[k], sk, acc0);
     }
     const float h1 = hid ? (a.hidden_relu ? fmaxf(acc0 + acc1, 0.f) : tanh_fast(acc0 + acc1)) : 0.f;
-    // h2 = tanh(W2 h1 + b2): four chains
-    float c0 = b2, c1 = 0.f, c2 = 0.f, c3 = 0.f;
-#pragma unroll
-    for (int k = 0; k < NH; k += 4) {
-      c0 = __fmaf_rn(w2[k], lane_value(h1, k), c0);
-      if (k + 1 < NH) c1 = __fmaf_rn(w2[k + 1], lane_value(h1, k + 1), c1);
-      if (k + 2 < NH) c2 = __fmaf_rn(w2[k + 2], lane_value(h1, k + 2), c2);
-      if (k + 3 < NH) c3 = __fmaf_rn(w2[k + 3], lane_value(h1, k + 3), c3);
+    // h2 = tanh(W2 h1 + b2): every lane accumulates over its own row's inputs (row-broadcast DPP multiply-adds),
+    // then the rows' partial sums are added and moved to the lane of their unit by two row-swap stages
+    const float p0 = row_bcast_mac16<0>(0.f, h1, w2), p1 = row_bcast_mac16<16>(0.f, h1, w2);
+    float l2;
+    if (NQ == 4) {
+      const float p2 = row_bcast_mac16<NQ == 4 ? 32 : 0>(0.f, h1, w2), p3 = row_bcast_mac16<NQ == 4 ? 48 : 0>(0.f, h1, w2);
+      l2 = swap16_add(swap32_add(p0, p2), swap32_add(p1, p3));
+    } else {
+      l2 = swap16_add(p0, p1);
     }
-    const float h2 = hid ? (a.hidden_relu ? fmaxf((c0 + c1) + (c2 + c3), 0.f) : tanh_fast((c0 + c1) + (c2 + c3))) : 0.f;
-    // a = tanh(W3 h2 + b3): per-lane products, wavefront reductions, results as uniform scalars
-    // the NA totals are gathered into lanes 0..NA-1 (lane c also holds b3[c]) so that one tanh serves all of them
-    float pv = 0.f;
-#pragma unroll
-    for (int c = 0; c < NA; ++c) {
-      const float tot = wave_total(w3[c] * h2);
-      pv = (u == c) ? tot : pv;
-    }
+    l2 += b2;
+    const float h2 = hid ? (a.hidden_relu ? fmaxf(l2, 0.f) : tanh_fast(l2)) : 0.f;
+    // a = tanh(W3 h2 + b3): row-broadcast multiply-adds as above, the four rows' partial sums added by two row swaps;
+    // lane c of every row then holds unit c's total, and one tanh serves all units
+    float pv = row_bcast_mac16<0>(0.f, h2, w3);
+    pv = swap16_add(pv, pv);
+    pv = swap32_add(pv, pv);
     pv = pv + b3;
     const float tv = a.out_tanh ? tanh_fast(pv) : pv;
     float act[NA];
