@@ -2,16 +2,17 @@
 //
 // Paper Sec. 3.2 / 5.2: population x environment-copy evaluation of a deterministic
 // two-hidden-layer MLP policy, fitness = mean undiscounted return.  One wavefront runs one
-// (individual, environment copy) episode; lane u owns hidden unit u.  The individual's
-// perturbed weights (theta + sign*sigma*eps, fused into the load) and the environment
-// matrices live in that lane's registers for all T steps:
-//   W1 row u (obs values), a 16-column slice of four W2 rows (hid values) and of one W3 row,
-//   A row u and B row u (lanes < obs).
-// The obs-wide matrix-vector products are runs of v_readlane (the input element becomes a scalar
-// operand) + v_fmac.  The hid x hid layer and the action layer instead broadcast their inputs within
-// 16-lane rows by DPP (one instruction per multiply-add: the lane in row r, column c adds up the
-// inputs 16 r .. 16 r + 15 for the output units c, c + 16, ...) and add the rows' partial sums with
-// row swaps.  The reward norms are DPP wavefront reductions read back as scalars.  No LDS, no barriers.
+// (individual, environment copy) episode; lane u owns hidden unit u, and the state vector is spread
+// over the four 16-lane rows of the wavefront (element k in row k % 4, column k / 4).  The individual's
+// perturbed weights (theta + sign*sigma*eps, fused into the load) and the environment matrices live in
+// registers for all T steps.
+// Every matrix-vector product broadcasts its inputs within the 16-lane rows by DPP, fused into the
+// multiply-add (v_fmac_f32_dpp ... row_newbcast:j, one instruction per multiply-add, no scalar hop):
+// the lane in row r, column c adds up the inputs that live in ITS row into partial sums for the outputs
+// that belong to ITS column (hidden units c, c + 16, ...; state elements 4 c .. 4 c + 3), and two
+// row-swap stages (v_permlane32_swap, v_permlane16_swap + add) add the four rows' partial sums and
+// leave each output's total in the lane that owns it.  The reward norms are reduced the same way and end
+// in lane 15.  No LDS, no barriers, one scalar read per step (the termination test).
 // Bound: the dependent instruction chain of one step times T (the workloads that use this
 // kernel have 32-256 episodes for 1024 SIMDs).
 #include "es_device.hpp"
@@ -31,7 +32,7 @@ struct RegArgs {
   int32_t* ep_len;
   uint32_t N, E, T, ld;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, out_tanh, noise_mode, hidden_relu;
+  uint32_t antithetic, noise_mode;
   float sigma, done_thresh, act_cost;
 };
 
@@ -93,6 +94,49 @@ __device__ __forceinline__ float row_bcast_mac16(float acc, float h, const float
         "v"(w[B + 14]), "v"(w[B + 15]));
   return acc;
 }
+// Four such runs at once, their instructions interleaved (accumulator 0, 1, 2, 3 for input 0, then for input 1, ...), so that
+// consecutive instructions never depend on each other: out_q += sum_j w[16 q + j] * (lane 16*row + j of h).
+#define ES_DPP4(J, A, B, C, D)                                                                     \
+  "v_fmac_f32_dpp %0, %4, %" #A " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+  "v_fmac_f32_dpp %1, %4, %" #B " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+  "v_fmac_f32_dpp %2, %4, %" #C " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+  "v_fmac_f32_dpp %3, %4, %" #D " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+__device__ __forceinline__ void row_bcast_mac16x4(float& o0, float& o1, float& o2, float& o3, float h, const float (&w)[64]) {
+  asm volatile(
+      "s_nop 1\n\t"
+      ES_DPP4(0, 5, 21, 37, 53) ES_DPP4(1, 6, 22, 38, 54) ES_DPP4(2, 7, 23, 39, 55) ES_DPP4(3, 8, 24, 40, 56)
+      ES_DPP4(4, 9, 25, 41, 57) ES_DPP4(5, 10, 26, 42, 58) ES_DPP4(6, 11, 27, 43, 59) ES_DPP4(7, 12, 28, 44, 60)
+      ES_DPP4(8, 13, 29, 45, 61) ES_DPP4(9, 14, 30, 46, 62) ES_DPP4(10, 15, 31, 47, 63) ES_DPP4(11, 16, 32, 48, 64)
+      ES_DPP4(12, 17, 33, 49, 65) ES_DPP4(13, 18, 34, 50, 66) ES_DPP4(14, 19, 35, 51, 67) ES_DPP4(15, 20, 36, 52, 68)
+      : "+v"(o0), "+v"(o1), "+v"(o2), "+v"(o3)
+      : "v"(h),
+        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
+        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]), "v"(w[20]),
+        "v"(w[21]), "v"(w[22]), "v"(w[23]), "v"(w[24]), "v"(w[25]), "v"(w[26]), "v"(w[27]), "v"(w[28]), "v"(w[29]), "v"(w[30]),
+        "v"(w[31]), "v"(w[32]), "v"(w[33]), "v"(w[34]), "v"(w[35]), "v"(w[36]), "v"(w[37]), "v"(w[38]), "v"(w[39]), "v"(w[40]),
+        "v"(w[41]), "v"(w[42]), "v"(w[43]), "v"(w[44]), "v"(w[45]), "v"(w[46]), "v"(w[47]), "v"(w[48]), "v"(w[49]), "v"(w[50]),
+        "v"(w[51]), "v"(w[52]), "v"(w[53]), "v"(w[54]), "v"(w[55]), "v"(w[56]), "v"(w[57]), "v"(w[58]), "v"(w[59]), "v"(w[60]),
+        "v"(w[61]), "v"(w[62]), "v"(w[63]));
+}
+#undef ES_DPP4
+// The same with N <= 6 inputs per row (the observation-wide products and the action term of the environment step).
+#define ES_DPP_FMAC(J, OP) "v_fmac_f32_dpp %0, %1, %" #OP " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+template <int N, int B, int M>
+__device__ __forceinline__ float row_bcast_mac(float acc, float h, const float (&w)[M]) {
+  static_assert(N == 3 || N == 5 || N == 6, "run lengths the two register-resident shapes need");
+  static_assert(B + N <= M, "weights of this run");
+  if constexpr (N == 3)
+    asm volatile("s_nop 1\n\t" ES_DPP_FMAC(0, 2) ES_DPP_FMAC(1, 3) ES_DPP_FMAC(2, 4)
+                 : "+v"(acc) : "v"(h), "v"(w[B]), "v"(w[B + 1]), "v"(w[B + 2]));
+  else if constexpr (N == 5)
+    asm volatile("s_nop 1\n\t" ES_DPP_FMAC(0, 2) ES_DPP_FMAC(1, 3) ES_DPP_FMAC(2, 4) ES_DPP_FMAC(3, 5) ES_DPP_FMAC(4, 6)
+                 : "+v"(acc) : "v"(h), "v"(w[B]), "v"(w[B + 1]), "v"(w[B + 2]), "v"(w[B + 3]), "v"(w[B + 4]));
+  else
+    asm volatile("s_nop 1\n\t" ES_DPP_FMAC(0, 2) ES_DPP_FMAC(1, 3) ES_DPP_FMAC(2, 4) ES_DPP_FMAC(3, 5) ES_DPP_FMAC(4, 6) ES_DPP_FMAC(5, 7)
+                 : "+v"(acc) : "v"(h), "v"(w[B]), "v"(w[B + 1]), "v"(w[B + 2]), "v"(w[B + 3]), "v"(w[B + 4]), "v"(w[B + 5]));
+  return acc;
+}
+#undef ES_DPP_FMAC
 // x + (the same register of the other 16-lane row of the pair / of the other half), via the row-swap instructions
 __device__ __forceinline__ float swap16_add(float x, float y) {   // rows (0,1,2,3) <- x0+y... see the caller
   const auto p = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
@@ -102,8 +146,41 @@ __device__ __forceinline__ float swap32_add(float x, float y) {
   const auto p = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
   return __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
 }
+__device__ __forceinline__ float swap16_max(float x) {      // non-negative values
+  const auto p = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false, false);
+  return fmaxf(__builtin_bit_cast(float, (unsigned)p[0]), __builtin_bit_cast(float, (unsigned)p[1]));
+}
+__device__ __forceinline__ float swap32_max(float x) {
+  const auto p = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false, false);
+  return fmaxf(__builtin_bit_cast(float, (unsigned)p[0]), __builtin_bit_cast(float, (unsigned)p[1]));
+}
+// out[row q] = sum over the four rows of x_q: two row-swap stages
+__device__ __forceinline__ float rows_transpose_add(float x0, float x1, float x2, float x3) {
+  return swap16_add(swap32_add(x0, x2), swap32_add(x1, x3));
+}
+// the same for two registers whose sums go to rows 0 and 1 (and again to rows 2 and 3)
+__device__ __forceinline__ float rows_transpose_add(float x0, float x1) {
+  const float t = swap16_add(x0, x1);
+  return swap32_add(t, t);
+}
+// sum / max over the lanes of each 16-lane row, result in lane 15 of the row (lanes without a source read 0)
+__device__ __forceinline__ float row_total(float v) {
+  v += dpp_zero<0x111, 0xF>(v);
+  v += dpp_zero<0x112, 0xF>(v);
+  v += dpp_zero<0x114, 0xF>(v);
+  return v + dpp_zero<0x118, 0xF>(v);
+}
+__device__ __forceinline__ float row_total_max(float v) {   // non-negative values
+  v = fmaxf(v, dpp_zero<0x111, 0xF>(v));
+  v = fmaxf(v, dpp_zero<0x112, 0xF>(v));
+  v = fmaxf(v, dpp_zero<0x114, 0xF>(v));
+  return fmaxf(v, dpp_zero<0x118, 0xF>(v));
+}
 
-template <int NO, int NH, int NA>
+// RELU / OUT_TANH: the activations are compile-time choices, and lanes that own no unit need no masking (their weights
+// and biases are zero, and both activations map 0 to 0), so a step is one straight-line block: a taken branch costs
+// this single in-order wavefront more than the few instructions it would skip.
+template <int NO, int NH, int NA, bool RELU, bool OUT_TANH>
 __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   static_assert(NH <= 64 && NO <= 64 && NA <= 64, "one lane per unit");
   static_assert(NH == 32 || NH == 64, "the second layer is tiled over whole 16-lane rows");
@@ -114,7 +191,14 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   const uint32_t i = blockIdx.x / a.E, e = blockIdx.x % a.E;
   const uint32_t row = a.antithetic ? (i >> 1) : i;
   const float scale = (a.antithetic && (i & 1u)) ? -a.sigma : a.sigma;
-  const bool hid = u < NH, obs = u < NO;
+  const bool hid = u < NH;
+  // Lane (row lr, column lc).  Hidden unit u lives in lane u.  The state is spread over the four rows so that every row
+  // holds a quarter of it: element k sits in row k % 4, column k / 4 - then a row-broadcast run of CJ = ceil(obs / 4)
+  // multiply-adds per output covers a whole observation-wide product, all four rows working.
+  const int lr = u >> 4, lc = u & 15;
+  constexpr int CJ = (NO + 3) / 4;
+  const int ks = 4 * lc + lr;                    // the state element of this lane
+  const bool sval = lc < CJ && ks < NO;
 
   const void* nbase = a.noise;      // shared table: this individual's row, addressed as row 0
   uint32_t nrow = row;
@@ -124,91 +208,100 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   };
 
   // ---- this lane's weights ----
-  float w1[NO], w2[NH], w3[16], ar[NO], br[NA];
+  // first layer: partial sums of the units lc, lc + 16, ... over the inputs of row lr: w1[CJ q + j] = W1[lc + 16 q][4 j + lr]
+  // second layer and action layer: the same over the 16 hidden units of row lr: w2[16 q + j] = W2[lc + 16 q][16 lr + j],
+  //   w3[j] = W3[lc][16 lr + j]
+  // environment: partial sums of the four state elements of column lc: ar[CJ r + j] = A[4 lc + r][4 j + lr];
+  //   action term of this lane's own element: br[c] = B[ks][c]
+  float w1[NQ * CJ], w2[NH], w3[16], ar[4 * CJ], br[NA];
   float b1 = 0.f, b2 = 0.f, b3 = 0.f;
 #pragma unroll
-  for (int k = 0; k < NO; ++k) w1[k] = hid ? param(oW1 + u * NO + k) : 0.f;
-  // second layer: the lane in row r, column c multiplies the 16 inputs of ITS row (h1[16 r + j]) into partial sums of
-  // the output units c, c + 16, ...; w2[16 q + j] = W2[c + 16 q][16 r + j]
-  const int lr = u >> 4, lc = u & 15;
+  for (int qq = 0; qq < NQ; ++qq)
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) w1[CJ * qq + j] = (4 * j + lr < NO) ? param(oW1 + (uint32_t)(lc + 16 * qq) * NO + 4 * j + lr) : 0.f;
 #pragma unroll
   for (int qq = 0; qq < NQ; ++qq) {
     const uint32_t d0 = oW2 + (uint32_t)(lc + 16 * qq) * NH + 16u * (uint32_t)lr;     // sixteen consecutive parameters
 #pragma unroll
     for (int j = 0; j < 16; ++j) w2[16 * qq + j] = hid ? param(d0 + j) : 0.f;
   }
-  // action layer, the same scheme: w3[j] = W3[c][16 r + j] (columns c >= act are zero)
 #pragma unroll
   for (int j = 0; j < 16; ++j) w3[j] = (hid && lc < NA) ? param(oW3 + (uint32_t)lc * NH + 16u * (uint32_t)lr + j) : 0.f;
   if (hid) { b1 = param(ob1 + u); b2 = param(ob2 + u); }
-  if (u < NA) b3 = param(ob3 + u);
+  if (lc < NA) b3 = param(ob3 + lc);            // in every row: the action vector is kept once per row
 #pragma unroll
-  for (int k = 0; k < NO; ++k) ar[k] = obs ? a.A[u * NO + k] : 0.f;
+  for (int r = 0; r < 4; ++r)
 #pragma unroll
-  for (int c = 0; c < NA; ++c) br[c] = obs ? a.B[u * NA + c] : 0.f;
+    for (int j = 0; j < CJ; ++j)
+      ar[CJ * r + j] = (lc < CJ && 4 * lc + r < NO && 4 * j + lr < NO) ? a.A[(4 * lc + r) * NO + 4 * j + lr] : 0.f;
+#pragma unroll
+  for (int c = 0; c < NA; ++c) br[c] = sval ? a.B[ks * NA + c] : 0.f;
 
-  // frozen observation statistics of lane k's state element (identity when none are set: (s - 0) * 1 = s exactly)
-  const float mu = (obs && a.obs_mean) ? a.obs_mean[u] : 0.f;
-  const float iv = (obs && a.obs_mean) ? a.obs_inv[u] : 1.f;
-  float s = obs ? reset_value((uint32_t)u, e, a.gen, a.k0, a.k1) : 0.f;     // lane k holds s[k]
-  float R = 0.f;
+  // frozen observation statistics of this lane's state element (identity when none are set: (s - 0) * 1 = s exactly)
+  const float mu = (sval && a.obs_mean) ? a.obs_mean[ks] : 0.f;
+  const float iv = (sval && a.obs_mean) ? a.obs_inv[ks] : 1.f;
+  float s = sval ? reset_value((uint32_t)ks, e, a.gen, a.k0, a.k1) : 0.f;
+  float R = 0.f;                      // meaningful in lane 15 (where the row reductions end), stored from there
   int32_t len = 0;
   const float inv_no = 1.0f / (float)NO;
 
   for (uint32_t t = 0; t < a.T; ++t) {
-    // h1 = tanh(W1 s + b1): two accumulation chains
+    // h1 = tanh(W1 s + b1)
     const float xp = (s - mu) * iv;      // the policy's input (paper App. B: fixed normalisation statistics)
-    float acc0 = b1, acc1 = 0.f;
-#pragma unroll
-    for (int k = 0; k < NO; ++k) {
-      const float sk = lane_value(xp, k);
-      if (k & 1) acc1 = __fmaf_rn(w1[k], sk, acc1); else acc0 = __fmaf_rn(w1[k], sk, acc0);
+    float l1;
+    {
+      const float p0 = row_bcast_mac<CJ, 0>(0.f, xp, w1), p1 = row_bcast_mac<CJ, CJ>(0.f, xp, w1);
+      if (NQ == 4) {
+        const float p2 = row_bcast_mac<CJ, NQ == 4 ? 2 * CJ : 0>(0.f, xp, w1), p3 = row_bcast_mac<CJ, NQ == 4 ? 3 * CJ : 0>(0.f, xp, w1);
+        l1 = rows_transpose_add(p0, p1, p2, p3);
+      } else {
+        l1 = rows_transpose_add(p0, p1);
+      }
     }
-    const float h1 = hid ? (a.hidden_relu ? fmaxf(acc0 + acc1, 0.f) : tanh_fast(acc0 + acc1)) : 0.f;
+    l1 += b1;
+    const float h1 = RELU ? fmaxf(l1, 0.f) : tanh_fast(l1);
     // h2 = tanh(W2 h1 + b2): every lane accumulates over its own row's inputs (row-broadcast DPP multiply-adds),
     // then the rows' partial sums are added and moved to the lane of their unit by two row-swap stages
-    const float p0 = row_bcast_mac16<0>(0.f, h1, w2), p1 = row_bcast_mac16<16>(0.f, h1, w2);
     float l2;
-    if (NQ == 4) {
-      const float p2 = row_bcast_mac16<NQ == 4 ? 32 : 0>(0.f, h1, w2), p3 = row_bcast_mac16<NQ == 4 ? 48 : 0>(0.f, h1, w2);
-      l2 = swap16_add(swap32_add(p0, p2), swap32_add(p1, p3));
+    if constexpr (NQ == 4) {
+      float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+      row_bcast_mac16x4(p0, p1, p2, p3, h1, w2);
+      l2 = rows_transpose_add(p0, p1, p2, p3);
     } else {
-      l2 = swap16_add(p0, p1);
+      const float p0 = row_bcast_mac16<0>(0.f, h1, w2), p1 = row_bcast_mac16<16>(0.f, h1, w2);
+      l2 = swap16_add(p0, p1);          // h1 is zero in rows 2 and 3
     }
     l2 += b2;
-    const float h2 = hid ? (a.hidden_relu ? fmaxf(l2, 0.f) : tanh_fast(l2)) : 0.f;
+    const float h2 = RELU ? fmaxf(l2, 0.f) : tanh_fast(l2);
     // a = tanh(W3 h2 + b3): row-broadcast multiply-adds as above, the four rows' partial sums added by two row swaps;
-    // lane c of every row then holds unit c's total, and one tanh serves all units
+    // column c of every row then holds unit c's total, and one tanh serves all units
     float pv = row_bcast_mac16<0>(0.f, h2, w3);
     pv = swap16_add(pv, pv);
     pv = swap32_add(pv, pv);
     pv = pv + b3;
-    const float tv = a.out_tanh ? tanh_fast(pv) : pv;
-    float act[NA];
-    float aa = 0.f;
-#pragma unroll
-    for (int c = 0; c < NA; ++c) {
-      act[c] = lane_value(tv, c);
-      aa = __fmaf_rn(act[c], act[c], aa);
-    }
-    // reward from the pre-step state
-    const float ss = wave_total(s * s);
+    const float tv = OUT_TANH ? tanh_fast(pv) : pv;      // columns >= act: weights and bias are zero
+    // reward from the pre-step state: |a|^2 per row, |s|^2 over the rows and then along the row (both end in lane 15)
+    const float aa = row_total(tv * tv);
+    const float sq = s * s;
+    const float sq2 = swap16_add(sq, sq);
+    const float ss = row_total(swap32_add(sq2, sq2));
     R += __fmaf_rn(-ss, inv_no, 1.0f) - a.act_cost * aa;
     len += 1;
-    // s' = tanh(A s + B a)
-    float e0 = 0.f, e1 = 0.f;
-#pragma unroll
-    for (int k = 0; k < NO; ++k) {
-      const float sk = lane_value(s, k);
-      if (k & 1) e1 = __fmaf_rn(ar[k], sk, e1); else e0 = __fmaf_rn(ar[k], sk, e0);
+    // s' = tanh(A s + B a): partial sums of the four elements of this column over the inputs of this row, rows added
+    // and moved to their element's lane; the action term straight from the row's action vector
+    float pre;
+    {
+      const float e0 = row_bcast_mac<CJ, 0>(0.f, s, ar), e1 = row_bcast_mac<CJ, CJ>(0.f, s, ar);
+      const float e2 = row_bcast_mac<CJ, 2 * CJ>(0.f, s, ar), e3 = row_bcast_mac<CJ, 3 * CJ>(0.f, s, ar);
+      pre = rows_transpose_add(e0, e1, e2, e3);
     }
-#pragma unroll
-    for (int c = 0; c < NA; ++c) e0 = __fmaf_rn(br[c], act[c], e0);
-    s = obs ? tanh_fast(e0 + e1) : 0.f;
-    const float mx = wave_total_max(fabsf(s));
+    pre = row_bcast_mac<NA, 0>(pre, tv, br);
+    s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
+    const float ab = fabsf(s);
+    const float mx = lane_value(row_total_max(swap32_max(swap16_max(ab))), 15);
     if (mx > a.done_thresh) break;       // uniform: mx is a scalar
   }
-  if (u == 0) {
+  if (u == 15) {
     a.returns[(size_t)i * a.E + e] = R;
     a.ep_len[(size_t)i * a.E + e] = len;
   }
@@ -238,12 +331,20 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   a.theta = theta; a.noise = nv.base; a.noise_offs = nv.offs; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
   a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode; a.hidden_relu = c.hidden_act == 1;
+  a.antithetic = c.antithetic; a.noise_mode = nv.mode;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const dim3 grid(s.N * s.E), block(64);
+  const bool relu = c.hidden_act == 1, otanh = c.out_tanh != 0;
+  auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, st, a); };
   switch (ctx->reg_variant) {
-    case 0: hipLaunchKernelGGL((rollout_reg_kernel<11, 32, 3>), grid, block, 0, st, a); break;
-    case 1: hipLaunchKernelGGL((rollout_reg_kernel<17, 64, 6>), grid, block, 0, st, a); break;
+    case 0:
+      if (relu) { if (otanh) go(rollout_reg_kernel<11, 32, 3, true, true>); else go(rollout_reg_kernel<11, 32, 3, true, false>); }
+      else { if (otanh) go(rollout_reg_kernel<11, 32, 3, false, true>); else go(rollout_reg_kernel<11, 32, 3, false, false>); }
+      break;
+    case 1:
+      if (relu) { if (otanh) go(rollout_reg_kernel<17, 64, 6, true, true>); else go(rollout_reg_kernel<17, 64, 6, true, false>); }
+      else { if (otanh) go(rollout_reg_kernel<17, 64, 6, false, true>); else go(rollout_reg_kernel<17, 64, 6, false, false>); }
+      break;
     default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident binary32 variant for this shape");
   }
   int rc = check_launch(ctx, "es_rollout (register-resident f32)");
