@@ -40,30 +40,6 @@ template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_zero(float v) {      // lanes without a source (or masked off) read 0
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF));
 }
-// Sum over the 64 lanes; the total is read from lane 63 and returned as a wavefront-uniform value.
-__device__ __forceinline__ float wave_total(float v) {
-  v += dpp_zero<0x111, 0xF>(v);      // row_shr:1
-  v += dpp_zero<0x112, 0xF>(v);      // row_shr:2
-  v += dpp_zero<0x114, 0xF>(v);      // row_shr:4
-  v += dpp_zero<0x118, 0xF>(v);      // row_shr:8   -> lane 15 of every row holds the row total
-  v += dpp_zero<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
-  v += dpp_zero<0x143, 0xC>(v);      // row_bcast:31 into rows 2 and 3 -> lane 63 holds the total
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-__device__ __forceinline__ float wave_total_max(float v) {   // for non-negative values
-  v = fmaxf(v, dpp_zero<0x111, 0xF>(v));
-  v = fmaxf(v, dpp_zero<0x112, 0xF>(v));
-  v = fmaxf(v, dpp_zero<0x114, 0xF>(v));
-  v = fmaxf(v, dpp_zero<0x118, 0xF>(v));
-  v = fmaxf(v, dpp_zero<0x142, 0xA>(v));
-  v = fmaxf(v, dpp_zero<0x143, 0xC>(v));
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-
-__device__ __forceinline__ float lane_value(float v, int lane) {   // lane is a compile-time constant after unrolling
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
-}
-
 // acc += w[j] * (lane 16*row + j of h), j = 0..15: sixteen multiply-adds whose first operand is broadcast
 // within each 16-lane row by the DPP modifier, so no input element has to travel through a scalar register.
 // The compiler's hazard checks do not look inside inline assembly: a vector ALU write of `h` must be two
@@ -146,14 +122,6 @@ __device__ __forceinline__ float swap32_add(float x, float y) {
   const auto p = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
   return __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
 }
-__device__ __forceinline__ float swap16_max(float x) {      // non-negative values
-  const auto p = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false, false);
-  return fmaxf(__builtin_bit_cast(float, (unsigned)p[0]), __builtin_bit_cast(float, (unsigned)p[1]));
-}
-__device__ __forceinline__ float swap32_max(float x) {
-  const auto p = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false, false);
-  return fmaxf(__builtin_bit_cast(float, (unsigned)p[0]), __builtin_bit_cast(float, (unsigned)p[1]));
-}
 // out[row q] = sum over the four rows of x_q: two row-swap stages
 __device__ __forceinline__ float rows_transpose_add(float x0, float x1, float x2, float x3) {
   return swap16_add(swap32_add(x0, x2), swap32_add(x1, x3));
@@ -163,18 +131,12 @@ __device__ __forceinline__ float rows_transpose_add(float x0, float x1) {
   const float t = swap16_add(x0, x1);
   return swap32_add(t, t);
 }
-// sum / max over the lanes of each 16-lane row, result in lane 15 of the row (lanes without a source read 0)
+// sum over the lanes of each 16-lane row, result in lane 15 of the row (lanes without a source read 0)
 __device__ __forceinline__ float row_total(float v) {
   v += dpp_zero<0x111, 0xF>(v);
   v += dpp_zero<0x112, 0xF>(v);
   v += dpp_zero<0x114, 0xF>(v);
   return v + dpp_zero<0x118, 0xF>(v);
-}
-__device__ __forceinline__ float row_total_max(float v) {   // non-negative values
-  v = fmaxf(v, dpp_zero<0x111, 0xF>(v));
-  v = fmaxf(v, dpp_zero<0x112, 0xF>(v));
-  v = fmaxf(v, dpp_zero<0x114, 0xF>(v));
-  return fmaxf(v, dpp_zero<0x118, 0xF>(v));
 }
 
 // RELU / OUT_TANH: the activations are compile-time choices, and lanes that own no unit need no masking (their weights
@@ -243,7 +205,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   float s = sval ? reset_value((uint32_t)ks, e, a.gen, a.k0, a.k1) : 0.f;
   float R = 0.f;                      // meaningful in lane 15 (where the row reductions end), stored from there
   int32_t len = 0;
-  const float inv_no = 1.0f / (float)NO;
+  const float inv_no = 1.0f / (float)NO, quarter_cost = 0.25f * a.act_cost;
 
   for (uint32_t t = 0; t < a.T; ++t) {
     // h1 = tanh(W1 s + b1)
@@ -280,12 +242,11 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     pv = swap32_add(pv, pv);
     pv = pv + b3;
     const float tv = OUT_TANH ? tanh_fast(pv) : pv;      // columns >= act: weights and bias are zero
-    // reward from the pre-step state: |a|^2 per row, |s|^2 over the rows and then along the row (both end in lane 15)
-    const float aa = row_total(tv * tv);
-    const float sq = s * s;
-    const float sq2 = swap16_add(sq, sq);
-    const float ss = row_total(swap32_add(sq2, sq2));
-    R += __fmaf_rn(-ss, inv_no, 1.0f) - a.act_cost * aa;
+    // reward from the pre-step state, 1 - |s|^2 / obs - cost |a|^2, as one sum over all 64 lanes (the action vector is
+    // held once per row, hence the quarter) that ends in lane 15
+    const float rl = __fmaf_rn(-inv_no * s, s, -quarter_cost * (tv * tv));
+    const float rl2 = swap16_add(rl, rl);
+    R += 1.0f + row_total(swap32_add(rl2, rl2));
     len += 1;
     // s' = tanh(A s + B a): partial sums of the four elements of this column over the inputs of this row, rows added
     // and moved to their element's lane; the action term straight from the row's action vector
@@ -297,9 +258,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     }
     pre = row_bcast_mac<NA, 0>(pre, tv, br);
     s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
-    const float ab = fabsf(s);
-    const float mx = lane_value(row_total_max(swap32_max(swap16_max(ab))), 15);
-    if (mx > a.done_thresh) break;       // uniform: mx is a scalar
+    if (__ballot(fabsf(s) > a.done_thresh) != 0ull) break;       // max |s| > threshold: some lane exceeds it
   }
   if (u == 15) {
     a.returns[(size_t)i * a.E + e] = R;
