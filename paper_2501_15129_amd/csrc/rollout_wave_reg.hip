@@ -40,79 +40,132 @@ template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_zero(float v) {      // lanes without a source (or masked off) read 0
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF));
 }
-// acc += w[j] * (lane 16*row + j of h), j = 0..15: sixteen multiply-adds whose first operand is broadcast
-// within each 16-lane row by the DPP modifier, so no input element has to travel through a scalar register.
-// The compiler's hazard checks do not look inside inline assembly: a vector ALU write of `h` must be two
-// wait states away from the first DPP read, hence the leading s_nop.
-template <int B, int N>
-__device__ __forceinline__ float row_bcast_mac16(float acc, float h, const float (&w)[N]) {
-  asm volatile(
-      "s_nop 1\n\t"
-      "v_fmac_f32_dpp %0, %1, %2 row_newbcast:0 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %3 row_newbcast:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %4 row_newbcast:2 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %5 row_newbcast:3 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %6 row_newbcast:4 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %7 row_newbcast:5 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %8 row_newbcast:6 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %9 row_newbcast:7 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %10 row_newbcast:8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %11 row_newbcast:9 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %12 row_newbcast:10 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %13 row_newbcast:11 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %14 row_newbcast:12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %15 row_newbcast:13 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %16 row_newbcast:14 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-      "v_fmac_f32_dpp %0, %1, %17 row_newbcast:15 row_mask:0xf bank_mask:0xf bound_ctrl:1"
-      : "+v"(acc)
-      : "v"(h), "v"(w[B + 0]), "v"(w[B + 1]), "v"(w[B + 2]), "v"(w[B + 3]), "v"(w[B + 4]), "v"(w[B + 5]), "v"(w[B + 6]),
-        "v"(w[B + 7]), "v"(w[B + 8]), "v"(w[B + 9]), "v"(w[B + 10]), "v"(w[B + 11]), "v"(w[B + 12]), "v"(w[B + 13]),
-        "v"(w[B + 14]), "v"(w[B + 15]));
-  return acc;
-}
-// Four such runs at once, their instructions interleaved (accumulator 0, 1, 2, 3 for input 0, then for input 1, ...), so that
-// consecutive instructions never depend on each other: out_q += sum_j w[16 q + j] * (lane 16*row + j of h).
-#define ES_DPP4(J, A, B, C, D)                                                                     \
-  "v_fmac_f32_dpp %0, %4, %" #A " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
-  "v_fmac_f32_dpp %1, %4, %" #B " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
-  "v_fmac_f32_dpp %2, %4, %" #C " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
-  "v_fmac_f32_dpp %3, %4, %" #D " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-__device__ __forceinline__ void row_bcast_mac16x4(float& o0, float& o1, float& o2, float& o3, float h, const float (&w)[64]) {
-  asm volatile(
-      "s_nop 1\n\t"
-      ES_DPP4(0, 5, 21, 37, 53) ES_DPP4(1, 6, 22, 38, 54) ES_DPP4(2, 7, 23, 39, 55) ES_DPP4(3, 8, 24, 40, 56)
-      ES_DPP4(4, 9, 25, 41, 57) ES_DPP4(5, 10, 26, 42, 58) ES_DPP4(6, 11, 27, 43, 59) ES_DPP4(7, 12, 28, 44, 60)
-      ES_DPP4(8, 13, 29, 45, 61) ES_DPP4(9, 14, 30, 46, 62) ES_DPP4(10, 15, 31, 47, 63) ES_DPP4(11, 16, 32, 48, 64)
-      ES_DPP4(12, 17, 33, 49, 65) ES_DPP4(13, 18, 34, 50, 66) ES_DPP4(14, 19, 35, 51, 67) ES_DPP4(15, 20, 36, 52, 68)
-      : "+v"(o0), "+v"(o1), "+v"(o2), "+v"(o3)
+// The matrix-vector products.  "v_fmac_f32_dpp acc, h, w row_newbcast:j" adds w * (lane j of h's 16-lane row) to acc: the
+// input element is broadcast within each row by the DPP modifier, fused into the multiply-add - one instruction per
+// multiply-add, no scalar hop.  The compiler folds a DPP move into v_mul / v_add but not into v_fmac, so the runs below
+// are inline assembly.  Its hazard checks do not look inside inline assembly: a vector ALU write of `h` must be two
+// wait states away from the first DPP read, hence the s_nop that leads every run.  A run starts with multiplies (no
+// zeroed accumulators) and interleaves its accumulators, so that consecutive instructions never depend on each other.
+#define ES_DPP_TAIL(J) " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+#define ES_MUL(ACC, H, OP, J) "v_mul_f32_dpp %" #ACC ", %" #H ", %" #OP ES_DPP_TAIL(J)
+#define ES_MAC(ACC, H, OP, J) "v_fmac_f32_dpp %" #ACC ", %" #H ", %" #OP ES_DPP_TAIL(J)
+
+// o_q = sum_{j < N} w[N q + j] * (lane j of h's row), q = 0..3
+template <int N>
+__device__ __forceinline__ void row_bcast_dot_x4(float& o0, float& o1, float& o2, float& o3, float h, const float (&w)[4 * N]) {
+  static_assert(N == 3 || N == 5 || N == 16, "run lengths the register-resident shapes need");
+  if constexpr (N == 3)
+    asm volatile("s_nop 1\n\t"
+      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 8, 0) ES_MUL(2, 4, 11, 0) ES_MUL(3, 4, 14, 0)
+      ES_MAC(0, 4, 6, 1) ES_MAC(1, 4, 9, 1) ES_MAC(2, 4, 12, 1) ES_MAC(3, 4, 15, 1)
+      ES_MAC(0, 4, 7, 2) ES_MAC(1, 4, 10, 2) ES_MAC(2, 4, 13, 2) ES_MAC(3, 4, 16, 2)
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
       : "v"(h),
         "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
-        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]), "v"(w[20]),
-        "v"(w[21]), "v"(w[22]), "v"(w[23]), "v"(w[24]), "v"(w[25]), "v"(w[26]), "v"(w[27]), "v"(w[28]), "v"(w[29]), "v"(w[30]),
-        "v"(w[31]), "v"(w[32]), "v"(w[33]), "v"(w[34]), "v"(w[35]), "v"(w[36]), "v"(w[37]), "v"(w[38]), "v"(w[39]), "v"(w[40]),
-        "v"(w[41]), "v"(w[42]), "v"(w[43]), "v"(w[44]), "v"(w[45]), "v"(w[46]), "v"(w[47]), "v"(w[48]), "v"(w[49]), "v"(w[50]),
-        "v"(w[51]), "v"(w[52]), "v"(w[53]), "v"(w[54]), "v"(w[55]), "v"(w[56]), "v"(w[57]), "v"(w[58]), "v"(w[59]), "v"(w[60]),
-        "v"(w[61]), "v"(w[62]), "v"(w[63]));
-}
-#undef ES_DPP4
-// The same with N <= 6 inputs per row (the observation-wide products and the action term of the environment step).
-#define ES_DPP_FMAC(J, OP) "v_fmac_f32_dpp %0, %1, %" #OP " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-template <int N, int B, int M>
-__device__ __forceinline__ float row_bcast_mac(float acc, float h, const float (&w)[M]) {
-  static_assert(N == 3 || N == 5 || N == 6, "run lengths the two register-resident shapes need");
-  static_assert(B + N <= M, "weights of this run");
-  if constexpr (N == 3)
-    asm volatile("s_nop 1\n\t" ES_DPP_FMAC(0, 2) ES_DPP_FMAC(1, 3) ES_DPP_FMAC(2, 4)
-                 : "+v"(acc) : "v"(h), "v"(w[B]), "v"(w[B + 1]), "v"(w[B + 2]));
+        "v"(w[11]));
   else if constexpr (N == 5)
-    asm volatile("s_nop 1\n\t" ES_DPP_FMAC(0, 2) ES_DPP_FMAC(1, 3) ES_DPP_FMAC(2, 4) ES_DPP_FMAC(3, 5) ES_DPP_FMAC(4, 6)
-                 : "+v"(acc) : "v"(h), "v"(w[B]), "v"(w[B + 1]), "v"(w[B + 2]), "v"(w[B + 3]), "v"(w[B + 4]));
+    asm volatile("s_nop 1\n\t"
+      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 10, 0) ES_MUL(2, 4, 15, 0) ES_MUL(3, 4, 20, 0)
+      ES_MAC(0, 4, 6, 1) ES_MAC(1, 4, 11, 1) ES_MAC(2, 4, 16, 1) ES_MAC(3, 4, 21, 1)
+      ES_MAC(0, 4, 7, 2) ES_MAC(1, 4, 12, 2) ES_MAC(2, 4, 17, 2) ES_MAC(3, 4, 22, 2)
+      ES_MAC(0, 4, 8, 3) ES_MAC(1, 4, 13, 3) ES_MAC(2, 4, 18, 3) ES_MAC(3, 4, 23, 3)
+      ES_MAC(0, 4, 9, 4) ES_MAC(1, 4, 14, 4) ES_MAC(2, 4, 19, 4) ES_MAC(3, 4, 24, 4)
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+      : "v"(h),
+        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
+        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]));
   else
-    asm volatile("s_nop 1\n\t" ES_DPP_FMAC(0, 2) ES_DPP_FMAC(1, 3) ES_DPP_FMAC(2, 4) ES_DPP_FMAC(3, 5) ES_DPP_FMAC(4, 6) ES_DPP_FMAC(5, 7)
-                 : "+v"(acc) : "v"(h), "v"(w[B]), "v"(w[B + 1]), "v"(w[B + 2]), "v"(w[B + 3]), "v"(w[B + 4]), "v"(w[B + 5]));
+    asm volatile("s_nop 1\n\t"
+      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 21, 0) ES_MUL(2, 4, 37, 0) ES_MUL(3, 4, 53, 0)
+      ES_MAC(0, 4, 6, 1) ES_MAC(1, 4, 22, 1) ES_MAC(2, 4, 38, 1) ES_MAC(3, 4, 54, 1)
+      ES_MAC(0, 4, 7, 2) ES_MAC(1, 4, 23, 2) ES_MAC(2, 4, 39, 2) ES_MAC(3, 4, 55, 2)
+      ES_MAC(0, 4, 8, 3) ES_MAC(1, 4, 24, 3) ES_MAC(2, 4, 40, 3) ES_MAC(3, 4, 56, 3)
+      ES_MAC(0, 4, 9, 4) ES_MAC(1, 4, 25, 4) ES_MAC(2, 4, 41, 4) ES_MAC(3, 4, 57, 4)
+      ES_MAC(0, 4, 10, 5) ES_MAC(1, 4, 26, 5) ES_MAC(2, 4, 42, 5) ES_MAC(3, 4, 58, 5)
+      ES_MAC(0, 4, 11, 6) ES_MAC(1, 4, 27, 6) ES_MAC(2, 4, 43, 6) ES_MAC(3, 4, 59, 6)
+      ES_MAC(0, 4, 12, 7) ES_MAC(1, 4, 28, 7) ES_MAC(2, 4, 44, 7) ES_MAC(3, 4, 60, 7)
+      ES_MAC(0, 4, 13, 8) ES_MAC(1, 4, 29, 8) ES_MAC(2, 4, 45, 8) ES_MAC(3, 4, 61, 8)
+      ES_MAC(0, 4, 14, 9) ES_MAC(1, 4, 30, 9) ES_MAC(2, 4, 46, 9) ES_MAC(3, 4, 62, 9)
+      ES_MAC(0, 4, 15, 10) ES_MAC(1, 4, 31, 10) ES_MAC(2, 4, 47, 10) ES_MAC(3, 4, 63, 10)
+      ES_MAC(0, 4, 16, 11) ES_MAC(1, 4, 32, 11) ES_MAC(2, 4, 48, 11) ES_MAC(3, 4, 64, 11)
+      ES_MAC(0, 4, 17, 12) ES_MAC(1, 4, 33, 12) ES_MAC(2, 4, 49, 12) ES_MAC(3, 4, 65, 12)
+      ES_MAC(0, 4, 18, 13) ES_MAC(1, 4, 34, 13) ES_MAC(2, 4, 50, 13) ES_MAC(3, 4, 66, 13)
+      ES_MAC(0, 4, 19, 14) ES_MAC(1, 4, 35, 14) ES_MAC(2, 4, 51, 14) ES_MAC(3, 4, 67, 14)
+      ES_MAC(0, 4, 20, 15) ES_MAC(1, 4, 36, 15) ES_MAC(2, 4, 52, 15) ES_MAC(3, 4, 68, 15)
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+      : "v"(h),
+        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
+        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]), "v"(w[20]), "v"(w[21]),
+        "v"(w[22]), "v"(w[23]), "v"(w[24]), "v"(w[25]), "v"(w[26]), "v"(w[27]), "v"(w[28]), "v"(w[29]), "v"(w[30]), "v"(w[31]), "v"(w[32]),
+        "v"(w[33]), "v"(w[34]), "v"(w[35]), "v"(w[36]), "v"(w[37]), "v"(w[38]), "v"(w[39]), "v"(w[40]), "v"(w[41]), "v"(w[42]), "v"(w[43]),
+        "v"(w[44]), "v"(w[45]), "v"(w[46]), "v"(w[47]), "v"(w[48]), "v"(w[49]), "v"(w[50]), "v"(w[51]), "v"(w[52]), "v"(w[53]), "v"(w[54]),
+        "v"(w[55]), "v"(w[56]), "v"(w[57]), "v"(w[58]), "v"(w[59]), "v"(w[60]), "v"(w[61]), "v"(w[62]), "v"(w[63]));
+}
+// the same for two accumulators (hidden width 32)
+template <int N>
+__device__ __forceinline__ void row_bcast_dot_x2(float& o0, float& o1, float h, const float (&w)[2 * N]) {
+  static_assert(N == 3 || N == 16, "run lengths the register-resident shapes need");
+  if constexpr (N == 3)
+    asm volatile("s_nop 1\n\t"
+      ES_MUL(0, 2, 3, 0) ES_MUL(1, 2, 6, 0)
+      ES_MAC(0, 2, 4, 1) ES_MAC(1, 2, 7, 1)
+      ES_MAC(0, 2, 5, 2) ES_MAC(1, 2, 8, 2)
+      : "=&v"(o0), "=&v"(o1)
+      : "v"(h),
+        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]));
+  else
+    asm volatile("s_nop 1\n\t"
+      ES_MUL(0, 2, 3, 0) ES_MUL(1, 2, 19, 0)
+      ES_MAC(0, 2, 4, 1) ES_MAC(1, 2, 20, 1)
+      ES_MAC(0, 2, 5, 2) ES_MAC(1, 2, 21, 2)
+      ES_MAC(0, 2, 6, 3) ES_MAC(1, 2, 22, 3)
+      ES_MAC(0, 2, 7, 4) ES_MAC(1, 2, 23, 4)
+      ES_MAC(0, 2, 8, 5) ES_MAC(1, 2, 24, 5)
+      ES_MAC(0, 2, 9, 6) ES_MAC(1, 2, 25, 6)
+      ES_MAC(0, 2, 10, 7) ES_MAC(1, 2, 26, 7)
+      ES_MAC(0, 2, 11, 8) ES_MAC(1, 2, 27, 8)
+      ES_MAC(0, 2, 12, 9) ES_MAC(1, 2, 28, 9)
+      ES_MAC(0, 2, 13, 10) ES_MAC(1, 2, 29, 10)
+      ES_MAC(0, 2, 14, 11) ES_MAC(1, 2, 30, 11)
+      ES_MAC(0, 2, 15, 12) ES_MAC(1, 2, 31, 12)
+      ES_MAC(0, 2, 16, 13) ES_MAC(1, 2, 32, 13)
+      ES_MAC(0, 2, 17, 14) ES_MAC(1, 2, 33, 14)
+      ES_MAC(0, 2, 18, 15) ES_MAC(1, 2, 34, 15)
+      : "=&v"(o0), "=&v"(o1)
+      : "v"(h),
+        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
+        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]), "v"(w[20]), "v"(w[21]),
+        "v"(w[22]), "v"(w[23]), "v"(w[24]), "v"(w[25]), "v"(w[26]), "v"(w[27]), "v"(w[28]), "v"(w[29]), "v"(w[30]), "v"(w[31]));
+}
+// sum_{j < 16} w[j] * (lane j of h's row), in four interleaved partial sums
+__device__ __forceinline__ float row_bcast_dot16(float h, const float (&w)[16]) {
+  float o0, o1, o2, o3;
+  asm volatile("s_nop 1\n\t"
+      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 6, 1) ES_MUL(2, 4, 7, 2) ES_MUL(3, 4, 8, 3)
+      ES_MAC(0, 4, 9, 4) ES_MAC(1, 4, 10, 5) ES_MAC(2, 4, 11, 6) ES_MAC(3, 4, 12, 7)
+      ES_MAC(0, 4, 13, 8) ES_MAC(1, 4, 14, 9) ES_MAC(2, 4, 15, 10) ES_MAC(3, 4, 16, 11)
+      ES_MAC(0, 4, 17, 12) ES_MAC(1, 4, 18, 13) ES_MAC(2, 4, 19, 14) ES_MAC(3, 4, 20, 15)
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+      : "v"(h),
+        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
+        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]));
+  return (o0 + o1) + (o2 + o3);
+}
+// acc + sum_{j < N} w[j] * (lane j of h's row): the short action term of the environment step
+template <int N>
+__device__ __forceinline__ float row_bcast_mac(float acc, float h, const float (&w)[N]) {
+  static_assert(N == 3 || N == 6, "action widths of the register-resident shapes");
+  if constexpr (N == 3)
+    asm volatile("s_nop 1\n\t" ES_MAC(0, 1, 2, 0) ES_MAC(0, 1, 3, 1) ES_MAC(0, 1, 4, 2)
+                 : "+v"(acc) : "v"(h), "v"(w[0]), "v"(w[1]), "v"(w[2]));
+  else
+    asm volatile("s_nop 1\n\t" ES_MAC(0, 1, 2, 0) ES_MAC(0, 1, 3, 1) ES_MAC(0, 1, 4, 2) ES_MAC(0, 1, 5, 3) ES_MAC(0, 1, 6, 4) ES_MAC(0, 1, 7, 5)
+                 : "+v"(acc) : "v"(h), "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]));
   return acc;
 }
-#undef ES_DPP_FMAC
+#undef ES_MAC
+#undef ES_MUL
+#undef ES_DPP_TAIL
 // x + (the same register of the other 16-lane row of the pair / of the other half), via the row-swap instructions
 __device__ __forceinline__ float swap16_add(float x, float y) {   // rows (0,1,2,3) <- x0+y... see the caller
   const auto p = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
@@ -211,14 +264,14 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     // h1 = tanh(W1 s + b1)
     const float xp = (s - mu) * iv;      // the policy's input (paper App. B: fixed normalisation statistics)
     float l1;
-    {
-      const float p0 = row_bcast_mac<CJ, 0>(0.f, xp, w1), p1 = row_bcast_mac<CJ, CJ>(0.f, xp, w1);
-      if (NQ == 4) {
-        const float p2 = row_bcast_mac<CJ, NQ == 4 ? 2 * CJ : 0>(0.f, xp, w1), p3 = row_bcast_mac<CJ, NQ == 4 ? 3 * CJ : 0>(0.f, xp, w1);
-        l1 = rows_transpose_add(p0, p1, p2, p3);
-      } else {
-        l1 = rows_transpose_add(p0, p1);
-      }
+    if constexpr (NQ == 4) {
+      float p0, p1, p2, p3;
+      row_bcast_dot_x4<CJ>(p0, p1, p2, p3, xp, w1);
+      l1 = rows_transpose_add(p0, p1, p2, p3);
+    } else {
+      float p0, p1;
+      row_bcast_dot_x2<CJ>(p0, p1, xp, w1);
+      l1 = rows_transpose_add(p0, p1);
     }
     l1 += b1;
     const float h1 = RELU ? fmaxf(l1, 0.f) : tanh_fast(l1);
@@ -226,18 +279,19 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     // then the rows' partial sums are added and moved to the lane of their unit by two row-swap stages
     float l2;
     if constexpr (NQ == 4) {
-      float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
-      row_bcast_mac16x4(p0, p1, p2, p3, h1, w2);
+      float p0, p1, p2, p3;
+      row_bcast_dot_x4<16>(p0, p1, p2, p3, h1, w2);
       l2 = rows_transpose_add(p0, p1, p2, p3);
     } else {
-      const float p0 = row_bcast_mac16<0>(0.f, h1, w2), p1 = row_bcast_mac16<16>(0.f, h1, w2);
-      l2 = swap16_add(p0, p1);          // h1 is zero in rows 2 and 3
+      float p0, p1;
+      row_bcast_dot_x2<16>(p0, p1, h1, w2);
+      l2 = swap16_add(p0, p1);          // the units' own rows 0 and 1 hold all of their inputs; rows 2 and 3 have zero weights
     }
     l2 += b2;
     const float h2 = RELU ? fmaxf(l2, 0.f) : tanh_fast(l2);
     // a = tanh(W3 h2 + b3): row-broadcast multiply-adds as above, the four rows' partial sums added by two row swaps;
     // column c of every row then holds unit c's total, and one tanh serves all units
-    float pv = row_bcast_mac16<0>(0.f, h2, w3);
+    float pv = row_bcast_dot16(h2, w3);
     pv = swap16_add(pv, pv);
     pv = swap32_add(pv, pv);
     pv = pv + b3;
@@ -252,11 +306,11 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     // and moved to their element's lane; the action term straight from the row's action vector
     float pre;
     {
-      const float e0 = row_bcast_mac<CJ, 0>(0.f, s, ar), e1 = row_bcast_mac<CJ, CJ>(0.f, s, ar);
-      const float e2 = row_bcast_mac<CJ, 2 * CJ>(0.f, s, ar), e3 = row_bcast_mac<CJ, 3 * CJ>(0.f, s, ar);
+      float e0, e1, e2, e3;
+      row_bcast_dot_x4<CJ>(e0, e1, e2, e3, s, ar);
       pre = rows_transpose_add(e0, e1, e2, e3);
     }
-    pre = row_bcast_mac<NA, 0>(pre, tv, br);
+    pre = row_bcast_mac<NA>(pre, tv, br);
     s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
     if (__ballot(fabsf(s) > a.done_thresh) != 0ull) break;       // max |s| > threshold: some lane exceeds it
   }
