@@ -195,7 +195,7 @@ __device__ __forceinline__ float row_total(float v) {
 // RELU / OUT_TANH: the activations are compile-time choices, and lanes that own no unit need no masking (their weights
 // and biases are zero, and both activations map 0 to 0), so a step is one straight-line block: a taken branch costs
 // this single in-order wavefront more than the few instructions it would skip.
-template <int NO, int NH, int NA, bool RELU, bool OUT_TANH>
+template <int NO, int NH, int NA, bool RELU, bool OUT_TANH, bool NORM>
 __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   static_assert(NH <= 64 && NO <= 64 && NA <= 64, "one lane per unit");
   static_assert(NH == 32 || NH == 64, "the second layer is tiled over whole 16-lane rows");
@@ -252,17 +252,17 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
 #pragma unroll
   for (int c = 0; c < NA; ++c) br[c] = sval ? a.B[ks * NA + c] : 0.f;
 
-  // frozen observation statistics of this lane's state element (identity when none are set: (s - 0) * 1 = s exactly)
-  const float mu = (sval && a.obs_mean) ? a.obs_mean[ks] : 0.f;
-  const float iv = (sval && a.obs_mean) ? a.obs_inv[ks] : 1.f;
+  // frozen observation statistics of this lane's state element (NORM: a context with statistics set)
+  const float mu = (NORM && sval) ? a.obs_mean[ks] : 0.f;
+  const float iv = (NORM && sval) ? a.obs_inv[ks] : 1.f;
   float s = sval ? reset_value((uint32_t)ks, e, a.gen, a.k0, a.k1) : 0.f;
-  float R = 0.f;                      // meaningful in lane 15 (where the row reductions end), stored from there
+  float R = 0.f;                      // per-lane share of the return
   int32_t len = 0;
   const float inv_no = 1.0f / (float)NO, quarter_cost = 0.25f * a.act_cost;
 
   for (uint32_t t = 0; t < a.T; ++t) {
     // h1 = tanh(W1 s + b1)
-    const float xp = (s - mu) * iv;      // the policy's input (paper App. B: fixed normalisation statistics)
+    const float xp = NORM ? (s - mu) * iv : s;      // the policy's input (paper App. B: fixed normalisation statistics)
     float l1;
     if constexpr (NQ == 4) {
       float p0, p1, p2, p3;
@@ -296,11 +296,9 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     pv = swap32_add(pv, pv);
     pv = pv + b3;
     const float tv = OUT_TANH ? tanh_fast(pv) : pv;      // columns >= act: weights and bias are zero
-    // reward from the pre-step state, 1 - |s|^2 / obs - cost |a|^2, as one sum over all 64 lanes (the action vector is
-    // held once per row, hence the quarter) that ends in lane 15
-    const float rl = __fmaf_rn(-inv_no * s, s, -quarter_cost * (tv * tv));
-    const float rl2 = swap16_add(rl, rl);
-    R += 1.0f + row_total(swap32_add(rl2, rl2));
+    // reward from the pre-step state, 1 - |s|^2 / obs - cost |a|^2: a sum over all 64 lanes (the action vector is held
+    // once per row, hence the quarter)
+    R += __fmaf_rn(-inv_no * s, s, -quarter_cost * (tv * tv));      // this lane's share; the lanes are added after the last step
     len += 1;
     // s' = tanh(A s + B a): partial sums of the four elements of this column over the inputs of this row, rows added
     // and moved to their element's lane; the action term straight from the row's action vector
@@ -314,12 +312,15 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
     if (__ballot(fabsf(s) > a.done_thresh) != 0ull) break;       // max |s| > threshold: some lane exceeds it
   }
+  const float r2 = swap16_add(R, R);
+  R = (float)len + row_total(swap32_add(r2, r2));      // ends in lane 15
   if (u == 15) {
     a.returns[(size_t)i * a.E + e] = R;
     a.ep_len[(size_t)i * a.E + e] = len;
   }
 }
 
+template <int O, int H, int A> struct RegWidths { static constexpr int no = O, nh = H, na = A; };
 struct RegShape { uint32_t no, nh, na; const char* name; };
 static const RegShape kRegShapes[] = {
     {11, 32, 3, "rollout_wave_reg_f32<11,32,3>"},
@@ -347,17 +348,25 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   a.antithetic = c.antithetic; a.noise_mode = nv.mode;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const dim3 grid(s.N * s.E), block(64);
-  const bool relu = c.hidden_act == 1, otanh = c.out_tanh != 0;
+  const bool relu = c.hidden_act == 1, otanh = c.out_tanh != 0, norm = ctx->obs_mean != nullptr;
   auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, st, a); };
+  auto pick = [&](auto shape) {       // shape carries the three widths; the activations and the statistics select the variant
+    constexpr int O = decltype(shape)::no, H = decltype(shape)::nh, A = decltype(shape)::na;
+    const int v = (relu ? 4 : 0) | (otanh ? 2 : 0) | (norm ? 1 : 0);
+    switch (v) {
+      case 0: go(rollout_reg_kernel<O, H, A, false, false, false>); break;
+      case 1: go(rollout_reg_kernel<O, H, A, false, false, true>); break;
+      case 2: go(rollout_reg_kernel<O, H, A, false, true, false>); break;
+      case 3: go(rollout_reg_kernel<O, H, A, false, true, true>); break;
+      case 4: go(rollout_reg_kernel<O, H, A, true, false, false>); break;
+      case 5: go(rollout_reg_kernel<O, H, A, true, false, true>); break;
+      case 6: go(rollout_reg_kernel<O, H, A, true, true, false>); break;
+      default: go(rollout_reg_kernel<O, H, A, true, true, true>); break;
+    }
+  };
   switch (ctx->reg_variant) {
-    case 0:
-      if (relu) { if (otanh) go(rollout_reg_kernel<11, 32, 3, true, true>); else go(rollout_reg_kernel<11, 32, 3, true, false>); }
-      else { if (otanh) go(rollout_reg_kernel<11, 32, 3, false, true>); else go(rollout_reg_kernel<11, 32, 3, false, false>); }
-      break;
-    case 1:
-      if (relu) { if (otanh) go(rollout_reg_kernel<17, 64, 6, true, true>); else go(rollout_reg_kernel<17, 64, 6, true, false>); }
-      else { if (otanh) go(rollout_reg_kernel<17, 64, 6, false, true>); else go(rollout_reg_kernel<17, 64, 6, false, false>); }
-      break;
+    case 0: pick(RegWidths<11, 32, 3>{}); break;
+    case 1: pick(RegWidths<17, 64, 6>{}); break;
     default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident binary32 variant for this shape");
   }
   int rc = check_launch(ctx, "es_rollout (register-resident f32)");
