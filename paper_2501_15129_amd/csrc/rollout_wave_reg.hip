@@ -1,18 +1,25 @@
-// es_rollout, register-resident binary32 variant for narrow policies (hidden width <= 64).
+// es_rollout, register-resident binary32 kernel for narrow policies (obs, hidden <= 64, act <= 16, two hidden layers).
 //
 // Paper Sec. 3.2 / 5.2: population x environment-copy evaluation of a deterministic
 // two-hidden-layer MLP policy, fitness = mean undiscounted return.  One wavefront runs one
-// (individual, environment copy) episode; lane u owns hidden unit u, and the state vector is spread
-// over the four 16-lane rows of the wavefront (element k in row k % 4, column k / 4).  The individual's
-// perturbed weights (theta + sign*sigma*eps, fused into the load) and the environment matrices live in
-// registers for all T steps.
+// (individual, environment copy) episode.  Lane u owns hidden unit u (with at most 16 hidden units every
+// 16-lane row owns all of them), and the state vector is spread over the four 16-lane rows of the
+// wavefront (element k in row k % 4, column k / 4).  The individual's perturbed weights
+// (theta + sign*sigma*eps) pass through LDS once, in coalesced order, and then live in registers for all
+// T steps, as do the environment matrices.
 // Every matrix-vector product broadcasts its inputs within the 16-lane rows by DPP, fused into the
 // multiply-add (v_fmac_f32_dpp ... row_newbcast:j, one instruction per multiply-add, no scalar hop):
 // the lane in row r, column c adds up the inputs that live in ITS row into partial sums for the outputs
 // that belong to ITS column (hidden units c, c + 16, ...; state elements 4 c .. 4 c + 3), and two
 // row-swap stages (v_permlane32_swap, v_permlane16_swap + add) add the four rows' partial sums and
-// leave each output's total in the lane that owns it.  The reward norms are reduced the same way and end
-// in lane 15.  No LDS, no barriers, one scalar read per step (the termination test).
+// leave each output's total in the lane that owns it.  A step is one straight-line block: no LDS, no
+// barriers, no masks (lanes without a unit have zero weights, and tanh and ReLU map 0 to 0), the return is
+// accumulated per lane and reduced after the last step, termination is one compare whose mask is the
+// branch condition.
+// The run lengths (inputs per row, rows of hidden units, action width) are compile-time: exact for the
+// benchmark shapes 11-32-3 and 17-64-6, whose activations and observation statistics are compile-time
+// variants too, and rounded up to a few classes for every other shape (padding has zero weights), where
+// the activations are chosen by branch-free selects.
 // Bound: the dependent instruction chain of one step times T (the workloads that use this
 // kernel have 32-256 episodes for 1024 SIMDs).
 #include "es_device.hpp"
@@ -30,144 +37,23 @@ struct RegArgs {
   const float* obs_inv;
   float* returns;
   int32_t* ep_len;
-  uint32_t N, E, T, ld;
+  uint32_t N, E, T, ld, D;
+  uint32_t no, nh, na;
+  uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
-  uint32_t antithetic, noise_mode;
+  uint32_t antithetic, noise_mode, hidden_relu, out_tanh;
   float sigma, done_thresh, act_cost;
 };
+
+#include "dpp_runs.inc"
 
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_zero(float v) {      // lanes without a source (or masked off) read 0
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF));
 }
-// The matrix-vector products.  "v_fmac_f32_dpp acc, h, w row_newbcast:j" adds w * (lane j of h's 16-lane row) to acc: the
-// input element is broadcast within each row by the DPP modifier, fused into the multiply-add - one instruction per
-// multiply-add, no scalar hop.  The compiler folds a DPP move into v_mul / v_add but not into v_fmac, so the runs below
-// are inline assembly.  Its hazard checks do not look inside inline assembly: a vector ALU write of `h` must be two
-// wait states away from the first DPP read, hence the s_nop that leads every run.  A run starts with multiplies (no
-// zeroed accumulators) and interleaves its accumulators, so that consecutive instructions never depend on each other.
-#define ES_DPP_TAIL(J) " row_newbcast:" #J " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-#define ES_MUL(ACC, H, OP, J) "v_mul_f32_dpp %" #ACC ", %" #H ", %" #OP ES_DPP_TAIL(J)
-#define ES_MAC(ACC, H, OP, J) "v_fmac_f32_dpp %" #ACC ", %" #H ", %" #OP ES_DPP_TAIL(J)
-
-// o_q = sum_{j < N} w[N q + j] * (lane j of h's row), q = 0..3
-template <int N>
-__device__ __forceinline__ void row_bcast_dot_x4(float& o0, float& o1, float& o2, float& o3, float h, const float (&w)[4 * N]) {
-  static_assert(N == 3 || N == 5 || N == 16, "run lengths the register-resident shapes need");
-  if constexpr (N == 3)
-    asm volatile("s_nop 1\n\t"
-      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 8, 0) ES_MUL(2, 4, 11, 0) ES_MUL(3, 4, 14, 0)
-      ES_MAC(0, 4, 6, 1) ES_MAC(1, 4, 9, 1) ES_MAC(2, 4, 12, 1) ES_MAC(3, 4, 15, 1)
-      ES_MAC(0, 4, 7, 2) ES_MAC(1, 4, 10, 2) ES_MAC(2, 4, 13, 2) ES_MAC(3, 4, 16, 2)
-      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
-      : "v"(h),
-        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
-        "v"(w[11]));
-  else if constexpr (N == 5)
-    asm volatile("s_nop 1\n\t"
-      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 10, 0) ES_MUL(2, 4, 15, 0) ES_MUL(3, 4, 20, 0)
-      ES_MAC(0, 4, 6, 1) ES_MAC(1, 4, 11, 1) ES_MAC(2, 4, 16, 1) ES_MAC(3, 4, 21, 1)
-      ES_MAC(0, 4, 7, 2) ES_MAC(1, 4, 12, 2) ES_MAC(2, 4, 17, 2) ES_MAC(3, 4, 22, 2)
-      ES_MAC(0, 4, 8, 3) ES_MAC(1, 4, 13, 3) ES_MAC(2, 4, 18, 3) ES_MAC(3, 4, 23, 3)
-      ES_MAC(0, 4, 9, 4) ES_MAC(1, 4, 14, 4) ES_MAC(2, 4, 19, 4) ES_MAC(3, 4, 24, 4)
-      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
-      : "v"(h),
-        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
-        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]));
-  else
-    asm volatile("s_nop 1\n\t"
-      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 21, 0) ES_MUL(2, 4, 37, 0) ES_MUL(3, 4, 53, 0)
-      ES_MAC(0, 4, 6, 1) ES_MAC(1, 4, 22, 1) ES_MAC(2, 4, 38, 1) ES_MAC(3, 4, 54, 1)
-      ES_MAC(0, 4, 7, 2) ES_MAC(1, 4, 23, 2) ES_MAC(2, 4, 39, 2) ES_MAC(3, 4, 55, 2)
-      ES_MAC(0, 4, 8, 3) ES_MAC(1, 4, 24, 3) ES_MAC(2, 4, 40, 3) ES_MAC(3, 4, 56, 3)
-      ES_MAC(0, 4, 9, 4) ES_MAC(1, 4, 25, 4) ES_MAC(2, 4, 41, 4) ES_MAC(3, 4, 57, 4)
-      ES_MAC(0, 4, 10, 5) ES_MAC(1, 4, 26, 5) ES_MAC(2, 4, 42, 5) ES_MAC(3, 4, 58, 5)
-      ES_MAC(0, 4, 11, 6) ES_MAC(1, 4, 27, 6) ES_MAC(2, 4, 43, 6) ES_MAC(3, 4, 59, 6)
-      ES_MAC(0, 4, 12, 7) ES_MAC(1, 4, 28, 7) ES_MAC(2, 4, 44, 7) ES_MAC(3, 4, 60, 7)
-      ES_MAC(0, 4, 13, 8) ES_MAC(1, 4, 29, 8) ES_MAC(2, 4, 45, 8) ES_MAC(3, 4, 61, 8)
-      ES_MAC(0, 4, 14, 9) ES_MAC(1, 4, 30, 9) ES_MAC(2, 4, 46, 9) ES_MAC(3, 4, 62, 9)
-      ES_MAC(0, 4, 15, 10) ES_MAC(1, 4, 31, 10) ES_MAC(2, 4, 47, 10) ES_MAC(3, 4, 63, 10)
-      ES_MAC(0, 4, 16, 11) ES_MAC(1, 4, 32, 11) ES_MAC(2, 4, 48, 11) ES_MAC(3, 4, 64, 11)
-      ES_MAC(0, 4, 17, 12) ES_MAC(1, 4, 33, 12) ES_MAC(2, 4, 49, 12) ES_MAC(3, 4, 65, 12)
-      ES_MAC(0, 4, 18, 13) ES_MAC(1, 4, 34, 13) ES_MAC(2, 4, 50, 13) ES_MAC(3, 4, 66, 13)
-      ES_MAC(0, 4, 19, 14) ES_MAC(1, 4, 35, 14) ES_MAC(2, 4, 51, 14) ES_MAC(3, 4, 67, 14)
-      ES_MAC(0, 4, 20, 15) ES_MAC(1, 4, 36, 15) ES_MAC(2, 4, 52, 15) ES_MAC(3, 4, 68, 15)
-      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
-      : "v"(h),
-        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
-        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]), "v"(w[20]), "v"(w[21]),
-        "v"(w[22]), "v"(w[23]), "v"(w[24]), "v"(w[25]), "v"(w[26]), "v"(w[27]), "v"(w[28]), "v"(w[29]), "v"(w[30]), "v"(w[31]), "v"(w[32]),
-        "v"(w[33]), "v"(w[34]), "v"(w[35]), "v"(w[36]), "v"(w[37]), "v"(w[38]), "v"(w[39]), "v"(w[40]), "v"(w[41]), "v"(w[42]), "v"(w[43]),
-        "v"(w[44]), "v"(w[45]), "v"(w[46]), "v"(w[47]), "v"(w[48]), "v"(w[49]), "v"(w[50]), "v"(w[51]), "v"(w[52]), "v"(w[53]), "v"(w[54]),
-        "v"(w[55]), "v"(w[56]), "v"(w[57]), "v"(w[58]), "v"(w[59]), "v"(w[60]), "v"(w[61]), "v"(w[62]), "v"(w[63]));
-}
-// the same for two accumulators (hidden width 32)
-template <int N>
-__device__ __forceinline__ void row_bcast_dot_x2(float& o0, float& o1, float h, const float (&w)[2 * N]) {
-  static_assert(N == 3 || N == 16, "run lengths the register-resident shapes need");
-  if constexpr (N == 3)
-    asm volatile("s_nop 1\n\t"
-      ES_MUL(0, 2, 3, 0) ES_MUL(1, 2, 6, 0)
-      ES_MAC(0, 2, 4, 1) ES_MAC(1, 2, 7, 1)
-      ES_MAC(0, 2, 5, 2) ES_MAC(1, 2, 8, 2)
-      : "=&v"(o0), "=&v"(o1)
-      : "v"(h),
-        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]));
-  else
-    asm volatile("s_nop 1\n\t"
-      ES_MUL(0, 2, 3, 0) ES_MUL(1, 2, 19, 0)
-      ES_MAC(0, 2, 4, 1) ES_MAC(1, 2, 20, 1)
-      ES_MAC(0, 2, 5, 2) ES_MAC(1, 2, 21, 2)
-      ES_MAC(0, 2, 6, 3) ES_MAC(1, 2, 22, 3)
-      ES_MAC(0, 2, 7, 4) ES_MAC(1, 2, 23, 4)
-      ES_MAC(0, 2, 8, 5) ES_MAC(1, 2, 24, 5)
-      ES_MAC(0, 2, 9, 6) ES_MAC(1, 2, 25, 6)
-      ES_MAC(0, 2, 10, 7) ES_MAC(1, 2, 26, 7)
-      ES_MAC(0, 2, 11, 8) ES_MAC(1, 2, 27, 8)
-      ES_MAC(0, 2, 12, 9) ES_MAC(1, 2, 28, 9)
-      ES_MAC(0, 2, 13, 10) ES_MAC(1, 2, 29, 10)
-      ES_MAC(0, 2, 14, 11) ES_MAC(1, 2, 30, 11)
-      ES_MAC(0, 2, 15, 12) ES_MAC(1, 2, 31, 12)
-      ES_MAC(0, 2, 16, 13) ES_MAC(1, 2, 32, 13)
-      ES_MAC(0, 2, 17, 14) ES_MAC(1, 2, 33, 14)
-      ES_MAC(0, 2, 18, 15) ES_MAC(1, 2, 34, 15)
-      : "=&v"(o0), "=&v"(o1)
-      : "v"(h),
-        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
-        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]), "v"(w[16]), "v"(w[17]), "v"(w[18]), "v"(w[19]), "v"(w[20]), "v"(w[21]),
-        "v"(w[22]), "v"(w[23]), "v"(w[24]), "v"(w[25]), "v"(w[26]), "v"(w[27]), "v"(w[28]), "v"(w[29]), "v"(w[30]), "v"(w[31]));
-}
-// sum_{j < 16} w[j] * (lane j of h's row), in four interleaved partial sums
-__device__ __forceinline__ float row_bcast_dot16(float h, const float (&w)[16]) {
-  float o0, o1, o2, o3;
-  asm volatile("s_nop 1\n\t"
-      ES_MUL(0, 4, 5, 0) ES_MUL(1, 4, 6, 1) ES_MUL(2, 4, 7, 2) ES_MUL(3, 4, 8, 3)
-      ES_MAC(0, 4, 9, 4) ES_MAC(1, 4, 10, 5) ES_MAC(2, 4, 11, 6) ES_MAC(3, 4, 12, 7)
-      ES_MAC(0, 4, 13, 8) ES_MAC(1, 4, 14, 9) ES_MAC(2, 4, 15, 10) ES_MAC(3, 4, 16, 11)
-      ES_MAC(0, 4, 17, 12) ES_MAC(1, 4, 18, 13) ES_MAC(2, 4, 19, 14) ES_MAC(3, 4, 20, 15)
-      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
-      : "v"(h),
-        "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]), "v"(w[8]), "v"(w[9]), "v"(w[10]),
-        "v"(w[11]), "v"(w[12]), "v"(w[13]), "v"(w[14]), "v"(w[15]));
-  return (o0 + o1) + (o2 + o3);
-}
-// acc + sum_{j < N} w[j] * (lane j of h's row): the short action term of the environment step
-template <int N>
-__device__ __forceinline__ float row_bcast_mac(float acc, float h, const float (&w)[N]) {
-  static_assert(N == 3 || N == 6, "action widths of the register-resident shapes");
-  if constexpr (N == 3)
-    asm volatile("s_nop 1\n\t" ES_MAC(0, 1, 2, 0) ES_MAC(0, 1, 3, 1) ES_MAC(0, 1, 4, 2)
-                 : "+v"(acc) : "v"(h), "v"(w[0]), "v"(w[1]), "v"(w[2]));
-  else
-    asm volatile("s_nop 1\n\t" ES_MAC(0, 1, 2, 0) ES_MAC(0, 1, 3, 1) ES_MAC(0, 1, 4, 2) ES_MAC(0, 1, 5, 3) ES_MAC(0, 1, 6, 4) ES_MAC(0, 1, 7, 5)
-                 : "+v"(acc) : "v"(h), "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]));
-  return acc;
-}
-#undef ES_MAC
-#undef ES_MUL
-#undef ES_DPP_TAIL
-// x + (the same register of the other 16-lane row of the pair / of the other half), via the row-swap instructions
-__device__ __forceinline__ float swap16_add(float x, float y) {   // rows (0,1,2,3) <- x0+y... see the caller
+// x + y after a row swap: permlane16_swap exchanges the odd rows of x with the even rows of y, permlane32_swap the
+// upper two rows of x with the lower two of y
+__device__ __forceinline__ float swap16_add(float x, float y) {
   const auto p = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
   return __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
 }
@@ -184,6 +70,11 @@ __device__ __forceinline__ float rows_transpose_add(float x0, float x1) {
   const float t = swap16_add(x0, x1);
   return swap32_add(t, t);
 }
+// the sum over the four rows, in every row
+__device__ __forceinline__ float rows_add(float x) {
+  const float t = swap16_add(x, x);
+  return swap32_add(t, t);
+}
 // sum over the lanes of each 16-lane row, result in lane 15 of the row (lanes without a source read 0)
 __device__ __forceinline__ float row_total(float v) {
   v += dpp_zero<0x111, 0xF>(v);
@@ -192,148 +83,198 @@ __device__ __forceinline__ float row_total(float v) {
   return v + dpp_zero<0x118, 0xF>(v);
 }
 
-// RELU / OUT_TANH: the activations are compile-time choices, and lanes that own no unit need no masking (their weights
-// and biases are zero, and both activations map 0 to 0), so a step is one straight-line block: a taken branch costs
-// this single in-order wavefront more than the few instructions it would skip.
-template <int NO, int NH, int NA, bool RELU, bool OUT_TANH, bool NORM>
+// CJ: state elements per row (ceil(obs / 4), or its class); NQ: 16-lane rows of hidden units (1, 2, 4); NAR: action
+// run length (act, or its class).  MODE 0..7 = ReLU (4) | tanh on the action layer (2) | observation statistics (1)
+// fixed at compile time; MODE < 0: read from the arguments and applied by selects.
+template <int CJ, int NQ, int NAR, int MODE>
 __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
-  static_assert(NH <= 64 && NO <= 64 && NA <= 64, "one lane per unit");
-  static_assert(NH == 32 || NH == 64, "the second layer is tiled over whole 16-lane rows");
-  static_assert(NA <= 16, "one 16-lane row of action units");
-  constexpr int NQ = NH / 16;      // 16-lane rows that hold hidden units
-  constexpr uint32_t oW1 = 0, ob1 = NH * NO, oW2 = ob1 + NH, ob2 = oW2 + NH * NH, oW3 = ob2 + NH, ob3 = oW3 + NA * NH;
+  static_assert(NQ == 1 || NQ == 2 || NQ == 4, "rows of hidden units");
+  constexpr bool FIXED = MODE >= 0;
+  constexpr bool RELU = FIXED && (MODE & 4), OUT_TANH = FIXED && (MODE & 2), NORM = !FIXED || (MODE & 1);
+  extern __shared__ float sp[];      // the individual's perturbed parameters, once
   const int u = threadIdx.x;
   const uint32_t i = blockIdx.x / a.E, e = blockIdx.x % a.E;
   const uint32_t row = a.antithetic ? (i >> 1) : i;
   const float scale = (a.antithetic && (i & 1u)) ? -a.sigma : a.sigma;
-  const bool hid = u < NH;
-  // Lane (row lr, column lc).  Hidden unit u lives in lane u.  The state is spread over the four rows so that every row
-  // holds a quarter of it: element k sits in row k % 4, column k / 4 - then a row-broadcast run of CJ = ceil(obs / 4)
-  // multiply-adds per output covers a whole observation-wide product, all four rows working.
+  const int no = (int)a.no, nh = (int)a.nh, na = (int)a.na;
   const int lr = u >> 4, lc = u & 15;
-  constexpr int CJ = (NO + 3) / 4;
   const int ks = 4 * lc + lr;                    // the state element of this lane
-  const bool sval = lc < CJ && ks < NO;
+  const bool sval = lc < CJ && ks < no;
+  const int hu = NQ == 1 ? lc : u;               // the hidden unit of this lane
+  const bool hid = hu < nh;
 
-  const void* nbase = a.noise;      // shared table: this individual's row, addressed as row 0
-  uint32_t nrow = row;
-  if (a.noise_offs) { nbase = table_row_base(a.noise_mode, a.noise, a.noise_offs, row); nrow = 0u; }
-  auto param = [&](uint32_t d) -> float {     // perturbed parameter d of individual i (binary32, one rounding)
-    return __fmaf_rn(scale, noise_value(a.noise_mode, nbase, a.ld, nrow, d, a.gen, a.k0, a.k1), a.theta[d]);
-  };
+  // ---- perturbed parameters -> LDS (coalesced, binary32, one rounding each) ----
+  {
+    const void* nbase = a.noise;      // shared table: this individual's row, addressed as row 0
+    uint32_t nrow = row;
+    if (a.noise_offs) { nbase = table_row_base(a.noise_mode, a.noise, a.noise_offs, row); nrow = 0u; }
+    if (a.noise_mode >= 2u) {       // regenerated noise: one counter block gives four consecutive parameters
+      for (uint32_t d0 = 4u * (uint32_t)u; d0 < a.D; d0 += 256u) {
+        float z[4];
+        noise_regen4(row, d0, a.gen, a.k0, a.k1, a.noise_mode == 3u, z);
+#pragma unroll
+        for (uint32_t k = 0; k < 4u; ++k)
+          if (d0 + k < a.D) sp[d0 + k] = __fmaf_rn(scale, z[k], a.theta[d0 + k]);
+      }
+    } else {
+      for (uint32_t d = (uint32_t)u; d < a.D; d += 64u)
+        sp[d] = __fmaf_rn(scale, noise_value(a.noise_mode, nbase, a.ld, nrow, d, a.gen, a.k0, a.k1), a.theta[d]);
+    }
+    __syncthreads();
+  }
 
   // ---- this lane's weights ----
   // first layer: partial sums of the units lc, lc + 16, ... over the inputs of row lr: w1[CJ q + j] = W1[lc + 16 q][4 j + lr]
   // second layer and action layer: the same over the 16 hidden units of row lr: w2[16 q + j] = W2[lc + 16 q][16 lr + j],
-  //   w3[j] = W3[lc][16 lr + j]
+  //   w3[j] = W3[lc][16 lr + j] (with one row of hidden units every row holds all of them: input j)
   // environment: partial sums of the four state elements of column lc: ar[CJ r + j] = A[4 lc + r][4 j + lr];
   //   action term of this lane's own element: br[c] = B[ks][c]
-  float w1[NQ * CJ], w2[NH], w3[16], ar[4 * CJ], br[NA];
-  float b1 = 0.f, b2 = 0.f, b3 = 0.f;
+  float w1[NQ * CJ], w2[NQ * 16], w3[16], ar[4 * CJ], br[NAR];
 #pragma unroll
   for (int qq = 0; qq < NQ; ++qq)
 #pragma unroll
-    for (int j = 0; j < CJ; ++j) w1[CJ * qq + j] = (4 * j + lr < NO) ? param(oW1 + (uint32_t)(lc + 16 * qq) * NO + 4 * j + lr) : 0.f;
+    for (int j = 0; j < CJ; ++j) {
+      const int unit = lc + 16 * qq, k = 4 * j + lr;
+      w1[CJ * qq + j] = (unit < nh && k < no) ? sp[a.oW1 + unit * no + k] : 0.f;
+    }
 #pragma unroll
-  for (int qq = 0; qq < NQ; ++qq) {
-    const uint32_t d0 = oW2 + (uint32_t)(lc + 16 * qq) * NH + 16u * (uint32_t)lr;     // sixteen consecutive parameters
+  for (int qq = 0; qq < NQ; ++qq)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) w2[16 * qq + j] = hid ? param(d0 + j) : 0.f;
+    for (int j = 0; j < 16; ++j) {
+      const int unit = lc + 16 * qq, k = (NQ == 1 ? 0 : 16 * lr) + j;
+      w2[16 * qq + j] = (unit < nh && k < nh) ? sp[a.oW2 + unit * nh + k] : 0.f;
+    }
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int k = (NQ == 1 ? 0 : 16 * lr) + j;
+    w3[j] = (lc < na && k < nh) ? sp[a.oW3 + lc * nh + k] : 0.f;
   }
-#pragma unroll
-  for (int j = 0; j < 16; ++j) w3[j] = (hid && lc < NA) ? param(oW3 + (uint32_t)lc * NH + 16u * (uint32_t)lr + j) : 0.f;
-  if (hid) { b1 = param(ob1 + u); b2 = param(ob2 + u); }
-  if (lc < NA) b3 = param(ob3 + lc);            // in every row: the action vector is kept once per row
+  const float b1 = hid ? sp[a.ob1 + hu] : 0.f, b2 = hid ? sp[a.ob2 + hu] : 0.f;
+  const float b3 = lc < na ? sp[a.ob3 + lc] : 0.f;            // in every row: the action vector is kept once per row
 #pragma unroll
   for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int j = 0; j < CJ; ++j)
-      ar[CJ * r + j] = (lc < CJ && 4 * lc + r < NO && 4 * j + lr < NO) ? a.A[(4 * lc + r) * NO + 4 * j + lr] : 0.f;
+    for (int j = 0; j < CJ; ++j) {
+      const int el = 4 * lc + r, k = 4 * j + lr;
+      ar[CJ * r + j] = (lc < CJ && el < no && k < no) ? a.A[el * no + k] : 0.f;
+    }
 #pragma unroll
-  for (int c = 0; c < NA; ++c) br[c] = sval ? a.B[ks * NA + c] : 0.f;
+  for (int c = 0; c < NAR; ++c) br[c] = (sval && c < na) ? a.B[ks * na + c] : 0.f;
 
-  // frozen observation statistics of this lane's state element (NORM: a context with statistics set)
-  const float mu = (NORM && sval) ? a.obs_mean[ks] : 0.f;
-  const float iv = (NORM && sval) ? a.obs_inv[ks] : 1.f;
+  // frozen observation statistics of this lane's state element (identity when none are set: (s - 0) * 1 = s exactly)
+  const bool stats = a.obs_mean != nullptr;
+  const float mu = (NORM && stats && sval) ? a.obs_mean[ks] : 0.f;
+  const float iv = (NORM && stats && sval) ? a.obs_inv[ks] : 1.f;
+  // run-time activation choices as per-lane values the compiler cannot prove uniform: selects, not branches
+  uint32_t relu_l = a.hidden_relu, otanh_l = a.out_tanh;
+  if (!FIXED) asm volatile("" : "+v"(relu_l), "+v"(otanh_l));
+  auto hidden = [&](float l) {
+    if (FIXED) return RELU ? fmaxf(l, 0.f) : tanh_fast(l);
+    const float t = tanh_fast(l);
+    return relu_l ? fmaxf(l, 0.f) : t;
+  };
   float s = sval ? reset_value((uint32_t)ks, e, a.gen, a.k0, a.k1) : 0.f;
   float R = 0.f;                      // per-lane share of the return
   int32_t len = 0;
-  const float inv_no = 1.0f / (float)NO, quarter_cost = 0.25f * a.act_cost;
+  const float inv_no = 1.0f / (float)no, quarter_cost = 0.25f * a.act_cost;
 
   for (uint32_t t = 0; t < a.T; ++t) {
-    // h1 = tanh(W1 s + b1)
+    // h1 = act(W1 s + b1)
     const float xp = NORM ? (s - mu) * iv : s;      // the policy's input (paper App. B: fixed normalisation statistics)
+    float p[NQ];
+    row_bcast_dot<NQ, CJ>(p, xp, w1);
     float l1;
-    if constexpr (NQ == 4) {
-      float p0, p1, p2, p3;
-      row_bcast_dot_x4<CJ>(p0, p1, p2, p3, xp, w1);
-      l1 = rows_transpose_add(p0, p1, p2, p3);
-    } else {
-      float p0, p1;
-      row_bcast_dot_x2<CJ>(p0, p1, xp, w1);
-      l1 = rows_transpose_add(p0, p1);
-    }
-    l1 += b1;
-    const float h1 = RELU ? fmaxf(l1, 0.f) : tanh_fast(l1);
-    // h2 = tanh(W2 h1 + b2): every lane accumulates over its own row's inputs (row-broadcast DPP multiply-adds),
-    // then the rows' partial sums are added and moved to the lane of their unit by two row-swap stages
+    if constexpr (NQ == 4) l1 = rows_transpose_add(p[0], p[1], p[2], p[3]);
+    else if constexpr (NQ == 2) l1 = rows_transpose_add(p[0], p[1]);
+    else l1 = rows_add(p[0]);
+    const float h1 = hidden(l1 + b1);
+    // h2 = act(W2 h1 + b2)
+    row_bcast_dot<NQ, 16>(p, h1, w2);
     float l2;
-    if constexpr (NQ == 4) {
-      float p0, p1, p2, p3;
-      row_bcast_dot_x4<16>(p0, p1, p2, p3, h1, w2);
-      l2 = rows_transpose_add(p0, p1, p2, p3);
-    } else {
-      float p0, p1;
-      row_bcast_dot_x2<16>(p0, p1, h1, w2);
-      l2 = swap16_add(p0, p1);          // the units' own rows 0 and 1 hold all of their inputs; rows 2 and 3 have zero weights
-    }
-    l2 += b2;
-    const float h2 = RELU ? fmaxf(l2, 0.f) : tanh_fast(l2);
-    // a = tanh(W3 h2 + b3): row-broadcast multiply-adds as above, the four rows' partial sums added by two row swaps;
-    // column c of every row then holds unit c's total, and one tanh serves all units
-    float pv = row_bcast_dot16(h2, w3);
-    pv = swap16_add(pv, pv);
-    pv = swap32_add(pv, pv);
+    if constexpr (NQ == 4) l2 = rows_transpose_add(p[0], p[1], p[2], p[3]);
+    else if constexpr (NQ == 2) l2 = swap16_add(p[0], p[1]);      // the units' own rows 0 and 1 hold all of their inputs
+    else l2 = p[0];                                               // every row holds all inputs
+    const float h2 = hidden(l2 + b2);
+    // a = tanh(W3 h2 + b3): column c of every row ends up with unit c's total, one tanh serves all units
+    float pa[1];
+    row_bcast_dot<1, 16>(pa, h2, w3);
+    float pv = NQ == 1 ? pa[0] : rows_add(pa[0]);
     pv = pv + b3;
-    const float tv = OUT_TANH ? tanh_fast(pv) : pv;      // columns >= act: weights and bias are zero
+    float tv;
+    if (FIXED) tv = OUT_TANH ? tanh_fast(pv) : pv;      // columns >= act: weights and bias are zero
+    else { const float tt = tanh_fast(pv); tv = otanh_l ? tt : pv; }
     // reward from the pre-step state, 1 - |s|^2 / obs - cost |a|^2: a sum over all 64 lanes (the action vector is held
     // once per row, hence the quarter)
     R += __fmaf_rn(-inv_no * s, s, -quarter_cost * (tv * tv));      // this lane's share; the lanes are added after the last step
     len += 1;
     // s' = tanh(A s + B a): partial sums of the four elements of this column over the inputs of this row, rows added
     // and moved to their element's lane; the action term straight from the row's action vector
-    float pre;
-    {
-      float e0, e1, e2, e3;
-      row_bcast_dot_x4<CJ>(e0, e1, e2, e3, s, ar);
-      pre = rows_transpose_add(e0, e1, e2, e3);
-    }
-    pre = row_bcast_mac<NA>(pre, tv, br);
+    float ev[4];
+    row_bcast_dot<4, CJ>(ev, s, ar);
+    float pre = rows_transpose_add(ev[0], ev[1], ev[2], ev[3]);
+    pre = row_bcast_mac<NAR>(pre, tv, br);
     s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
     if (__ballot(fabsf(s) > a.done_thresh) != 0ull) break;       // max |s| > threshold: some lane exceeds it
   }
-  const float r2 = swap16_add(R, R);
-  R = (float)len + row_total(swap32_add(r2, r2));      // ends in lane 15
+  R = (float)len + row_total(rows_add(R));      // ends in lane 15
   if (u == 15) {
     a.returns[(size_t)i * a.E + e] = R;
     a.ep_len[(size_t)i * a.E + e] = len;
   }
 }
 
-template <int O, int H, int A> struct RegWidths { static constexpr int no = O, nh = H, na = A; };
-struct RegShape { uint32_t no, nh, na; const char* name; };
-static const RegShape kRegShapes[] = {
-    {11, 32, 3, "rollout_wave_reg_f32<11,32,3>"},
-    {17, 64, 6, "rollout_wave_reg_f32<17,64,6>"},
-};
+// ---- variants: two exact shapes, and classes for everything else ----
+constexpr int REG_EXACT = 2;
+struct RegExact { uint32_t no, nh, na; };
+static const RegExact kRegExact[REG_EXACT] = {{11, 32, 3}, {17, 64, 6}};
+// class variant index = REG_EXACT + 9 * (obs class) + 3 * (hidden class) + (act class)
+static int class_of(uint32_t v, uint32_t a, uint32_t b) { return v <= a ? 0 : (v <= b ? 1 : 2); }
 
 int reg_variant_for(const es_config& c) {
   if (c.dtype != 0 || (c.num_hidden != 0 && c.num_hidden != 2)) return -1;
-  for (int v = 0; v < 2; ++v)
-    if (c.obs_dim == kRegShapes[v].no && c.hid_dim == kRegShapes[v].nh && c.act_dim == kRegShapes[v].na) return v;
-  return -1;
+  if (c.obs_dim > 64 || c.hid_dim > 64 || c.act_dim > 16) return -1;
+  for (int v = 0; v < REG_EXACT; ++v)
+    if (c.obs_dim == kRegExact[v].no && c.hid_dim == kRegExact[v].nh && c.act_dim == kRegExact[v].na) return v;
+  return REG_EXACT + 9 * class_of(c.obs_dim, 16, 32) + 3 * class_of(c.hid_dim, 16, 32) + class_of(c.act_dim, 4, 8);
 }
-const char* reg_variant_name(int v) { return (v >= 0 && v < 2) ? kRegShapes[v].name : "none"; }
+
+std::string reg_variant_name(int v) {
+  if (v < 0) return "none";
+  if (v < REG_EXACT)
+    return "rollout_wave_reg_f32<" + std::to_string(kRegExact[v].no) + "," + std::to_string(kRegExact[v].nh) + "," +
+           std::to_string(kRegExact[v].na) + ">";
+  v -= REG_EXACT;
+  static const char* obs[] = {"16", "32", "64"}, *hid[] = {"16", "32", "64"}, *act[] = {"4", "8", "16"};
+  return std::string("rollout_wave_reg_f32<obs<=") + obs[v / 9] + ",hid<=" + hid[(v / 3) % 3] + ",act<=" + act[v % 3] + ">";
+}
+
+template <int CJ, int NQ, int NAR>
+static void launch_fixed(int mode, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
+  auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(64), lds, st, a); };
+  switch (mode) {
+    case 0: go(rollout_reg_kernel<CJ, NQ, NAR, 0>); break;
+    case 1: go(rollout_reg_kernel<CJ, NQ, NAR, 1>); break;
+    case 2: go(rollout_reg_kernel<CJ, NQ, NAR, 2>); break;
+    case 3: go(rollout_reg_kernel<CJ, NQ, NAR, 3>); break;
+    case 4: go(rollout_reg_kernel<CJ, NQ, NAR, 4>); break;
+    case 5: go(rollout_reg_kernel<CJ, NQ, NAR, 5>); break;
+    case 6: go(rollout_reg_kernel<CJ, NQ, NAR, 6>); break;
+    default: go(rollout_reg_kernel<CJ, NQ, NAR, 7>); break;
+  }
+}
+template <int CJ, int NQ>
+static void launch_class_act(int act_class, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
+  auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(64), lds, st, a); };
+  if (act_class == 0) go(rollout_reg_kernel<CJ, NQ, 4, -1>);
+  else if (act_class == 1) go(rollout_reg_kernel<CJ, NQ, 8, -1>);
+  else go(rollout_reg_kernel<CJ, NQ, 16, -1>);
+}
+template <int CJ>
+static void launch_class_hid(int hid_class, int act_class, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
+  if (hid_class == 0) launch_class_act<CJ, 1>(act_class, grid, lds, st, a);
+  else if (hid_class == 1) launch_class_act<CJ, 2>(act_class, grid, lds, st, a);
+  else launch_class_act<CJ, 4>(act_class, grid, lds, st, a);
+}
 
 int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,
                        const float* B, float* returns, int32_t* ep_len, float* fitness, void* /*ws*/,
@@ -343,31 +284,25 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   RegArgs a;
   const NoiseView nv = noise_view(ctx, noise);
   a.theta = theta; a.noise = nv.base; a.noise_offs = nv.offs; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std; a.returns = returns; a.ep_len = ep_len;
-  a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld;
+  a.N = s.N; a.E = s.E; a.T = s.T; a.ld = s.ld; a.D = s.D;
+  a.no = s.no; a.nh = s.nh; a.na = s.na;
+  a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
-  a.antithetic = c.antithetic; a.noise_mode = nv.mode;
+  a.antithetic = c.antithetic; a.noise_mode = nv.mode; a.hidden_relu = c.hidden_act == 1; a.out_tanh = c.out_tanh != 0;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
-  const dim3 grid(s.N * s.E), block(64);
-  const bool relu = c.hidden_act == 1, otanh = c.out_tanh != 0, norm = ctx->obs_mean != nullptr;
-  auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, st, a); };
-  auto pick = [&](auto shape) {       // shape carries the three widths; the activations and the statistics select the variant
-    constexpr int O = decltype(shape)::no, H = decltype(shape)::nh, A = decltype(shape)::na;
-    const int v = (relu ? 4 : 0) | (otanh ? 2 : 0) | (norm ? 1 : 0);
-    switch (v) {
-      case 0: go(rollout_reg_kernel<O, H, A, false, false, false>); break;
-      case 1: go(rollout_reg_kernel<O, H, A, false, false, true>); break;
-      case 2: go(rollout_reg_kernel<O, H, A, false, true, false>); break;
-      case 3: go(rollout_reg_kernel<O, H, A, false, true, true>); break;
-      case 4: go(rollout_reg_kernel<O, H, A, true, false, false>); break;
-      case 5: go(rollout_reg_kernel<O, H, A, true, false, true>); break;
-      case 6: go(rollout_reg_kernel<O, H, A, true, true, false>); break;
-      default: go(rollout_reg_kernel<O, H, A, true, true, true>); break;
-    }
-  };
-  switch (ctx->reg_variant) {
-    case 0: pick(RegWidths<11, 32, 3>{}); break;
-    case 1: pick(RegWidths<17, 64, 6>{}); break;
-    default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident binary32 variant for this shape");
+  const dim3 grid(s.N * s.E);
+  const size_t lds = (size_t)s.D * sizeof(float);      // at most 65*64 + 65*64 + 65*16 values: 37 KB
+  const int mode = (c.hidden_act == 1 ? 4 : 0) | (c.out_tanh ? 2 : 0) | (ctx->obs_mean ? 1 : 0);
+  const int v = ctx->reg_variant;
+  if (v < 0 || s.no > 64 || s.nh > 64 || s.na > 16 || s.m != 2)
+    return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident binary32 variant for this shape");
+  if (v == 0) launch_fixed<3, 2, 3>(mode, grid, lds, st, a);
+  else if (v == 1) launch_fixed<5, 4, 6>(mode, grid, lds, st, a);
+  else {
+    const int k = v - REG_EXACT, oc = k / 9, hc = (k / 3) % 3, ac = k % 3;
+    if (oc == 0) launch_class_hid<4>(hc, ac, grid, lds, st, a);
+    else if (oc == 1) launch_class_hid<8>(hc, ac, grid, lds, st, a);
+    else launch_class_hid<16>(hc, ac, grid, lds, st, a);
   }
   int rc = check_launch(ctx, "es_rollout (register-resident f32)");
   if (rc != ES_OK) return rc;

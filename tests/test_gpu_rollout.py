@@ -215,6 +215,66 @@ def test_rollout_bf16_configs_full_size_fixed_length(es, idx):
     assert np.all(got[1] == t_short) and not chaotic_short
 
 
+# ---- register-resident binary32 kernel, shape classes: every run length (inputs per row 4 / 8 / 16, rows of hidden
+# units 1 / 2 / 4, action run 4 / 8 / 16), ragged widths inside a class, both activations, linear output ----
+REG_CLASS_CASES = [
+    Workload("rc-5-8-2", pop=6, envs=3, horizon=40, obs=5, hid=8, act=2, dtype=0, noise_dtype=0, seed=81),
+    Workload("rc-16-16-4", pop=6, envs=3, horizon=40, obs=16, hid=16, act=4, dtype=0, noise_dtype=0, seed=82, hidden_act=1),
+    Workload("rc-net16-ant", pop=8, envs=2, horizon=60, obs=27, hid=16, act=8, dtype=0, noise_dtype=0, seed=83),
+    Workload("rc-net16-hopper-relu", pop=8, envs=2, horizon=60, obs=11, hid=16, act=3, dtype=0, noise_dtype=0, seed=84, hidden_act=1),
+    Workload("rc-net16-walker", pop=8, envs=2, horizon=60, obs=17, hid=16, act=6, dtype=0, noise_dtype=0, seed=85),
+    Workload("rc-13-29-7-linear", pop=6, envs=3, horizon=40, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=86, out_tanh=0),
+    Workload("rc-32-32-12", pop=6, envs=2, horizon=40, obs=32, hid=32, act=12, dtype=0, noise_dtype=0, seed=87),
+    Workload("rc-40-48-16-relu", pop=6, envs=2, horizon=30, obs=40, hid=48, act=16, dtype=0, noise_dtype=0, seed=88, hidden_act=1),
+    Workload("rc-64-64-9", pop=4, envs=2, horizon=30, obs=64, hid=64, act=9, dtype=0, noise_dtype=0, seed=89),
+    Workload("rc-27-64-8-noanti", pop=5, envs=2, horizon=40, obs=27, hid=64, act=8, dtype=0, noise_dtype=0, seed=90, antithetic=0),
+    Workload("rc-33-17-5-regen", pop=6, envs=2, horizon=40, obs=33, hid=17, act=5, dtype=0, noise_dtype=2, seed=91),
+    Workload("rc-17-64-7-bf16noise", pop=6, envs=2, horizon=40, obs=17, hid=64, act=7, dtype=0, noise_dtype=1, seed=92),
+    Workload("rc-9-33-1", pop=6, envs=2, horizon=40, obs=9, hid=33, act=1, dtype=0, noise_dtype=0, seed=93),
+]
+
+
+@pytest.mark.parametrize("w", REG_CLASS_CASES, ids=lambda w: w.name)
+def test_rollout_register_resident_shape_classes(es, w):
+    ws = replace(w, noise_dtype=w.noise_dtype & 1)
+    a_mat, b_mat, theta = make_inputs(w)
+    theta = (theta + np.random.default_rng(w.seed).standard_normal(theta.size) * 0.02).astype(np.float32)   # non-zero biases
+    ctx = es.EsContext(w)
+    assert "wave_reg" in ctx.rollout_kernel, ctx.rollout_kernel
+    eps = oracle.sample_population(ws, 1)
+    noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
+    got = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
+    ref = oracle.rollout(ws, 1, theta, eps, a_mat, b_mat)
+    probe = oracle.rollout(ws, 1, theta, eps, a_mat, b_mat, arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens}")
+    assert not chaotic
+
+
+def test_register_resident_class_with_obs_norm_and_table(es):
+    from gpu_util import dev
+    w = Workload("rc-norm-table", pop=6, envs=2, horizon=40, obs=27, hid=16, act=8, dtype=0, noise_dtype=4, seed=94,
+                 noise_table_len=1 << 14, hidden_act=1)
+    a_mat, b_mat, theta = make_inputs(w)
+    rng = np.random.default_rng(94)
+    mean = (rng.standard_normal(w.obs) * 0.05).astype(np.float32)
+    inv = (1.0 / (0.33 + rng.random(w.obs) * 0.67)).astype(np.float32)
+    ctx = es.EsContext(w)
+    assert "wave_reg" in ctx.rollout_kernel
+    mean_d, inv_d = dev(mean), dev(inv)
+    ctx.set_obs_norm(mean_d, inv_d)
+    noise = ctx.alloc_noise()
+    ctx.build_noise_table(noise)
+    ctx.sample_population(3, noise)
+    got = run_rollout(ctx, w, 3, theta, noise, a_mat, b_mat)
+    eps = oracle.table_rows(w, 3, w.noise_table_len, ctx.noise_ld, False)
+    ws = replace(w, noise_dtype=0)
+    ref = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
+    probe = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), arith=1)
+    flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
+    assert not chaotic
+
+
 # ---- register-resident binary32 variants (the narrow policies of configs[0..2]) ----
 REG = Workload("reg", pop=6, envs=3, horizon=50, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=41)
 
