@@ -99,7 +99,7 @@ int es_create(const es_config* cfg, es_ctx** out) {
   ctx->reg_variant = reg_variant_for(c);
   if (ctx->reg_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_WAVE_REG;
-    ctx->kernel_name = reg_variant_name(ctx->reg_variant);
+    ctx->kernel_name = reg_variant_name(ctx->reg_variant, c.dtype == 1);
   } else if (ctx->mfma_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_MFMA_REG;
     ctx->kernel_name = mfma_variant_name(ctx->mfma_variant);

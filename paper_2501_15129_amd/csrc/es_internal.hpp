@@ -93,8 +93,8 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
                        const float* A, const float* B, float* returns, int32_t* ep_len,
                        float* fitness, void* ws, hipStream_t st);
 int launch_fitness(es_ctx* ctx, const float* returns, float* fitness, hipStream_t st);
-int reg_variant_for(const es_config& cfg);        // -1 when no binary32 register-resident kernel is built for the shape
-std::string reg_variant_name(int variant);
+int reg_variant_for(const es_config& cfg);        // -1 when no one-wavefront register-resident kernel is built for the shape
+std::string reg_variant_name(int variant, bool bf16);
 int mfma_variant_for(const es_config& cfg);       // -1 when no register-resident kernel fits
 const char* mfma_variant_name(int variant);
 size_t wave_rollout_lds_bytes(const es_config& cfg);

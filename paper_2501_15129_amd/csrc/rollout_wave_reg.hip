@@ -1,4 +1,5 @@
-// es_rollout, register-resident binary32 kernel for narrow policies (obs, hidden <= 64, act <= 16, two hidden layers).
+// es_rollout, register-resident kernel for narrow policies (obs, hidden <= 64, act <= 16, two hidden layers), binary32
+// or bf16 operands.
 //
 // Paper Sec. 3.2 / 5.2: population x environment-copy evaluation of a deterministic
 // two-hidden-layer MLP policy, fitness = mean undiscounted return.  One wavefront runs one
@@ -85,8 +86,9 @@ __device__ __forceinline__ float row_total(float v) {
 
 // CJ: state elements per row (ceil(obs / 4), or its class); NQ: 16-lane rows of hidden units (1, 2, 4); NAR: action
 // run length (act, or its class).  MODE 0..7 = ReLU (4) | tanh on the action layer (2) | observation statistics (1)
-// fixed at compile time; MODE < 0: read from the arguments and applied by selects.
-template <int CJ, int NQ, int NAR, int MODE>
+// fixed at compile time; MODE < 0: read from the arguments and applied by selects.  BF16: every operand of a product
+// (weights, biases, environment matrices, state, activations, action) is rounded to bf16; sums, tanh, reward binary32.
+template <int CJ, int NQ, int NAR, int MODE, bool BF16>
 __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   static_assert(NQ == 1 || NQ == 2 || NQ == 4, "rows of hidden units");
   constexpr bool FIXED = MODE >= 0;
@@ -102,6 +104,7 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   const bool sval = lc < CJ && ks < no;
   const int hu = NQ == 1 ? lc : u;               // the hidden unit of this lane
   const bool hid = hu < nh;
+  auto opnd = [](float v) { return BF16 ? bf16_round(v) : v; };      // a value as an operand of a product
 
   // ---- perturbed parameters -> LDS (coalesced, binary32, one rounding each) ----
   {
@@ -114,11 +117,11 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
         noise_regen4(row, d0, a.gen, a.k0, a.k1, a.noise_mode == 3u, z);
 #pragma unroll
         for (uint32_t k = 0; k < 4u; ++k)
-          if (d0 + k < a.D) sp[d0 + k] = __fmaf_rn(scale, z[k], a.theta[d0 + k]);
+          if (d0 + k < a.D) sp[d0 + k] = opnd(__fmaf_rn(scale, z[k], a.theta[d0 + k]));
       }
     } else {
       for (uint32_t d = (uint32_t)u; d < a.D; d += 64u)
-        sp[d] = __fmaf_rn(scale, noise_value(a.noise_mode, nbase, a.ld, nrow, d, a.gen, a.k0, a.k1), a.theta[d]);
+        sp[d] = opnd(__fmaf_rn(scale, noise_value(a.noise_mode, nbase, a.ld, nrow, d, a.gen, a.k0, a.k1), a.theta[d]));
     }
     __syncthreads();
   }
@@ -156,10 +159,10 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
 #pragma unroll
     for (int j = 0; j < CJ; ++j) {
       const int el = 4 * lc + r, k = 4 * j + lr;
-      ar[CJ * r + j] = (lc < CJ && el < no && k < no) ? a.A[el * no + k] : 0.f;
+      ar[CJ * r + j] = (lc < CJ && el < no && k < no) ? opnd(a.A[el * no + k]) : 0.f;
     }
 #pragma unroll
-  for (int c = 0; c < NAR; ++c) br[c] = (sval && c < na) ? a.B[ks * na + c] : 0.f;
+  for (int c = 0; c < NAR; ++c) br[c] = (sval && c < na) ? opnd(a.B[ks * na + c]) : 0.f;
 
   // frozen observation statistics of this lane's state element (identity when none are set: (s - 0) * 1 = s exactly)
   const bool stats = a.obs_mean != nullptr;
@@ -180,21 +183,21 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
 
   for (uint32_t t = 0; t < a.T; ++t) {
     // h1 = act(W1 s + b1)
-    const float xp = NORM ? (s - mu) * iv : s;      // the policy's input (paper App. B: fixed normalisation statistics)
+    const float xp = opnd(NORM ? (s - mu) * iv : s);      // the policy's input (paper App. B: fixed normalisation statistics)
     float p[NQ];
     row_bcast_dot<NQ, CJ>(p, xp, w1);
     float l1;
     if constexpr (NQ == 4) l1 = rows_transpose_add(p[0], p[1], p[2], p[3]);
     else if constexpr (NQ == 2) l1 = rows_transpose_add(p[0], p[1]);
     else l1 = rows_add(p[0]);
-    const float h1 = hidden(l1 + b1);
+    const float h1 = opnd(hidden(l1 + b1));
     // h2 = act(W2 h1 + b2)
     row_bcast_dot<NQ, 16>(p, h1, w2);
     float l2;
     if constexpr (NQ == 4) l2 = rows_transpose_add(p[0], p[1], p[2], p[3]);
     else if constexpr (NQ == 2) l2 = swap16_add(p[0], p[1]);      // the units' own rows 0 and 1 hold all of their inputs
     else l2 = p[0];                                               // every row holds all inputs
-    const float h2 = hidden(l2 + b2);
+    const float h2 = opnd(hidden(l2 + b2));
     // a = tanh(W3 h2 + b3): column c of every row ends up with unit c's total, one tanh serves all units
     float pa[1];
     row_bcast_dot<1, 16>(pa, h2, w3);
@@ -210,9 +213,9 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     // s' = tanh(A s + B a): partial sums of the four elements of this column over the inputs of this row, rows added
     // and moved to their element's lane; the action term straight from the row's action vector
     float ev[4];
-    row_bcast_dot<4, CJ>(ev, s, ar);
+    row_bcast_dot<4, CJ>(ev, opnd(s), ar);
     float pre = rows_transpose_add(ev[0], ev[1], ev[2], ev[3]);
-    pre = row_bcast_mac<NAR>(pre, tv, br);
+    pre = row_bcast_mac<NAR>(pre, opnd(tv), br);
     s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
     if (__ballot(fabsf(s) > a.done_thresh) != 0ull) break;       // max |s| > threshold: some lane exceeds it
   }
@@ -231,49 +234,55 @@ static const RegExact kRegExact[REG_EXACT] = {{11, 32, 3}, {17, 64, 6}};
 static int class_of(uint32_t v, uint32_t a, uint32_t b) { return v <= a ? 0 : (v <= b ? 1 : 2); }
 
 int reg_variant_for(const es_config& c) {
-  if (c.dtype != 0 || (c.num_hidden != 0 && c.num_hidden != 2)) return -1;
+  if (c.dtype > 1 || (c.num_hidden != 0 && c.num_hidden != 2)) return -1;
   if (c.obs_dim > 64 || c.hid_dim > 64 || c.act_dim > 16) return -1;
-  for (int v = 0; v < REG_EXACT; ++v)
+  for (int v = 0; v < REG_EXACT && c.dtype == 0; ++v)
     if (c.obs_dim == kRegExact[v].no && c.hid_dim == kRegExact[v].nh && c.act_dim == kRegExact[v].na) return v;
   return REG_EXACT + 9 * class_of(c.obs_dim, 16, 32) + 3 * class_of(c.hid_dim, 16, 32) + class_of(c.act_dim, 4, 8);
 }
 
-std::string reg_variant_name(int v) {
+std::string reg_variant_name(int v, bool bf16) {
   if (v < 0) return "none";
   if (v < REG_EXACT)
     return "rollout_wave_reg_f32<" + std::to_string(kRegExact[v].no) + "," + std::to_string(kRegExact[v].nh) + "," +
            std::to_string(kRegExact[v].na) + ">";
   v -= REG_EXACT;
   static const char* obs[] = {"16", "32", "64"}, *hid[] = {"16", "32", "64"}, *act[] = {"4", "8", "16"};
-  return std::string("rollout_wave_reg_f32<obs<=") + obs[v / 9] + ",hid<=" + hid[(v / 3) % 3] + ",act<=" + act[v % 3] + ">";
+  return std::string(bf16 ? "rollout_wave_reg_bf16<obs<=" : "rollout_wave_reg_f32<obs<=") + obs[v / 9] + ",hid<=" + hid[(v / 3) % 3] + ",act<=" + act[v % 3] + ">";
 }
 
 template <int CJ, int NQ, int NAR>
 static void launch_fixed(int mode, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
   auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(64), lds, st, a); };
   switch (mode) {
-    case 0: go(rollout_reg_kernel<CJ, NQ, NAR, 0>); break;
-    case 1: go(rollout_reg_kernel<CJ, NQ, NAR, 1>); break;
-    case 2: go(rollout_reg_kernel<CJ, NQ, NAR, 2>); break;
-    case 3: go(rollout_reg_kernel<CJ, NQ, NAR, 3>); break;
-    case 4: go(rollout_reg_kernel<CJ, NQ, NAR, 4>); break;
-    case 5: go(rollout_reg_kernel<CJ, NQ, NAR, 5>); break;
-    case 6: go(rollout_reg_kernel<CJ, NQ, NAR, 6>); break;
-    default: go(rollout_reg_kernel<CJ, NQ, NAR, 7>); break;
+    case 0: go(rollout_reg_kernel<CJ, NQ, NAR, 0, false>); break;
+    case 1: go(rollout_reg_kernel<CJ, NQ, NAR, 1, false>); break;
+    case 2: go(rollout_reg_kernel<CJ, NQ, NAR, 2, false>); break;
+    case 3: go(rollout_reg_kernel<CJ, NQ, NAR, 3, false>); break;
+    case 4: go(rollout_reg_kernel<CJ, NQ, NAR, 4, false>); break;
+    case 5: go(rollout_reg_kernel<CJ, NQ, NAR, 5, false>); break;
+    case 6: go(rollout_reg_kernel<CJ, NQ, NAR, 6, false>); break;
+    default: go(rollout_reg_kernel<CJ, NQ, NAR, 7, false>); break;
   }
 }
-template <int CJ, int NQ>
+template <int CJ, int NQ, bool BF16>
 static void launch_class_act(int act_class, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
   auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(64), lds, st, a); };
-  if (act_class == 0) go(rollout_reg_kernel<CJ, NQ, 4, -1>);
-  else if (act_class == 1) go(rollout_reg_kernel<CJ, NQ, 8, -1>);
-  else go(rollout_reg_kernel<CJ, NQ, 16, -1>);
+  if (act_class == 0) go(rollout_reg_kernel<CJ, NQ, 4, -1, BF16>);
+  else if (act_class == 1) go(rollout_reg_kernel<CJ, NQ, 8, -1, BF16>);
+  else go(rollout_reg_kernel<CJ, NQ, 16, -1, BF16>);
 }
-template <int CJ>
+template <int CJ, bool BF16>
 static void launch_class_hid(int hid_class, int act_class, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
-  if (hid_class == 0) launch_class_act<CJ, 1>(act_class, grid, lds, st, a);
-  else if (hid_class == 1) launch_class_act<CJ, 2>(act_class, grid, lds, st, a);
-  else launch_class_act<CJ, 4>(act_class, grid, lds, st, a);
+  if (hid_class == 0) launch_class_act<CJ, 1, BF16>(act_class, grid, lds, st, a);
+  else if (hid_class == 1) launch_class_act<CJ, 2, BF16>(act_class, grid, lds, st, a);
+  else launch_class_act<CJ, 4, BF16>(act_class, grid, lds, st, a);
+}
+template <bool BF16>
+static void launch_class(int obs_class, int hid_class, int act_class, dim3 grid, size_t lds, hipStream_t st, const RegArgs& a) {
+  if (obs_class == 0) launch_class_hid<4, BF16>(hid_class, act_class, grid, lds, st, a);
+  else if (obs_class == 1) launch_class_hid<8, BF16>(hid_class, act_class, grid, lds, st, a);
+  else launch_class_hid<16, BF16>(hid_class, act_class, grid, lds, st, a);
 }
 
 int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,
@@ -300,9 +309,8 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   else if (v == 1) launch_fixed<5, 4, 6>(mode, grid, lds, st, a);
   else {
     const int k = v - REG_EXACT, oc = k / 9, hc = (k / 3) % 3, ac = k % 3;
-    if (oc == 0) launch_class_hid<4>(hc, ac, grid, lds, st, a);
-    else if (oc == 1) launch_class_hid<8>(hc, ac, grid, lds, st, a);
-    else launch_class_hid<16>(hc, ac, grid, lds, st, a);
+    if (c.dtype == 1) launch_class<true>(oc, hc, ac, grid, lds, st, a);
+    else launch_class<false>(oc, hc, ac, grid, lds, st, a);
   }
   int rc = check_launch(ctx, "es_rollout (register-resident f32)");
   if (rc != ES_OK) return rc;

@@ -26,7 +26,8 @@ CASES = [
     (replace(CONFIGS[1], name="cfg1-k2-T120", episodes=2, horizon=120, pop=8, envs=5), "wave_reg"),
     (Workload("odd-k4", pop=6, envs=3, horizon=50, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=51, episodes=4), "wave_reg"),
     (Workload("wide-k2", pop=4, envs=2, horizon=30, obs=70, hid=100, act=9, dtype=0, noise_dtype=0, seed=57, episodes=2), "wave_lds_f32"),
-    (Workload("odd-k2-bf16", pop=6, envs=3, horizon=50, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=52, episodes=2), "wave_lds_bf16"),
+    (Workload("odd-k2-bf16", pop=6, envs=3, horizon=50, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=52, episodes=2), "wave_reg_bf16"),
+    (Workload("wide-k2-bf16", pop=4, envs=2, horizon=30, obs=70, hid=100, act=9, dtype=1, noise_dtype=1, seed=58, episodes=2), "wave_lds_bf16"),
     (Workload("mfma32-k5", pop=4, envs=5, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=53, episodes=5), "mfma"),   # 25 columns: ragged second block
     (Workload("mfma32-narrow-k2", pop=4, envs=2, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=54, episodes=2), "mfma"),
     (Workload("mfma256-k4", pop=4, envs=4, horizon=16, obs=244, hid=256, act=17, dtype=1, noise_dtype=1, seed=55, episodes=4,

@@ -39,7 +39,8 @@ def _case(es, w, gen=1, expect_kernel=None):
 RELU_CASES = [
     (Workload("relu-odd", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=22, hidden_act=1), "wave_reg"),
     (Workload("relu-wide", pop=4, envs=2, horizon=40, obs=70, hid=100, act=9, dtype=0, noise_dtype=0, seed=24, hidden_act=1), "wave_lds_f32"),
-    (Workload("relu-odd-bf16", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=22, hidden_act=1), "wave_lds_bf16"),
+    (Workload("relu-odd-bf16", pop=10, envs=5, horizon=60, obs=13, hid=29, act=7, dtype=1, noise_dtype=1, seed=22, hidden_act=1), "wave_reg_bf16"),
+    (Workload("relu-wide-bf16", pop=4, envs=2, horizon=40, obs=70, hid=100, act=9, dtype=1, noise_dtype=1, seed=25, hidden_act=1), "wave_lds_bf16"),
     (Workload("relu-linear-out", pop=6, envs=3, horizon=40, obs=13, hid=29, act=7, dtype=0, noise_dtype=0, seed=23, hidden_act=1, out_tanh=0), "wave_reg"),
     (replace(CONFIGS[0], name="relu-cfg0", hidden_act=1), "wave_reg"),
     (replace(CONFIGS[1], name="relu-cfg1-T150", hidden_act=1, horizon=150), "wave_reg"),

@@ -231,6 +231,11 @@ REG_CLASS_CASES = [
     Workload("rc-33-17-5-regen", pop=6, envs=2, horizon=40, obs=33, hid=17, act=5, dtype=0, noise_dtype=2, seed=91),
     Workload("rc-17-64-7-bf16noise", pop=6, envs=2, horizon=40, obs=17, hid=64, act=7, dtype=0, noise_dtype=1, seed=92),
     Workload("rc-9-33-1", pop=6, envs=2, horizon=40, obs=9, hid=33, act=1, dtype=0, noise_dtype=0, seed=93),
+    # bf16 operands on the same kernel
+    Workload("rc-bf16-net16-ant", pop=8, envs=2, horizon=60, obs=27, hid=16, act=8, dtype=1, noise_dtype=1, seed=95),
+    Workload("rc-bf16-17-64-6-relu", pop=6, envs=2, horizon=40, obs=17, hid=64, act=6, dtype=1, noise_dtype=1, seed=96, hidden_act=1),
+    Workload("rc-bf16-40-32-12-regen", pop=6, envs=2, horizon=40, obs=40, hid=32, act=12, dtype=1, noise_dtype=3, seed=97, out_tanh=0),
+    Workload("rc-bf16-5-8-2-f32noise", pop=6, envs=3, horizon=40, obs=5, hid=8, act=2, dtype=1, noise_dtype=0, seed=98),
 ]
 
 
