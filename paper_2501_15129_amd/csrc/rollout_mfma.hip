@@ -15,8 +15,7 @@
 //   * The narrow 256 -> act layer is read from LDS and computed by one wavefront per 16-row
 //     tile; reward norms and the termination test are reduced through per-wavefront LDS
 //     partials that every lane adds in the same fixed order, so reruns are bit-identical.
-//   * The grid is persistent: workgroup b handles noise rows b, b + grid, ...; the two
-//     mirrored individuals of a row run back to back.
+//   * The grid is persistent: workgroup b handles individuals b, b + grid, ...
 // Bound: MFMA issue (dense 16x16x32 bf16) plus the tanh epilogue on the vector ALU.
 #include "es_device.hpp"
 #include "es_internal.hpp"
@@ -348,13 +347,14 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   __syncthreads();
 
   const uint32_t per_unit = a.antithetic ? 2u : 1u;
-  const uint32_t units = a.N / per_unit;
   const uint32_t nblk = (a.E + (uint32_t)NC - 1u) / (uint32_t)NC;
   int x0_block = -1;
 
-  for (uint32_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
-    for (uint32_t sub = 0; sub < per_unit; ++sub) {
-      const uint32_t i = unit * per_unit + sub;
+  // the grid is persistent over individuals (not over mirrored pairs: a small population then still fills the chip;
+  // the noise row is fetched once per individual either way)
+  for (uint32_t i = blockIdx.x; i < a.N; i += gridDim.x) {
+    {
+      const uint32_t unit = i / per_unit, sub = i - unit * per_unit;
       const float scale = sub ? -a.sigma : a.sigma;
       NoiseRow nz;
       nz.mode = a.noise_mode; nz.row = unit; nz.gen = a.gen; nz.k0 = a.k0; nz.k1 = a.k1;
@@ -876,7 +876,7 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   if ((int)V256<16, 4>::LDS_BYTES > ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");
-  const uint32_t units = c.antithetic ? s.N / 2 : s.N;
+  const uint32_t units = s.N;      // one work item per individual
   const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
   if (s.m == 3) {
     if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32D<4, 4, 1>>(ctx, a, units, st) : launch_variant<V32D<16, 4, 1>>(ctx, a, units, st);
