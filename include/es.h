@@ -89,10 +89,11 @@ typedef struct es_config {
                             EA experiments use ReLU MLPs, App. B); the action layer follows out_tanh */
   uint32_t num_hidden;   /* m hidden layers of width hid_dim (the paper's Sec. 5.1 varies m; its base
                             case and the default are 2; 0 means 2).  Flat parameters: W1[hid,obs], b1,
-                            then (m - 1) x (W[hid,hid], b[hid]), then W3[act,hid], b3.  The binary32
-                            register kernels serve m = 2, the bf16 matrix-core kernel m = 2 for every
-                            shape and m = 3, 4 for obs_dim <= 64, act_dim <= 16; other depths run on
-                            the LDS kernel (the individual must fit the LDS)                           */
+                            then (m - 1) x (W[hid,hid], b[hid]), then W3[act,hid], b3.  The one-
+                            wavefront register kernel serves m = 2 with obs, hid <= 64, act <= 16; the
+                            bf16 matrix-core kernel m = 2 for hid <= 256, obs <= 256, act <= 32 and
+                            m = 3, 4 for obs_dim <= 64, act_dim <= 16; everything else runs on the LDS
+                            kernel if the individual fits the LDS (else ES_EUNSUPPORTED from es_rollout) */
   uint64_t noise_table_len; /* entries of the shared noise table (noise_dtype 4, 5 only): a multiple
                             of 8, at least es_noise_ld(), below 2^32                                    */
   uint32_t episodes_per_env; /* k episodes run back to back in every environment copy, the copy resetting
