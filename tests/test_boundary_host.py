@@ -112,3 +112,15 @@ def test_oversized_shape_reports_unsupported_or_picks_a_kernel(binding):
     one = C.c_void_p(0x1000)
     assert lib.es_rollout(ctx._h, 0, one, one, one, one, one, one, one, one, None) == binding.ES_EUNSUPPORTED
     assert b"exceed" in lib.es_last_error(ctx._h)
+
+
+def test_generated_dpp_runs_are_current():
+    """csrc/dpp_runs.inc is the committed output of csrc/gen_dpp_runs.py."""
+    import importlib.util
+    csrc = ROOT / "paper_2501_15129_amd" / "csrc"
+    committed = (csrc / "dpp_runs.inc").read_text()
+    spec = importlib.util.spec_from_file_location("gen_dpp_runs", csrc / "gen_dpp_runs.py")
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    gen.main()
+    assert (csrc / "dpp_runs.inc").read_text() == committed
