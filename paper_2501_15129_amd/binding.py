@@ -123,7 +123,7 @@ class EsContext:
         self.episodes = self.cfg.envs_per_ind * max(1, self.cfg.episodes_per_env)   # E: columns of returns / ep_len
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:      # module globals may be gone at interpreter shutdown
             _lib.es_destroy(self._h)
             self._h = None
 

@@ -181,3 +181,23 @@ def test_generation_call_recorded_in_a_graph_replays_exactly(es, w):
             assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), f"replay {replay}"
         eager.generation_one_call(6 + replay)   # the program's own eager work between replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("algo", ["openes", "ars", "vanilla"])
+def test_strategies_improve_the_mean_fitness(es, algo):
+    """End-to-end sanity that does not involve the checker: forty generations of each strategy on a small workload must
+    raise the population's mean fitness (a wrong sign or scale anywhere in rank / update would not)."""
+    base = Workload("learn", pop=256, envs=2, horizon=100, obs=17, hid=64, act=6, dtype=0, noise_dtype=0, seed=11,
+                    done_thresh=float("inf"), act_cost=0.05)
+    w = {"openes": base,                       # the paper's settings (App. B Table 5b): Adam, lr 0.01, sigma 0.02
+         "ars": replace(base, algorithm=1, num_elites=32, lr=0.05, sigma=0.03),
+         "vanilla": replace(base, algorithm=2, num_elites=32, antithetic=0, sigma=0.05)}[algo]
+    a_mat, b_mat, theta = make_inputs(w)
+    run = GpuChain(es, w, theta, a_mat, b_mat)
+    means = []
+    for g in range(40):
+        run.generation_one_call(g)
+        means.append(float(run.fit.mean().item()))
+    first, last = np.mean(means[:3]), np.mean(means[-3:])
+    print(f"[{algo}] mean fitness {first:.3f} -> {last:.3f}")
+    assert np.all(np.isfinite(means)) and last > first + 5.0
