@@ -137,6 +137,11 @@ def main() -> int:
                     help="hidden-layer activation (the paper's EA experiments use ReLU MLPs, App. B)")
     ap.add_argument("--obs-norm", action="store_true",
                     help="frozen observation statistics for the policy input (paper App. B); synthetic: mean N(0, 0.05^2), std U[0.33, 1]")
+    ap.add_argument("--paper-base", action="store_true",
+                    help="the base configuration of the paper's OpenES timing experiment (Sec. 5.1: m = 2 hidden layers of 256, "
+                         "population n = 128, k = 1 episode, T = 1000) on the synthetic environment at Swimmer's widths (obs 8, act 2), "
+                         "bf16 operands; vary it with --num-hidden (m), --pop (n), --episodes-per-env (k)")
+    ap.add_argument("--pop", type=int, default=None, help="population size override (with --paper-base: n)")
     ap.add_argument("--num-hidden", type=int, default=2, help="m hidden layers (paper Sec. 5.1 varies m); not the default workload")
     ap.add_argument("--episodes-per-env", type=int, default=1,
                     help="k episodes per environment copy (auto-reset wrapper, paper Sec. 3.1); not the default workload")
@@ -153,6 +158,7 @@ def main() -> int:
     import numpy as np
     import torch
     from paper_2501_15129_amd import CONFIGS, EsContext, make_inputs
+    from paper_2501_15129_amd.workloads import Workload
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -170,6 +176,10 @@ def main() -> int:
                           "copies": 3}))
         return 0
     base = CONFIGS[args.config]
+    if args.paper_base:
+        base = Workload("paper-base", pop=128, envs=1, horizon=1000, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=5)
+    if args.pop is not None:
+        base = replace(base, name=base.name + f"-n{args.pop}", pop=args.pop)
     if args.noise_dtype is not None:
         base = replace(base, noise_dtype=args.noise_dtype, noise_table_len=args.table_len if args.noise_dtype >= 4 else 0)
     if args.hidden_act == "relu":
@@ -228,7 +238,7 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm and args.episodes_per_env == 1 and args.num_hidden == 2 else None) or {}
+    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm and args.episodes_per_env == 1 and args.num_hidden == 2 and not args.paper_base and args.pop is None else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9

@@ -92,7 +92,7 @@ typedef struct es_config {
                             then (m - 1) x (W[hid,hid], b[hid]), then W3[act,hid], b3.  The one-
                             wavefront register kernel serves m = 2 with obs, hid <= 64, act <= 16; the
                             bf16 matrix-core kernel m = 2 for hid <= 256, obs <= 256, act <= 32 and
-                            m = 3, 4 for obs_dim <= 64, act_dim <= 16; everything else runs on the LDS
+                            m = 1, 3, 4 for obs_dim <= 64, act_dim <= 16; everything else runs on the LDS
                             kernel if the individual fits the LDS (else ES_EUNSUPPORTED from es_rollout) */
   uint64_t noise_table_len; /* entries of the shared noise table (noise_dtype 4, 5 only): a multiple
                             of 8, at least es_noise_ld(), below 2^32                                    */

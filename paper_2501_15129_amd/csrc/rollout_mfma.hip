@@ -58,7 +58,8 @@ constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
 template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_, int NW_, int OCC_ = 1, int ME_ = 0>
 struct Variant {
-  static constexpr int ME = ME_;              // hidden layers beyond the second (depth m = 2 + ME), each 256 x 256 in registers
+  static constexpr int ME = ME_;              // hidden layers beyond the second (depth m = 2 + ME), each 256 x 256 in registers;
+                                              // -1: a single hidden layer (the second layer's phase is skipped)
   static constexpr int OCC = OCC_;            // workgroups per CU the register budget is sized for (1 or 2)
   static constexpr int NW = NW_;              // wavefronts per workgroup: 4 (one per SIMD) or 8 (two per SIMD)
   static constexpr int NT = 64 * NW;          // threads per workgroup
@@ -103,7 +104,7 @@ struct Variant {
   // initial value, and the statistics themselves
   static constexpr int OFF_BX = OFF_SS0 + 4 * 16;              // biases of the extra hidden layers [ME][NHP]
   static constexpr int OFF_HL = (ME & 1) ? OFF_H1 : OFF_H2;   // the last hidden layer's activations (the layers ping-pong)
-  static constexpr int OFF_XP = OFF_BX + 4 * NHP * ME;
+  static constexpr int OFF_XP = OFF_BX + 4 * NHP * (ME > 0 ? ME : 0);
   static constexpr int OFF_X0P = OFF_XP + 2 * NC * PX;
   static constexpr int OFF_MU = OFF_X0P + 2 * NC * PX;
   static constexpr int OFF_IV = OFF_MU + 4 * NOP;
@@ -115,7 +116,8 @@ struct Variant {
   static_assert(NAP >= 16 * MT3 && KTA <= KC, "action K padding");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
   static_assert(NC == 4 || NC == 16, "columns per pass");
-  static_assert(ME == 0 || (OCC == 1 && KTAL == 0), "deeper policies need the whole register file of the CU");
+  static_assert(ME <= 0 || (OCC == 1 && KTAL == 0), "deeper policies need the whole register file of the CU");
+  static_assert(ME >= 0 || KTAL == 0, "the single-layer variant keeps all of A in registers");
   static_assert(MT3 <= 2 && MT3 <= 4, "action tiles: one wavefront each, partial layout holds two");
 };
 
@@ -369,9 +371,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         float v1 = 0.0f, v2 = 0.0f;
         if (u < nh) {
           const uint32_t i1 = a.ob1 + u, i2 = a.ob2 + u;
-          const float e1 = row_noise(nz, i1), e2 = row_noise(nz, i2);
-          v1 = bf16_round(__fmaf_rn(scale, e1, a.theta[i1]));
-          v2 = bf16_round(__fmaf_rn(scale, e2, a.theta[i2]));
+          v1 = bf16_round(__fmaf_rn(scale, row_noise(nz, i1), a.theta[i1]));
+          if (ME >= 0) v2 = bf16_round(__fmaf_rn(scale, row_noise(nz, i2), a.theta[i2]));      // a single hidden layer has no second one
         }
         b1s[u] = v1;
         b2s[u] = v2;
@@ -409,7 +410,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         __syncthreads();
       }
 #pragma unroll
-      for (int kr = 0; kr < KT_H / KC; ++kr) {
+      for (int kr = 0; kr < (ME >= 0 ? KT_H / KC : 0); ++kr) {
         stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, a.theta, nz, scale, a.oW2);
         __syncthreads();
 #pragma unroll
@@ -483,7 +484,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         float Rn = 0.0f;
         int32_t Ln = 0;
         const float inv_no = 1.0f / (float)no;
-        constexpr int KA1 = (KT1 + 1) / 2;       // K tiles of A x done beside layer 1; the rest beside layer 2
+        constexpr int KA1 = ME < 0 ? KT1 : (KT1 + 1) / 2;       // K tiles of A x done beside layer 1; the rest beside layer 2
 
         f32x4 acc[MT_H], accE[MTE];
 #pragma unroll
@@ -585,11 +586,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, NC == 4 ? 4 : 8, 0);
           }
-#pragma unroll
-          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
-          __syncthreads();
           // ---- phase B: h2 = tanh(W2 h1 + b2); second half of A x ----
-          {
+          if constexpr (ME >= 0) {
+#pragma unroll
+            for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
+            __syncthreads();
             constexpr int NT2 = (KT1 - KA1) * MTE;      // MFMAs of the second half of A x; j = (kt - KA1) * MTE + tt
             constexpr int PS = (NT2 + KT_H - 1) / KT_H; // ... of which this many ride in each stage of the W2 stream
             bf16x8 bh[3], at[3 * (PS > 0 ? PS : 1)], bx2[KT1 - KA1 > 0 ? KT1 - KA1 : 1];
@@ -820,6 +821,9 @@ template <int NC, int NW> using V128 = Variant<4, 2, env_tiles(128, NW), 4, NC, 
 // extra 256 x 256 layers take the registers the second workgroup would have used.
 template <int NC, int NW, int ME> using V32D = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 1, ME>;
 template <int NC, int NW, int ME> using V64D = Variant<2, 1, env_tiles(64, NW), 2, NC, NW, 1, ME>;
+// A single hidden layer (m = 1) of the same two shapes: the second layer's phase and weights drop out.
+template <int NC, int NW> using V32S = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2, -1>;
+template <int NC, int NW> using V64S = Variant<2, 1, env_tiles(64, NW), 2, NC, NW, 1, -1>;
 template <int NC, int NW> using V256 = Variant<8, 2, env_tiles(256, NW), ES_V256_KTAR, NC, NW>;   // obs <= 256, act <= 32; part of A lives in LDS
 
 struct VariantInfo { int max_obs, max_act; const char* name; };
@@ -832,12 +836,12 @@ static const VariantInfo kVariants[] = {
 
 int mfma_variant_for(const es_config& c) {
   const uint32_t m = c.num_hidden ? c.num_hidden : 2;
-  if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP || m < 2 || m > 4) return -1;
+  if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP || m < 1 || m > 4) return -1;
   // narrow policies are served better by the one-wavefront-per-episode kernel when it fits
   if (c.hid_dim < 128 && wave_rollout_lds_bytes(c) <= 160 * 1024) return -1;
   for (int v = 0; v < 4; ++v)
     if ((int)c.obs_dim <= kVariants[v].max_obs && (int)c.act_dim <= kVariants[v].max_act)
-      return (m > 2 && v > 1) ? -1 : v;      // three and four hidden layers: the two narrow-observation shapes only
+      return (m != 2 && v > 1) ? -1 : v;      // one, three and four hidden layers: the two narrow-observation shapes only
   return -1;
 }
 
@@ -878,7 +882,10 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");
   const uint32_t units = s.N;      // one work item per individual
   const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
-  if (s.m == 3) {
+  if (s.m == 1) {
+    if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32S<4, 4>>(ctx, a, units, st) : launch_variant<V32S<16, 4>>(ctx, a, units, st);
+    if (ctx->mfma_variant == 1) return narrow ? launch_variant<V64S<4, 4>>(ctx, a, units, st) : launch_variant<V64S<16, 4>>(ctx, a, units, st);
+  } else if (s.m == 3) {
     if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32D<4, 4, 1>>(ctx, a, units, st) : launch_variant<V32D<16, 4, 1>>(ctx, a, units, st);
     if (ctx->mfma_variant == 1) return narrow ? launch_variant<V64D<4, 4, 1>>(ctx, a, units, st) : launch_variant<V64D<16, 4, 1>>(ctx, a, units, st);
   } else if (s.m == 4) {

@@ -181,7 +181,8 @@ def test_rollout_other_depths(es, w):
     assert not chaotic
 
 
-# three and four hidden layers of the paper's width (256) in bf16: the matrix-core kernel keeps the extra layers in registers
+# one, three and four hidden layers of the paper's width (256) in bf16: the matrix-core kernel skips the second layer's
+# phase, or keeps the extra layers in registers
 DEEP_MFMA_CASES = [
     Workload("deep3-obs8", pop=4, envs=16, horizon=40, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=71, num_hidden=3),
     Workload("deep4-obs8", pop=4, envs=16, horizon=40, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=72, num_hidden=4),
@@ -191,6 +192,12 @@ DEEP_MFMA_CASES = [
     Workload("deep3-obs60-hid200", pop=4, envs=20, horizon=30, obs=60, hid=200, act=10, dtype=1, noise_dtype=1, seed=75, num_hidden=3),
     Workload("deep4-obs60-relu", pop=4, envs=16, horizon=30, obs=60, hid=256, act=10, dtype=1, noise_dtype=1, seed=76, num_hidden=4,
              hidden_act=1),
+    Workload("one-layer-obs8", pop=4, envs=16, horizon=40, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=61, num_hidden=1),
+    Workload("one-layer-narrow-relu", pop=4, envs=3, horizon=40, obs=27, hid=256, act=8, dtype=1, noise_dtype=1, seed=62, num_hidden=1,
+             hidden_act=1),
+    Workload("one-layer-obs60-hid200", pop=4, envs=20, horizon=30, obs=60, hid=200, act=10, dtype=1, noise_dtype=1, seed=63, num_hidden=1),
+    Workload("one-layer-obs60-narrow-linear", pop=4, envs=2, horizon=30, obs=60, hid=256, act=16, dtype=1, noise_dtype=1, seed=64, num_hidden=1,
+             out_tanh=0),
     Workload("deep3-regen-linear-out", pop=5, envs=4, horizon=30, obs=17, hid=256, act=6, dtype=1, noise_dtype=3, seed=77, num_hidden=3,
              antithetic=0, out_tanh=0),
 ]
