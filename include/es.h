@@ -222,6 +222,23 @@ int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float*
               void* stream);
 
 /*
+ * es_update for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as es_update, bit for bit, minus workspace_d: the binary64 partial sums live
+ * in a built-in device array of es_static_scratch_bytes() = 32 MiB that every GPU the library runs
+ * on holds until the process ends (all five benchmark shapes fit, stored or regenerated noise).
+ * The call allocates and frees nothing and clears nothing (the reduction writes every partial it
+ * later reads).  A context whose es_workspace_bytes() exceeds the array is refused with
+ * ES_EUNSUPPORTED before any launch.  All calls on one GPU share that GPU's array, whatever their
+ * context: calls that may overlap in time on one GPU (different streams or threads) race and must
+ * be serialised by the caller; calls on one stream are safe.  The array's address is looked up
+ * once per device (in es_create when a GPU is current, else on the first call).
+ */
+size_t es_static_scratch_bytes(void);
+int es_update_static(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d,
+                     float* theta_d, float* m_d, float* v_d, float* grad_d, void* stream);
+
+/*
  * One whole generation - the four calls above in their order, es_sample_population(generation),
  * es_rollout(generation), es_rank, es_update(adam_step), enqueued on `stream` by one call: the
  * counterpart of the paper's Workflow.step() running as one device program (Sec. 3.1, 3.2).

@@ -65,6 +65,9 @@ def load_library() -> C.CDLL:
     lib.es_rank.argtypes = [vp, vp, vp, vp, vp]
     lib.es_update.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.es_generation.argtypes = [vp, u64, u64] + [vp] * 14
+    lib.es_update_static.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, vp]
+    lib.es_static_scratch_bytes.argtypes = []
+    lib.es_static_scratch_bytes.restype = sz
     return lib
 
 
@@ -194,6 +197,14 @@ class EsContext:
             _ptr(shaped, f32, self.cfg.pop, "shaped"), _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"),
             _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"),      # m, v may be None for ARS / VanillaES
             _ptr(workspace, torch.uint8, self.workspace_bytes, "workspace"), _stream()))
+
+    def update_static(self, adam_step: int, noise, shaped, theta, m, v, grad):
+        """``es_update`` without a workspace argument: partial sums go to the library's built-in scratch."""
+        f32, d, n = torch.float32, self.param_count, self.noise_rows * self.noise_ld
+        self._check(_lib.es_update_static(
+            self._h, adam_step, self._noise_ptr(noise, n),
+            _ptr(shaped, f32, self.cfg.pop, "shaped"), _ptr(theta, f32, d, "theta"), _ptr(m, f32, d, "m"),
+            _ptr(v, f32, d, "v"), _ptr(grad, f32, d, "grad"), _stream()))
 
     def generation(self, generation: int, adam_step: int, noise, a_mat, b_mat, theta, m, v, returns, ep_len, fitness,
                    rank, shaped, grad, workspace):

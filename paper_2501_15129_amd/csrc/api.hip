@@ -2,6 +2,7 @@
 // contract of every entry point.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "es_internal.hpp"
@@ -20,6 +21,37 @@ int check_launch(es_ctx* ctx, const char* what) {
 }
 
 static thread_local std::string g_create_error;
+
+// Scratch of es_update_static: the binary64 partial rows that es_update keeps in the caller's workspace
+// live here instead, in device memory that exists from the moment the code object is loaded until the
+// process ends, once per GPU.  In host code the array's name is only a handle for hipGetSymbolAddress;
+// the device address it yields (one per device) is what kernels and copies are given.
+constexpr size_t STATIC_SCRATCH_BYTES = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];     // device address of `scratch` on each GPU, or null
+
+// Address of this GPU's copy of `scratch` (looked up once per device, with that device current).
+static int static_scratch(es_ctx* ctx, void** out) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) { (void)hipGetLastError(); return fail(ctx, ES_EHIP, std::string("es_update_static: hipGetDevice: ") + hipGetErrorString(err)); }
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return fail(ctx, ES_EUNSUPPORTED, "es_update_static: device ordinal beyond 63");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return fail(ctx, ES_EHIP, std::string("es_update_static: hipGetSymbolAddress: ") + hipGetErrorString(err));
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return ES_OK;
+}
 
 }  // namespace es
 
@@ -89,6 +121,8 @@ int es_create(const es_config* cfg, es_ctx** out) {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0) lds = v;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    void* scratch_here = nullptr;
+    (void)static_scratch(nullptr, &scratch_here);   // resolve this GPU's scratch of es_update_static now, outside any capture
   } else {
     (void)hipGetLastError();   // no device here (host-only checks): keep the conservative default
   }
@@ -249,6 +283,23 @@ int es_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float*
   if (int rc = check_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, workspace_d, ctx->regen_valid)) return rc;
   return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, workspace_d,
                        static_cast<hipStream_t>(stream));
+}
+
+size_t es_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int es_update_static(es_ctx* ctx, uint64_t adam_step, const void* noise_d, const float* shaped_d, float* theta_d,
+                     float* m_d, float* v_d, float* grad_d, void* stream) {
+  if (!ctx) return ES_EINVAL;
+  if (ctx->workspace_bytes > STATIC_SCRATCH_BYTES)
+    return fail(ctx, ES_EUNSUPPORTED, "es_update_static: this shape needs " + std::to_string(ctx->workspace_bytes) +
+                                          " B of partial sums, more than the built-in scratch of " +
+                                          std::to_string(STATIC_SCRATCH_BYTES) + " B; use es_update with a workspace");
+  void* ws = nullptr;
+  if (int rc = static_scratch(ctx, &ws)) return rc;
+  if (int rc = check_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, ws, ctx->regen_valid)) return rc;
+  // every partial row the parameter step reads is written by the reduction kernel of the same call:
+  // nothing in the scratch has to start at zero
+  return launch_update(ctx, adam_step, noise_d, shaped_d, theta_d, m_d, v_d, grad_d, ws, static_cast<hipStream_t>(stream));
 }
 
 int es_generation(es_ctx* ctx, uint64_t generation, uint64_t adam_step, void* noise_d, const float* A_d, const float* B_d,
