@@ -48,6 +48,10 @@ class Workload:
     num_hidden: int = 2 # m hidden layers of width hid (paper Sec. 5.1 varies m; base case 2)
     noise_table_len: int = 0  # entries of the shared noise table (noise_dtype 4, 5; paper Sec. 5.1)
     episodes: int = 1   # episodes run back to back in every environment copy (auto-reset; paper Sec. 3.1)
+    # input recipe only (seen by make_inputs, not by the library or the checker):
+    a_radius: float = 0.9       # spectral radius the environment matrix A is rescaled to
+    b_var: float = 1.0 / 3.0    # variance of the entries of B
+    bias_std: float = 0.0       # standard deviation of the initial biases (0: biases start at zero)
 
     @property
     def n_params(self) -> int:
@@ -66,6 +70,22 @@ class Workload:
         """Same workload with the termination rule switched off (every episode runs T steps)."""
         return replace(self, name=self.name + "-fixedlen", done_thresh=math.inf)
 
+    def contractive(self) -> "Workload":
+        """Twin of this workload - same population, copies, horizon, widths, precision, fixed-length
+        episodes (the paper's timing protocol, Sec. 5.1) - whose closed loop s' = tanh(A s + B pi(s)) is a
+        contraction: A and B are drawn from the same streams and scaled down, and the policy starts with
+        non-zero biases so that every individual settles at its own non-trivial fixed point.  Rounding
+        differences between two evaluations of such a loop die out instead of growing, so the returns of a
+        finite-precision evaluation can be held to the strict tolerance at the full horizon."""
+        return replace(self, name=self.name + "-contractive", done_thresh=math.inf,
+                       a_radius=CONTRACTIVE_A_RADIUS, b_var=CONTRACTIVE_B_VAR, bias_std=CONTRACTIVE_BIAS_STD)
+
+
+# Scales of the contractive twins (chosen by measurement on the CPU checker alone: one-ulp nudges of a
+# handful of operands move no return of any twin by more than 1/8 of its tolerance at T = 1000).
+CONTRACTIVE_A_RADIUS = 0.5
+CONTRACTIVE_B_VAR = 0.1
+CONTRACTIVE_BIAS_STD = 0.3
 
 CONFIGS = (
     Workload("cfg0", pop=8, envs=4, horizon=100, obs=11, hid=32, act=3, dtype=0, noise_dtype=0, seed=0),
@@ -86,21 +106,23 @@ def layer_shapes(w: Workload):
 def make_inputs(w: Workload):
     """Draw A [n_o,n_o], B [n_o,n_a], theta0 [D] (float32) for a workload, from its seed.
 
-    A: i.i.d. N(0,1) rescaled to spectral radius 0.9.  B: i.i.d. N(0, 1/3).
-    theta0: every weight matrix N(0, 2/(fan_in+fan_out)), biases zero.
+    A: i.i.d. N(0,1) rescaled to spectral radius ``a_radius`` (0.9).  B: i.i.d. N(0, ``b_var``) (1/3).
+    theta0: every weight matrix N(0, 2/(fan_in+fan_out)), biases zero (N(0, ``bias_std``^2) for the
+    contractive twins).
     """
     rng = np.random.default_rng([int(w.seed), 0x45534D49])
     g = rng.standard_normal((w.obs, w.obs))
     rho = float(np.max(np.abs(np.linalg.eigvals(g))))
-    a_mat = (0.9 / rho) * g
-    b_mat = rng.standard_normal((w.obs, w.act)) * math.sqrt(1.0 / 3.0)
+    a_mat = (w.a_radius / rho) * g
+    b_mat = rng.standard_normal((w.obs, w.act)) * math.sqrt(w.b_var)
     parts = []
+    bias_rng = np.random.default_rng([int(w.seed), 0x42494153])     # a stream of its own: the weights do not move
     for shp in layer_shapes(w):
         if len(shp) == 2:
             fan_out, fan_in = shp
             parts.append((rng.standard_normal(shp) * math.sqrt(2.0 / (fan_in + fan_out))).ravel())
         else:
-            parts.append(np.zeros(shp))
+            parts.append(bias_rng.standard_normal(shp) * w.bias_std if w.bias_std else np.zeros(shp))
     theta0 = np.concatenate(parts)
     assert theta0.size == w.n_params
     return (np.ascontiguousarray(a_mat, dtype=np.float32),

@@ -5,6 +5,8 @@ from __future__ import annotations
 import numpy as np
 import torch
 
+from sensitivity import probe_rollout, spread_of  # noqa: F401  (re-exported for the test modules)
+
 # Target tolerances: episode returns within 1e-4 relative in fp32 and 2e-2 in bf16;
 # updated parameters within 1e-5 relative (+1e-7 absolute for parameters near zero).
 RET_RTOL = {0: 1e-4, 1: 2e-2}
@@ -50,42 +52,56 @@ def run_rollout(ctx, w, gen, theta, noise_dev, a_mat, b_mat):
     return ret.cpu().numpy(), ln.cpu().numpy(), fit.cpu().numpy()
 
 
-# A trajectory is called sensitive when the checker's OWN second evaluation of it (same
-# algorithm, binary32 accumulation instead of binary64) already drifts from the reference by
-# more than this fraction of the tolerance: some random policies make the closed loop
-# chaotic, and there no finite-precision kernel can track the binary64 return (in bf16 mode a
-# single flipped rounding decorrelates the trajectories).  Such episodes are held to
-# SENSITIVE_RTOL instead, and the share of episodes that actually need the allowance is capped
-# - unless the whole batch is in the chaotic regime (more than CHAOTIC_SHARE of its episodes
-# flagged): then every episode is held to SENSITIVE_RTOL, the batch mean to CHAOTIC_MEAN_RTOL,
-# and the caller must ALSO pass a strict comparison at a horizon short enough for the
-# trajectories not to have diverged (the per-step code path is the same for every step).
+# A trajectory is called sensitive when the checker's OWN returns move by more than this fraction of the
+# tolerance after a handful of operands have been nudged by one unit in the last place of the operand type
+# (tests/sensitivity.py): some random policies make the closed loop chaotic, and there no finite-precision
+# kernel can track the binary64 return - one different rounding decision decorrelates the trajectories.
+# Nothing about the allowance is a free tolerance:
+#  * regular regime - a sensitive episode is held to SPREAD_FACTOR times the spread the checker itself showed
+#    for it (never less than the regular tolerance), the share of episodes that actually need the allowance is
+#    capped, and every one of them is listed with its checker-side spread.  SPREAD_FACTOR: the probe moves
+#    eight operands per matrix once and takes the largest of three draws, which averages 0.85 sigma of the
+#    episode's own scatter; a correct kernel's deviation is one more draw, and 4 x that covers 3.4 sigma.
+#  * chaotic regime (more than CHAOTIC_SHARE of a batch flagged AND some episode beyond the regular tolerance) -
+#    the nudged and the reference evaluation are then independent draws from each episode's own return
+#    distribution, and so is a correct kernel's: its deviations must be statistically indistinguishable from the
+#    checker's own.  Root mean square over the batch within CHAOTIC_RMS_RATIO of the probes' (256 episodes pin
+#    an rms to ~10 %), largest deviation within CHAOTIC_MAX_RATIO of the largest any probe showed on any
+#    episode of the batch (three times as many draws as the kernel has), batch mean within SPREAD_FACTOR
+#    times the shift of the checker's own batch mean under the nudges.  The caller must ALSO pass a strict
+#    comparison on a workload of the same shape and launch configuration whose loop is not chaotic.
 SENSITIVE_FRACTION_OF_RTOL = 0.125
-SENSITIVE_RTOL = 5e-2
+SPREAD_FACTOR = 4.0
 MAX_SENSITIVE_SHARE = 0.03
 CHAOTIC_SHARE = 0.25
-CHAOTIC_MEAN_RTOL = 1.5e-2
+CHAOTIC_RMS_RATIO = 1.5
+CHAOTIC_MAX_RATIO = 2.0
 
 
 def compare_rollout(w, got, ref, label="", probe=None):
     """got = (returns, ep_len, fitness) from the GPU; ref = (returns, ep_len, fitness, margin) from the
-    checker in binary64; probe = the checker's binary32 evaluation of the same episodes (optional).
+    checker in binary64; probe = probe_rollout() of the same episodes (optional).
 
     Episode lengths must be identical except for episodes the checker flags as knife-edge;
     returns are compared where the lengths agree; fitness where every episode of the
     individual agrees.  Returns (knife-edge flips, worst error on regular episodes,
-    number of sensitive episodes, chaotic-regime flag)."""
+    number of sensitive episodes, chaotic-regime flag).  The flag says that the chaotic-regime allowance
+    was USED: a batch the probe flags as chaotic in which every episode nevertheless meets the regular
+    tolerance has been verified strictly, and is reported as such (flag False, worst = over all episodes)."""
     g_ret, g_len, g_fit = got
     r_ret, r_len, r_fit, r_mar = ref
     rtol = RET_RTOL[w.dtype]
     scale = np.maximum(np.abs(r_ret), 1e-3)
     if probe is not None:
-        sens = (np.abs(probe[0].astype(np.float64) - r_ret) / scale > SENSITIVE_FRACTION_OF_RTOL * rtol) | (probe[1] != r_len)
+        spread, mean_spread, dev = spread_of(probe, r_ret, r_len)
+        sens = spread > SENSITIVE_FRACTION_OF_RTOL * rtol
     else:
+        spread, mean_spread, dev = np.zeros(r_ret.shape), 0.0, np.zeros(r_ret.shape + (1,))
         sens = np.zeros(r_ret.shape, dtype=bool)
-    chaotic = bool(np.mean(sens) > CHAOTIC_SHARE)
-    if chaotic:
-        sens = np.ones_like(sens)
+    flagged_chaotic = bool(np.mean(sens) > CHAOTIC_SHARE)
+    finite = spread[np.isfinite(spread)]
+    # an episode whose LENGTH a nudge changed has no spread of its own: it borrows the largest finite one
+    own = np.where(np.isfinite(spread), spread, float(finite.max()) if finite.size else 1.0)
     edge = (r_mar < KNIFE_EDGE[w.dtype]) | sens
     same = g_len == r_len
     assert np.all(same | edge), f"{label}: episode length differs away from the termination threshold: " \
@@ -97,12 +113,36 @@ def compare_rollout(w, got, ref, label="", probe=None):
     worst = float(np.max(np.where(same & ~sens, err, 0.0)))
     assert worst <= rtol, f"{label}: return mismatch {worst:.3e} > {rtol}"
     worst_sens = float(np.max(np.where(same & sens, err, 0.0)))
-    assert worst_sens <= SENSITIVE_RTOL, f"{label}: return mismatch {worst_sens:.3e} on a sensitive episode"
+    excused = same & sens & (err > rtol)
+    chaotic = flagged_chaotic and bool(excused.any())
+    n_flagged = int(sens.sum())
+    if flagged_chaotic and not chaotic:
+        print(f"[{label}] the checker's probe flags this batch as chaotic (largest spread {float(finite.max()):.2e}), yet every "
+              f"episode meets {rtol}: worst {worst_sens:.2e}")
+        worst = max(worst, worst_sens)
+        sens = np.zeros_like(sens)          # verified strictly: the fitness check below covers every individual
     if chaotic:
+        pooled = dev[np.isfinite(dev)]
+        probe_rms, probe_max = float(np.sqrt(np.mean(np.square(pooled)))), float(pooled.max())
+        kern = err[same]
+        kern_rms, kern_max = float(np.sqrt(np.mean(np.square(kern)))), float(kern.max())
         mean_err = abs(float(np.mean(g_ret[same].astype(np.float64))) - float(np.mean(r_ret[same]))) / abs(float(np.mean(r_ret[same])))
-        assert mean_err <= CHAOTIC_MEAN_RTOL, f"{label}: mean return over the batch off by {mean_err:.3e}"
+        print(f"[{label}] chaotic regime: {int(excused.sum())} of {same.size} episodes beyond {rtol}; deviation from the reference, "
+              f"kernel vs the checker's own nudged evaluations: rms {kern_rms:.2e} vs {probe_rms:.2e}, max {kern_max:.2e} vs {probe_max:.2e}, "
+              f"batch mean {mean_err:.2e} vs {mean_spread:.2e}")
+        assert kern_rms <= CHAOTIC_RMS_RATIO * probe_rms, f"{label}: kernel deviations (rms {kern_rms:.3e}) exceed the checker's own scatter (rms {probe_rms:.3e})"
+        assert kern_max <= CHAOTIC_MAX_RATIO * probe_max, f"{label}: largest kernel deviation {kern_max:.3e} against the checker's own {probe_max:.3e}"
+        assert mean_err <= max(SPREAD_FACTOR * mean_spread, SENSITIVE_FRACTION_OF_RTOL * rtol), \
+            f"{label}: mean return over the batch off by {mean_err:.3e} (checker's own shift {mean_spread:.3e})"
+        sens = np.ones_like(sens)
     else:
-        excused = same & sens & (err > rtol)
+        tol = np.where(sens, np.maximum(rtol, SPREAD_FACTOR * own), rtol)
+        for ix in np.argwhere(excused):
+            print(f"[{label}] excused episode {tuple(int(k) for k in ix)}: kernel deviation {float(err[tuple(ix)]):.2e}, "
+                  f"checker-side spread {float(spread[tuple(ix)]):.2e}")
+        over = same & sens & (err > tol)
+        assert not over.any(), f"{label}: {int(over.sum())} sensitive episodes beyond {SPREAD_FACTOR} x the checker's own spread, e.g. " \
+            f"{[(tuple(int(k) for k in ix), float(err[tuple(ix)]), float(own[tuple(ix)])) for ix in np.argwhere(over)[:4]]}"
         assert np.mean(excused) <= MAX_SENSITIVE_SHARE + 1.0 / same.size, \
             f"{label}: {int(excused.sum())} sensitive episodes beyond the regular tolerance"
     ind_ok = np.all(same & ~sens, axis=1)
@@ -110,7 +150,9 @@ def compare_rollout(w, got, ref, label="", probe=None):
     assert float(np.max(np.where(ind_ok, ferr, 0.0))) <= rtol, f"{label}: fitness mismatch"
     # fitness is the mean of the returns the kernel itself produced
     assert np.allclose(g_fit, g_ret.astype(np.float64).mean(axis=1), rtol=1e-5, atol=1e-5), f"{label}: fitness != mean"
-    return int(np.sum(~same)), (worst_sens if chaotic else worst), int(sens.sum()), chaotic
+    compare_rollout.last_excused = int(excused.sum())
+    compare_rollout.last_sensitive = n_flagged
+    return int(np.sum(~same)), (worst_sens if chaotic else worst), n_flagged, chaotic
 
 
 def assert_params_close(got, ref, label=""):

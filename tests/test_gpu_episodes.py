@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs
-from gpu_util import assert_params_close, compare_rollout, dev, noise_to_device, run_rollout
+from gpu_util import assert_params_close, compare_rollout, dev, noise_to_device, run_rollout, probe_rollout
 
 pytestmark = pytest.mark.gpu
 
@@ -45,7 +45,7 @@ def test_rollout_episodes_per_env(es, w, kernel):
     got = run_rollout(ctx, w, 1, theta, noise_to_device(ctx, eps), a_mat, b_mat)
     assert got[0].shape == (w.pop, w.envs * w.episodes)
     ref = oracle.rollout(w, 1, theta, eps, a_mat, b_mat)
-    probe = oracle.rollout(w, 1, theta, eps, a_mat, b_mat, arith=1)
+    probe = probe_rollout(w, 1, theta, eps, a_mat, b_mat, ref=ref)
     flips, worst, sens, chaotic = compare_rollout(w, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens}")
     assert not chaotic
@@ -103,7 +103,7 @@ def test_full_size_configs_with_four_episodes_per_env(es, idx):
         eps_j = oracle.sample_population(short, 0, rows=(j, j + 1))
         ind = (2 * j, 2 * j + 2)
         refs.append(oracle.rollout(short, 0, theta, eps_j, a_mat, b_mat, individuals=ind, noise_row0=j))
-        probes.append(oracle.rollout(short, 0, theta, eps_j, a_mat, b_mat, individuals=ind, noise_row0=j, arith=1))
+        probes.append(probe_rollout(short, 0, theta, eps_j, a_mat, b_mat, individuals=ind, noise_row0=j, ref=refs[-1]))
         subs.append(tuple(x[ind[0]:ind[1]] for x in got))
     cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
     flips, worst, sens, chaotic = compare_rollout(short, cat(subs), cat(refs), short.name, cat(probes))

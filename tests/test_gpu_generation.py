@@ -81,6 +81,47 @@ def test_three_generations_chained(es, w):
         assert np.max(rel) <= (1e-4 if w.dtype == 0 else 2e-2)
 
 
+@pytest.mark.parametrize("idx", [3, 4])
+def test_one_generation_full_size_chained(es, idx):
+    """configs[3] and configs[4] exactly as specified, whole population, the four calls chained on the GPU:
+    sampled noise rows bit-equal to the checker's, 32 sampled mirrored pairs of the rollout against the checker,
+    ranks of the GPU's own fitness bit-equal, and the update of all parameters against the checker's update fed
+    with the checker's own full noise matrix and those ranks."""
+    from gpu_util import compare_rollout, probe_rollout
+    w = CONFIGS[idx]
+    a_mat, b_mat, theta = make_inputs(w)
+    run = GpuChain(es, w, theta, a_mat, b_mat)
+    run.generation(0)
+    th_g, m_g, v_g, fit_g, rank_g = run.state()
+    shaped_g = run.shaped.cpu().numpy()
+    ret_g, len_g = run.ret.cpu().numpy(), run.len.cpu().numpy()
+    eps = oracle.sample_population(w, 0)                         # the checker's own full matrix
+    d, rows, block = w.n_params, w.noise_rows, 8
+    rng = np.random.default_rng([idx, 77])
+    starts = sorted({0, rows - block, *(int(x) for x in rng.integers(1, rows - block, size=2))})
+    refs, probes, subs = [], [], []
+    for j in starts:
+        got_rows = run.noise[j:j + block].float().cpu().numpy()
+        assert np.array_equal(got_rows[:, :d].view(np.uint32), eps[j:j + block].view(np.uint32)), f"noise rows {j}.."
+        ind = (2 * j, 2 * (j + block))
+        refs.append(oracle.rollout(w, 0, theta, eps[j:j + block], a_mat, b_mat, individuals=ind, noise_row0=j))
+        probes.append(probe_rollout(w, 0, theta, eps[j:j + block], a_mat, b_mat, individuals=ind, noise_row0=j, ref=refs[-1]))
+        subs.append((ret_g[ind[0]:ind[1]], len_g[ind[0]:ind[1]], fit_g[ind[0]:ind[1]]))
+    cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
+    flips, worst, sens, chaotic = compare_rollout(w, cat(subs), cat(refs), f"{w.name} chained", cat(probes))
+    assert not chaotic
+    rank, shaped = oracle.rank(fit_g)                            # discrete selection: continue from the GPU's fitness
+    assert np.array_equal(rank_g, rank) and np.array_equal(shaped_g.view(np.uint32), shaped.view(np.uint32))
+    th, m, v, _ = oracle.update(w, 1, eps, shaped, theta, np.zeros_like(theta), np.zeros_like(theta))
+    assert_params_close(th_g, th, f"{w.name} theta")
+    assert_params_close(m_g, m, f"{w.name} m")
+    assert_params_close(v_g, v, f"{w.name} v")
+    print(f"[{w.name}] chained generation: {len(starts) * block} pairs worst {worst:.2e} flips {flips} sensitive {sens}; "
+          f"{d} parameters updated, {float(np.mean(th_g == th)):.4f} bit-equal")
+    del run, eps
+    torch.cuda.empty_cache()
+
+
 def test_rerun_and_resume_are_bit_identical(es):
     """Counter-based noise and resets make a run a pure function of (theta, m, v, generation):
     four generations in one go equal two generations, a saved state, and two more."""

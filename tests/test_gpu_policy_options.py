@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs
-from gpu_util import compare_rollout, noise_to_device, run_rollout
+from gpu_util import compare_rollout, noise_to_device, run_rollout, probe_rollout
 
 pytestmark = pytest.mark.gpu
 
@@ -29,7 +29,7 @@ def _case(es, w, gen=1, expect_kernel=None):
     eps = oracle.sample_population(w, gen)
     got = run_rollout(ctx, w, gen, theta, noise_to_device(ctx, eps), a_mat, b_mat)
     ref = oracle.rollout(w, gen, theta, eps, a_mat, b_mat)
-    probe = oracle.rollout(w, gen, theta, eps, a_mat, b_mat, arith=1)
+    probe = probe_rollout(w, gen, theta, eps, a_mat, b_mat, ref=ref)
     flips, worst, sens, chaotic = compare_rollout(w, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
     assert not chaotic
@@ -85,7 +85,7 @@ def test_rollout_relu_full_size_bf16_configs(es, idx):
         eps = oracle.sample_population(w, 0, rows=(j, j + 1))
         ind = (2 * j, 2 * j + 2)
         refs.append(oracle.rollout(w, 0, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j))
-        probes.append(oracle.rollout(w, 0, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, arith=1))
+        probes.append(probe_rollout(w, 0, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, ref=refs[-1]))
         subs.append(tuple(x[ind[0]:ind[1]] for x in got))
     cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
     flips, worst, sens, chaotic = compare_rollout(w, cat(subs), cat(refs), w.name, cat(probes))
@@ -129,7 +129,7 @@ def test_rollout_with_observation_statistics(es, w):
     ctx.set_obs_norm(dev(mean), dev(inv))
     got = run_rollout(ctx, w, 1, theta, noise, a_mat, b_mat)
     ref = oracle.rollout(ws, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
-    probe = oracle.rollout(ws, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), arith=1)
+    probe = probe_rollout(ws, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), ref=ref)
     flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
     assert not chaotic
@@ -175,7 +175,7 @@ def test_rollout_other_depths(es, w):
     noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
     got = run_rollout(ctx, w, 2, theta, noise, a_mat, b_mat)
     ref = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat)
-    probe = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat, arith=1)
+    probe = probe_rollout(ws, 2, theta, eps, a_mat, b_mat, ref=ref)
     flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} D={ctx.param_count} worst {worst:.2e} flips {flips} sensitive {sens}")
     assert not chaotic
@@ -214,7 +214,7 @@ def test_rollout_deep_policies_on_the_matrix_core_kernel(es, w):
     noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
     got = run_rollout(ctx, w, 2, theta, noise, a_mat, b_mat)
     ref = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat)
-    probe = oracle.rollout(ws, 2, theta, eps, a_mat, b_mat, arith=1)
+    probe = probe_rollout(ws, 2, theta, eps, a_mat, b_mat, ref=ref)
     flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} D={ctx.param_count} worst {worst:.2e} flips {flips} sensitive {sens}")
     assert not chaotic
@@ -233,7 +233,7 @@ def test_deep_policy_with_obs_norm_on_the_matrix_core_kernel(es):
     eps = oracle.sample_population(w, 1)
     got = run_rollout(ctx, w, 1, theta, noise_to_device(ctx, eps), a_mat, b_mat)
     ref = oracle.rollout(w, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv))
-    probe = oracle.rollout(w, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), arith=1)
+    probe = probe_rollout(w, 1, theta, eps, a_mat, b_mat, obs_norm=(mean, inv), ref=ref)
     flips, worst, sens, chaotic = compare_rollout(w, got, ref, w.name, probe)
     assert not chaotic
 

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 from paper_2501_15129_amd.workloads import CONFIGS, Workload, make_inputs, random_fitness
-from gpu_util import assert_params_close, compare_rollout, dev, run_rollout
+from gpu_util import assert_params_close, compare_rollout, dev, run_rollout, probe_rollout
 
 pytestmark = pytest.mark.gpu
 
@@ -53,7 +53,7 @@ def test_rollout_regenerated_matches_checker_and_stored_mode(es, w):
     got = run_rollout(ctx, w, 3, theta, None, a_mat, b_mat)
     eps = oracle.sample_population(ws, 3)
     ref = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat)
-    probe = oracle.rollout(ws, 3, theta, eps, a_mat, b_mat, arith=1)
+    probe = probe_rollout(ws, 3, theta, eps, a_mat, b_mat, ref=ref)
     flips, worst, sens, chaotic = compare_rollout(ws, got, ref, w.name, probe)
     print(f"[{w.name}] kernel={ctx.rollout_kernel} worst {worst:.2e} flips {flips} sensitive {sens} chaotic {chaotic}")
     assert not chaotic
@@ -133,7 +133,7 @@ def test_generation_regenerated_full_size_cfg4(es):
         eps = oracle.sample_population(base, 1, rows=(j, j + 1))
         ind = (2 * j, 2 * j + 2)
         refs.append(oracle.rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j))
-        probes.append(oracle.rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, arith=1))
+        probes.append(probe_rollout(base, 1, theta, eps, a_mat, b_mat, individuals=ind, noise_row0=j, ref=refs[-1]))
         subs.append(tuple(x[ind[0]:ind[1]] for x in got))
     cat = lambda parts: tuple(np.concatenate([p[k] for p in parts]) for k in range(len(parts[0])))
     _, worst, _, chaotic = compare_rollout(base, cat(subs), cat(refs), w.name, cat(probes))

@@ -49,11 +49,13 @@ def test_sample_population_bit_exact(es, w, gen):
     assert np.all(got[:, d:] == 0.0)
 
 
-def test_sample_population_full_size_sampled_rows(es):
-    """cfg4 at full size (2048 x 133120 bf16): a few rows against the checker, all rows finite."""
-    w = CONFIGS[4]
+@pytest.mark.parametrize("idx", [3, 4])
+def test_sample_population_full_size_sampled_rows(es, idx):
+    """configs[3] (512 x 75264 bf16) and configs[4] (2048 x 133120 bf16) at full size: rows against the checker
+    bit for bit, all rows finite."""
+    w = CONFIGS[idx]
     ctx, noise = _sample(es, w, gen=1)
-    for j in (0, 1, 777, w.noise_rows - 1):
+    for j in (0, 1, 2, 3, w.noise_rows // 3, w.noise_rows // 2, w.noise_rows - 2, w.noise_rows - 1):
         want = oracle.sample_population(w, 1, rows=(j, j + 1))[0]
         got = noise[j].float().cpu().numpy()
         assert np.array_equal(got[: w.n_params].view(np.uint32), want.view(np.uint32))
@@ -144,10 +146,13 @@ def test_update_grad_pointer_optional_and_rerun_identical(es):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
-def test_update_full_size_cfg4(es):
-    """cfg4 at full size: GPU-sampled noise (bit-equal to the checker's, see the sampling test),
-    checker-side update over all 132 881 parameters from the same matrix."""
-    w = CONFIGS[4]
+@pytest.mark.parametrize("idx", [3, 4])
+def test_update_full_size(es, idx):
+    """configs[3] (one-launch kernel, 512 rows x 75 016 parameters) and configs[4] (chunked stream, 2048 rows x
+    132 881 parameters) at full size: GPU-sampled noise (bit-equal to the checker's, see the sampling test),
+    checker-side update over every parameter from the checker's own matrix."""
+    w = CONFIGS[idx]
+    assert ("single_pass" in es.EsContext(w).update_kernel) == (idx == 3)
     ctx, noise = _sample(es, w, gen=2)
     d = w.n_params
     rng = np.random.default_rng(4)
@@ -162,6 +167,6 @@ def test_update_full_size_cfg4(es):
     ctx.update(5, noise, dev(shaped), th_d, m_d, v_d, g_d, ctx.alloc_workspace())
     torch.cuda.synchronize()
     for got, ref, name in ((th_d, want[0], "theta"), (m_d, want[1], "m"), (v_d, want[2], "v"), (g_d, want[3], "grad")):
-        assert_params_close(got.cpu().numpy(), ref, f"cfg4 {name}")
+        assert_params_close(got.cpu().numpy(), ref, f"{w.name} {name}")
     del noise
     torch.cuda.empty_cache()
