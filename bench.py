@@ -82,8 +82,20 @@ def run_generations(torch, ctx, w, bufs, steps, warmup, gen0=0):
     return wall, stage, live
 
 
-def cpu_baseline(w, budget_s=12.0, obs_norm=None):
-    """The CPU checker, as it stands, on a bounded sample of the same workload (host cores of this machine)."""
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, budget_s=12.0, obs_norm=None, full=False):
+    """The CPU checker, as it stands, on the host cores of this machine: a bounded sample of the same workload by
+    default (said so in the result), the whole population once with full=True.  Small workloads (under a
+    second of checker time) are run whole, and once more on a single thread."""
     import numpy as np
     import oracle
     from paper_2501_15129_amd.workloads import make_inputs
@@ -106,16 +118,45 @@ def cpu_baseline(w, budget_s=12.0, obs_norm=None):
             oracle.update(ws, 1, eps, shaped, theta, np.zeros_like(theta), np.zeros_like(theta))
         return time.perf_counter() - t0, int(ln.sum())
 
-    n = min(w.pop, 2 * ((threads + 1) // 2))
+    n = w.pop if full else min(w.pop, 2 * ((threads + 1) // 2))
     dt, steps = timed(n)
     if dt < budget_s and n < w.pop:
         n2 = min(w.pop, 2 * int(max(1, (budget_s / max(dt, 1e-3)) * n / 2)))
         if n2 > n:
             n = n2
             dt, steps = timed(n)
-    return {"value": steps / dt, "unit": "env-steps/s", "cores": threads, "kind": "oracle",
-            "sample": f"one full generation (sample, rollout, rank, update) of the first {n} of {w.pop} individuals "
-                      f"x {w.envs} envs x T={w.horizon}, {steps} env-steps in {dt:.1f} s, OpenMP over individuals"}
+    whole = n == w.pop
+    out = {"value": steps / dt, "unit": "env-steps/s", "cores": threads, "kind": "oracle", "cpu_model": cpu_model(),
+           "is_sample": not whole, "sampled_fraction_of_population": n / w.pop, "seconds": dt,
+           "sample": (f"the WHOLE population, one full generation (sample, rollout, rank, update): {w.pop} individuals" if whole else
+                      f"a SAMPLE, not the whole job: one full generation (sample, rollout, rank, update) of the first {n} of {w.pop} individuals")
+                     + f" x {w.envs} envs x T={w.horizon}, {steps} env-steps in {dt:.1f} s, OpenMP over individuals on {threads} threads"
+                     + ("" if whole else "; bench.py --cpu-full runs all of it")}
+    if whole and dt < 5.0:          # the small workloads: also on one thread
+        oracle.set_threads(1)
+        try:
+            dt1, steps1 = timed(n)
+        finally:
+            oracle.set_threads(threads)
+        out["single_thread"] = {"value": steps1 / dt1, "unit": "env-steps/s", "seconds": dt1}
+    return out
+
+
+def measured_peaks(iters=4096):
+    """Runs the rate micro-benchmarks of csrc/microbench.hip (every CU, one workgroup each) and returns their figures."""
+    import ctypes as C
+    lib = C.CDLL(str(ROOT / "paper_2501_15129_amd" / "libes_microbench.so"))
+    lib.es_microbench_name.restype = C.c_char_p
+    lib.es_microbench_unit.restype = C.c_char_p
+    rows = []
+    for k in range(lib.es_microbench_count()):
+        cyc, ms, rate = C.c_double(), C.c_double(), C.c_double()
+        rc = lib.es_microbench_run(k, iters, C.byref(cyc), C.byref(ms), C.byref(rate))
+        if rc != 0:
+            raise RuntimeError(f"micro-benchmark {k} failed with HIP error {rc}")
+        rows.append({"test": lib.es_microbench_name(k).decode(), "unit": lib.es_microbench_unit(k).decode(),
+                     "cycles_per_unit_one_wavefront": cyc.value, "launch_ms": ms.value, "chip_units_per_s": rate.value})
+    return rows
 
 
 def main() -> int:
@@ -146,9 +187,17 @@ def main() -> int:
     ap.add_argument("--episodes-per-env", type=int, default=1,
                     help="k episodes per environment copy (auto-reset wrapper, paper Sec. 3.1); not the default workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-full", action="store_true",
+                    help="run the CPU checker once over the WHOLE population instead of a bounded sample (about two minutes at configs[4])")
+    ap.add_argument("--no-antithetic", action="store_true",
+                    help="independent noise rows for every individual (antithetic = 0): at configs[4] es_update then streams the literal "
+                         "4096 x 132k bf16 matrix, 1.09 GB")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the extra timing with the termination rule on")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain device copies of a known size instead (reference for the HBM byte counters)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="run the rate micro-benchmarks instead (matrix-core and vector-ALU issue, their overlap, transcendentals, "
+                         "LDS, barriers) and print them as one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; --gpus N with N > 1 is not supported "
@@ -164,6 +213,13 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.peaks:
+        rows = measured_peaks()
+        mfma = rows[0]["chip_units_per_s"] * 2 * 16 * 16 * 32 / 1e12
+        fma = rows[3]["chip_units_per_s"] * 64 * 2 / 1e12
+        print(json.dumps({"peaks": rows, "derived": {"bf16_mfma_tflops_one_wavefront_per_simd": mfma, "published_bf16_mfma_tflops": MFMA_BF16_PEAK_TFLOPS,
+                                                     "fp32_fma_tflops_one_wavefront_per_simd": fma, "published_fp32_vector_tflops": FP32_VALU_PEAK_TFLOPS}}))
+        return 0
     if args.copy_calibration:
         n_bytes = 1 << 30
         src = torch.empty(n_bytes, dtype=torch.uint8, device="cuda").fill_(1)
@@ -188,6 +244,8 @@ def main() -> int:
         base = replace(base, name=base.name + "-ars", algorithm=1, num_elites=max(1, base.pop // 8), lr=0.02, sigma=0.03)
     elif args.algorithm == "vanilla":
         base = replace(base, name=base.name + "-vanilla", algorithm=2, num_elites=max(1, base.pop // 8), antithetic=0)
+    if args.no_antithetic:
+        base = replace(base, name=base.name + "-noanti", antithetic=0)
     if args.num_hidden != 2:
         base = replace(base, name=base.name + f"-m{args.num_hidden}", num_hidden=args.num_hidden)
     if args.episodes_per_env != 1:
@@ -238,8 +296,19 @@ def main() -> int:
     roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    traffic = (measured_traffic(w.name) if args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm and args.episodes_per_env == 1 and args.num_hidden == 2 and not args.paper_base and args.pop is None else None) or {}
+    if bf16 and "mfma" in ctx.rollout_kernel:
+        # the environment copies are the 16 columns of the matrix-core tile: with fewer episodes per individual only
+        # that share of every MFMA is algorithmic work, whatever the kernel does
+        cols = min(16, ctx.episodes) if ctx.episodes <= 16 else ctx.episodes / (16 * ((ctx.episodes + 15) // 16)) * 16
+        roofline["column_ceiling"] = cols / 16.0
+        roofline["frac_of_column_ceiling"] = (ach / peak) / (cols / 16.0)
+    plain = (args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm
+             and args.episodes_per_env == 1 and args.num_hidden == 2 and not args.paper_base and args.pop is None
+             and not args.no_antithetic)
+    traffic = (measured_traffic(w.name) if plain else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
+    if traffic:
+        roofline["traffic_source"] = f"profiles/hbm_traffic_{w.name.replace('-', '_')}.txt: two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this command, scaled by a plain copy"
     ub = update_bytes(w, ctx)
     ugbs = ub / (upd_ms * 1e-3) / 1e9
     roofline_update = {"kernel": ctx.update_kernel, "bound": "hbm", "achieved": ugbs, "peak": HBM_PEAK_GBS,
@@ -284,7 +353,7 @@ def main() -> int:
                                         "stage_ms": {k: mean(v) for k, v in stage2.items()}}
         del ctx2, bufs2
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, obs_norm=obs_stats)
+        out["cpu_baseline"] = cpu_baseline(w, obs_norm=obs_stats, full=args.cpu_full)
         out["cpu_baseline"]["host_cpus_visible"] = os.cpu_count()
     print(json.dumps(out))
     return 0

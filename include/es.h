@@ -9,8 +9,12 @@
  *
  * Conventions
  *   - Every pointer whose name ends in _d is a DEVICE pointer owned by the caller.  The
- *     library never allocates, frees or retains device memory; the buffers must stay
- *     valid until the work enqueued on `stream` has completed.
+ *     library never allocates, frees or retains device memory (the one exception is the built-in
+ *     scratch of es_update_static); the buffers must stay valid until the work enqueued on
+ *     `stream` has completed.
+ *   - Alignment: theta_d, noise_d, A_d, B_d and workspace_d must be 16-byte aligned (the kernels
+ *     read them with 16-byte vector loads); every other array needs the alignment of its element
+ *     type.  A misaligned pointer is ES_EINVAL.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every hot
  *     call only enqueues kernels; none of them synchronises or reads back.
  *   - Return value: ES_OK (0) or a negative es_status.  Nothing throws or aborts;

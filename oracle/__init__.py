@@ -33,15 +33,29 @@ class OrcConfig(C.Structure):
     ]
 
 
-def build(force: bool = False) -> Path:
-    """Compile the checker with gcc (contraction off so the binary32 sequences are exact)."""
-    stale = (not _LIB.exists()) or any(p.stat().st_mtime > _LIB.stat().st_mtime for p in _SRC)
+_LIB_SAN = _HERE / "liboracle_san.so"
+
+
+def build(force: bool = False, sanitize: bool = False) -> Path:
+    """Compile the checker with gcc (contraction off so the binary32 sequences are exact).
+
+    ``sanitize=True`` builds a second library, ``liboracle_san.so``, with AddressSanitizer and
+    UndefinedBehaviorSanitizer (host code only); a process that loads it needs the sanitizer runtime
+    preloaded (``sanitizer_runtime()``), which is what the sanitizer test's child process does."""
+    lib_path = _LIB_SAN if sanitize else _LIB
+    stale = (not lib_path.exists()) or any(p.stat().st_mtime > lib_path.stat().st_mtime for p in _SRC)
     if force or stale:
-        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
-        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+        tmp = lib_path.with_suffix(f".tmp{os.getpid()}.so")
+        extra = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"] if sanitize else []
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", *extra,
                                "-o", str(tmp), str(_SRC[0]), "-lm"], cwd=str(_HERE))
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, lib_path)
+    return lib_path
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer runtime, to be preloaded by a process that loads the sanitized checker."""
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 _lib = None
@@ -50,7 +64,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(str(build()))
+        # ORACLE_SANITIZE=1 (set by the sanitizer test for its child process): the instrumented build
+        _lib = C.CDLL(str(build(sanitize=os.environ.get("ORACLE_SANITIZE") == "1")))
         _lib.orc_param_count.restype = C.c_size_t
         _lib.orc_bf16_round.restype = C.c_float
         _lib.orc_bf16_round.argtypes = [C.c_float]
@@ -77,6 +92,11 @@ def _f32(a):
 
 def max_threads() -> int:
     return int(lib().orc_max_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads of the checker's OpenMP loops from now on (the benchmark's single-thread leg)."""
+    lib().orc_set_threads(C.c_int(int(n)))
 
 
 def param_count(w) -> int:

@@ -506,6 +506,15 @@ void orc_update_vanilla(const orc_config *cfg, const float *noise, const float *
   free(g);
 }
 
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+  extern void omp_set_num_threads(int);
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 int orc_max_threads(void) {
 #ifdef _OPENMP
   extern int omp_get_max_threads(void);

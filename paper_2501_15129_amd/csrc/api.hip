@@ -180,6 +180,9 @@ const char* es_update_kernel(const es_ctx* ctx) {
   return ctx->upd_chunks == 1 ? "update_single_pass_kernel" : "grad_partial_kernel+adam_kernel";
 }
 
+// the kernels read parameters, noise rows and environment matrices with 16-byte vector loads
+static bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
 int es_set_obs_norm(es_ctx* ctx, const float* mean_d, const float* inv_std_d) {
   if (!ctx) return ES_EINVAL;
   if ((mean_d == nullptr) != (inv_std_d == nullptr))
@@ -193,6 +196,7 @@ int es_build_noise_table(es_ctx* ctx, void* noise_d, void* stream) {
   if (!ctx) return ES_EINVAL;
   if (ctx->cfg.noise_dtype < 4) return fail(ctx, ES_EINVAL, "es_build_noise_table: this context does not use a noise table");
   if (!noise_d) return fail(ctx, ES_EINVAL, "es_build_noise_table: noise_d is null");
+  if (misaligned16(noise_d)) return fail(ctx, ES_EINVAL, "es_build_noise_table: noise_d must be 16-byte aligned");
   return launch_table(ctx, noise_d, static_cast<hipStream_t>(stream));
 }
 
@@ -203,6 +207,7 @@ static bool regenerated(const es_ctx* ctx) { return ctx->cfg.noise_dtype == 2 ||
 static int check_sample(es_ctx* ctx, uint64_t generation, const void* noise_d) {
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_sample_population: generation must be < 2^32");
   if (!regenerated(ctx) && !noise_d) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d is null");
+  if (misaligned16(noise_d)) return fail(ctx, ES_EINVAL, "es_sample_population: noise_d must be 16-byte aligned");
   return ES_OK;
 }
 
@@ -212,6 +217,8 @@ static int check_rollout(es_ctx* ctx, uint64_t generation, const float* theta_d,
   if (!theta_d || !A_d || !B_d || !returns_d || !ep_len_d || !fitness_d || !workspace_d || (!noise_d && !regenerated(ctx)))
     return fail(ctx, ES_EINVAL, "es_rollout: null device pointer");
   if (generation >> 32) return fail(ctx, ES_EINVAL, "es_rollout: generation must be < 2^32");
+  if (misaligned16(theta_d) || misaligned16(noise_d) || misaligned16(A_d) || misaligned16(B_d) || misaligned16(workspace_d))
+    return fail(ctx, ES_EINVAL, "es_rollout: theta_d, noise_d, A_d, B_d and workspace_d must be 16-byte aligned");
   if (ctx->rollout_kind == ROLLOUT_WAVE_LDS && ctx->lds_bytes_wave > (size_t)ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: perturbed parameters of one individual (" +
                                           std::to_string(ctx->lds_bytes_wave) + " B) exceed the LDS of a workgroup (" +
@@ -229,6 +236,8 @@ static int check_update(es_ctx* ctx, uint64_t adam_step, const void* noise_d, co
   if (!shaped_d || !theta_d || !workspace_d || (!noise_d && !regenerated(ctx)) ||
       ((!m_d || !v_d) && ctx->cfg.algorithm == ES_OPENES))
     return fail(ctx, ES_EINVAL, "es_update: null device pointer");
+  if (misaligned16(noise_d) || misaligned16(workspace_d))
+    return fail(ctx, ES_EINVAL, "es_update: noise_d and workspace_d must be 16-byte aligned");
   if (regenerated(ctx) && !sampled)
     return fail(ctx, ES_EINVAL, "es_update: with regenerated noise, es_sample_population must name the generation first");
   if (adam_step < 1 && ctx->cfg.algorithm == ES_OPENES) return fail(ctx, ES_EINVAL, "es_update: adam_step is 1-based");

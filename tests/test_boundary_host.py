@@ -97,6 +97,25 @@ def test_hot_calls_reject_bad_arguments_before_launch(binding):
     assert b"ES_OK" in lib.es_strerror(0)
 
 
+def test_hot_calls_reject_misaligned_vector_operands(binding):
+    """theta_d, noise_d, A_d, B_d, workspace_d are read with 16-byte loads: a 4-byte-aligned sub-view is refused."""
+    lib = binding.raw_library()
+    ctx = binding.EsContext(CONFIGS[0])
+    h = ctx._h
+    ok, off = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    args = [ok] * 8          # theta, noise, A, B, returns, ep_len, fitness, workspace
+    for k in (0, 1, 2, 3, 7):
+        bad = list(args)
+        bad[k] = off
+        assert lib.es_rollout(h, 0, *bad, None) == binding.ES_EINVAL, k
+        assert b"16-byte aligned" in lib.es_last_error(h)
+    assert lib.es_sample_population(h, 0, off, None) == binding.ES_EINVAL
+    assert lib.es_update(h, 1, off, ok, ok, ok, ok, None, ok, None) == binding.ES_EINVAL
+    assert lib.es_update(h, 1, ok, ok, ok, ok, ok, None, off, None) == binding.ES_EINVAL
+    # returns / ep_len / fitness only need the alignment of their element type
+    assert b"16-byte aligned" in lib.es_last_error(h)
+
+
 def test_binding_rejects_non_device_tensors(binding):
     import torch
     ctx = binding.EsContext(CONFIGS[0])

@@ -33,7 +33,7 @@ def _rank_gpu(es, w, f):
 
 
 @pytest.mark.parametrize("n,b,ties", [(2, 1, False), (4, 1, False), (128, 16, False), (128, 64, True), (130, 7, True),
-                                      (2048, 100, True), (8192, 4096, False), (8192, 1, True)])
+                                      (512, 31, True), (514, 7, True), (2048, 100, True), (4096, 512, True), (8192, 4096, False), (8192, 1, True)])
 def test_rank_ars(es, n, b, ties):
     w = Workload("ars-rank", pop=n, envs=1, horizon=1, obs=3, hid=4, act=2, dtype=0, noise_dtype=0, seed=1,
                  algorithm=ARS, num_elites=b)
@@ -53,7 +53,7 @@ def test_rank_ars_constant_fitness_gives_zero_weights(es):
 
 
 @pytest.mark.parametrize("n,mu,ties", [(1, 1, False), (3, 2, False), (128, 16, False), (128, 128, True), (131, 1, True),
-                                       (2049, 1500, True), (8192, 16, True)])
+                                       (512, 64, True), (513, 100, True), (2049, 1500, True), (8192, 16, True)])
 def test_rank_vanilla(es, n, mu, ties):
     w = Workload("van-rank", pop=n, envs=1, horizon=1, obs=3, hid=4, act=2, dtype=0, noise_dtype=0, seed=1,
                  antithetic=0, algorithm=VANILLA, num_elites=mu)

@@ -49,6 +49,20 @@ def test_sample_population_bit_exact(es, w, gen):
     assert np.all(got[:, d:] == 0.0)
 
 
+def test_sample_population_more_rows_than_a_grid_dimension(es):
+    """70 000 noise rows (more than the 65 535 workgroups one grid dimension holds): first, last and the rows
+    around the limit against the checker."""
+    w = Workload("many-rows", pop=140000, envs=1, horizon=1, obs=2, hid=3, act=1, dtype=0, noise_dtype=1, seed=31)
+    ctx, noise = _sample(es, w, gen=4)
+    for j in (0, 65534, 65535, 65536, 69999):
+        want = oracle.sample_population(w, 4, rows=(j, j + 1))[0]
+        got = noise[j].float().cpu().numpy()
+        assert np.array_equal(got[: w.n_params].view(np.uint32), want.view(np.uint32)), j
+        assert np.all(got[w.n_params:] == 0.0)
+    del noise
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("idx", [3, 4])
 def test_sample_population_full_size_sampled_rows(es, idx):
     """configs[3] (512 x 75264 bf16) and configs[4] (2048 x 133120 bf16) at full size: rows against the checker
