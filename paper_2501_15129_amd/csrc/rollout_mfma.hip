@@ -43,7 +43,16 @@ struct MfmaArgs {
   uint32_t gen, k0, k1;
   uint32_t antithetic, out_tanh, noise_mode;
   float sigma, done_thresh, act_cost;
+  unsigned long long* prof;     // phase-timing build only (ES_PHASE_PROF): cycle totals per wavefront and phase
 };
+
+// Phase timing for tuning (compiled in with -DES_PHASE_PROF only): shader-clock cycles between consecutive stamps,
+// summed over all steps of the individuals of workgroup 0, one row of 16 slots per wavefront.
+#ifdef ES_PHASE_PROF
+#define PSTAMP(k) do { const unsigned long long now_ = __builtin_readcyclecounter(); prof_acc[k] += now_ - prof_last; prof_last = now_; } while (0)
+#else
+#define PSTAMP(k) do {} while (0)
+#endif
 
 constexpr int NHP = 256;          // padded hidden width handled by this kernel
 constexpr int KT_H = NHP / 32;    // 32-deep K tiles over the hidden width
@@ -108,7 +117,12 @@ struct Variant {
   static constexpr int OFF_X0P = OFF_XP + 2 * NC * PX;
   static constexpr int OFF_MU = OFF_X0P + 2 * NC * PX;
   static constexpr int OFF_IV = OFF_MU + 4 * NOP;
-  static constexpr int LDS_BYTES = OFF_IV + 4 * NOP;
+  // passes of four copies with the action layer split along K (FUSE3): the second state buffer (steps alternate)
+  // and the binary32 partial sums of the action layer [wavefront][copy][32 action rows]
+  static constexpr bool FUSE3 = NC_ == 4 && ME_ == 0 && NW_ == 4;
+  static constexpr int OFF_X1 = OFF_IV + 4 * NOP;
+  static constexpr int OFF_P3 = OFF_X1 + (FUSE3 ? 2 * NC * PX : 0);
+  static constexpr int LDS_BYTES = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : 0);
   static_assert(ENV_ROWS >= NOP, "the wavefronts must cover the padded state");
   static_assert(ENV_ROWS <= 256, "staging window rows");
   static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
@@ -185,6 +199,10 @@ __device__ __forceinline__ unsigned umax(unsigned a, unsigned b) { return a > b 
 template <int CTRL>
 __device__ __forceinline__ float dpp_shl(float v) {   // lane i <- lane i + n within the row, 0 past the end
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_shl_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 __device__ __forceinline__ float row_bank_sum(float v) {
   v = v + dpp_shl<0x104>(v);
@@ -437,6 +455,22 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         }
       }
 
+      // FUSE3: this wavefront's K slice (its own 64 hidden units) of the action-layer weights, as MFMA A operands.  The K
+      // order inside a tile follows the order in which the lane holds h2 after the layer-2 epilogue: slots 0..3 = units
+      // 4g..4g+3 of the even 16-unit tile, slots 4..7 = the same rows of the odd tile (any K order is as good as another
+      // as long as both operands agree), so h2 goes from the epilogue's registers into the MFMA with no exchange.
+      bf16x8 W3k[V::FUSE3 ? MT3 : 1][2];
+      if constexpr (V::FUSE3) {
+#pragma unroll
+        for (int mt = 0; mt < MT3; ++mt)
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            const unsigned char* src = lds + V::OFF_W3 + 2 * ((16 * mt + n) * PH + 64 * w + 32 * kk + 4 * g);
+            const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 2 * 16);
+            W3k[mt][kk] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
+          }
+      }
+
       float fit_sum = 0.0f;
       for (uint32_t cb = 0; cb < nblk; ++cb) {
         // ---------------- initial states of this block of environment copies ----------------
@@ -503,6 +537,208 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         float ss_cur = 0.0f;      // |s_{t-1}|^2 while step t starts; the reward of step t-1 is booked in step t
         bool first = true;
 
+#ifdef ES_PHASE_PROF
+        unsigned long long prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        unsigned long long prof_last = __builtin_readcyclecounter();
+#endif
+        if constexpr (V::FUSE3) {
+        // Passes of four copies, two hidden layers (FUSE3): the action layer is split along K.  Every wavefront multiplies
+        // the 64 units of h2 it has just produced - still in its registers - with its slice of the action-layer weights;
+        // only the binary32 partial sums [wavefront][copy][action row] cross the LDS, and every wavefront adds them in the
+        // same order.  h2 itself is never exchanged: three workgroup barriers per step instead of four, and no phase in
+        // which two wavefronts wait for the other two.  The state has two buffers (steps alternate) so that a wavefront
+        // may still read s_t while another already writes s_{t+1}; the books of the previous step ride under the layer-1 stream.
+        float* p3s = reinterpret_cast<float*>(lds + V::OFF_P3);
+        const int qq = q & 1;                                  // this lane adds up action rows 8g + 4qq .. + 3 of column col
+        const bool arow_ok = 8 * g + 4 * qq < 16 * MT3;        // rows past the padded action width stay exactly zero
+        for (uint32_t t = 0; t <= a.T; ++t) {
+          const int off_x = (t & 1u) ? V::OFF_X1 : V::OFF_X, off_xn = (t & 1u) ? V::OFF_X : V::OFF_X1;
+          // ---- phase A: h1 = act(W1 x + b1); books of the previous step; first half of A x under the epilogue ----
+          const f32x4 sp4 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col);
+          const u32x4 mp4 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col);
+          bf16x8 bx[KA1 > 0 ? KA1 : 1], bxr[3];
+          auto xload = [&](int kt) { return lds_tile(lds, off_x + 2 * (col * PX + 32 * kt + 8 * g)); };
+          auto xfetch = [&](int kt) {
+            if (NORM) {
+              bxr[kt % 3] = lds_tile(lds, V::OFF_XP + 2 * (col * PX + 32 * kt + 8 * g));
+              if (kt < KA1) bx[kt < KA1 ? kt : 0] = xload(kt);
+            } else if (kt < KA1) {
+              bx[kt < KA1 ? kt : 0] = xload(kt);
+            } else {
+              bxr[kt % 3] = xload(kt);
+            }
+          };
+#pragma unroll
+          for (int kt = 0; kt < 2 && kt < KT1; ++kt) xfetch(kt);
+          __builtin_amdgcn_sched_barrier(0);
+          constexpr int KT_BOOKS = KT1 > 2 ? 2 : KT1 - 1;      // the stage after which the books are done (their inputs have arrived by then)
+#pragma unroll
+          for (int kt = 0; kt < KT1; ++kt) {
+            if (kt + 2 < KT1) xfetch(kt + 2);
+#pragma unroll
+            for (int tt = 0; tt < MT_H; ++tt) {
+              if (V::OCC == 1) pin_agpr(W1r[tt][kt]);
+              acc[tt] = mfma16(W1r[tt][kt], (!NORM && kt < KA1) ? bx[kt < KA1 ? kt : 0] : bxr[kt % 3], acc[tt]);
+            }
+            if (kt == KT_BOOKS) {
+              // every lane combines the four wavefronts' partials of its column in the same fixed order; branch-free, so that
+              // the vector work issues between the matrix-core instructions
+              const float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
+              const float mx = __builtin_bit_cast(float, umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w)));
+              const bool book = !first, add = book && alive;
+              const float r = __fmaf_rn(-ss_cur, inv_no, 1.0f) - a.act_cost * aa_prev;
+              Rn += add ? r : 0.0f;
+              Ln += add ? 1 : 0;
+              alive = alive && !(book && mx > a.done_thresh);
+              ss_cur = ss_new;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          first = false;
+          PSTAMP(0);
+          if (t == a.T || __ballot(alive) == 0ull) break;       // identical in all four wavefronts
+          PSTAMP(1);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int tt = 0; tt < MTE; ++tt) accE[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kt = 0; kt < KA1; ++kt) {
+#pragma unroll
+            for (int tt = 0; tt < MTE; ++tt)
+              if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
+                if (kt < KTAR) accE[tt] = mfma16(Ar[tt][kt], bx[kt], accE[tt]);
+                else accE[tt] = mfma16(lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (kt - KTAR) + 8 * g)), bx[kt], accE[tt]);
+              }
+          }
+          {
+            const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
+            if (q < MT_H)
+              *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+          }
+#pragma unroll
+          for (int r = 0; r < KA1 * MTE; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          }
+          PSTAMP(2);
+          // ---- phase B: h2 = act(W2 h1 + b2) with the second half of A x in the same stream; then this wavefront's K slice of W3 h2 ----
+#pragma unroll
+          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
+          __syncthreads();
+          PSTAMP(3);
+          {
+            constexpr int NT2 = (KT1 - KA1) * MTE;      // MFMAs of the second half of A x; j = (kt - KA1) * MTE + tt
+            constexpr int PS = (NT2 + KT_H - 1) / KT_H; // ... of which this many ride in each stage of the W2 stream
+            bf16x8 bh[3], at[3 * (PS > 0 ? PS : 1)], bx2[KT1 - KA1 > 0 ? KT1 - KA1 : 1];
+            auto fetch = [&](int kt) {
+              bh[kt % 3] = lds_tile(lds, V::OFF_H1 + 2 * (col * PH + 32 * kt + 8 * g));
+#pragma unroll
+              for (int r = 0; r < PS; ++r) {
+                const int j = kt * PS + r;
+                if (j < NT2) {
+                  const int ka = KA1 + j / MTE, tt = j % MTE;
+                  if (ka >= KTAR) at[(kt % 3) * PS + r] = lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (ka - KTAR) + 8 * g));
+                  if (tt == 0 || r == 0) bx2[ka - KA1] = lds_tile(lds, off_x + 2 * (col * PX + 32 * ka + 8 * g));
+                }
+              }
+            };
+            fetch(0);
+            fetch(1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kt = 0; kt < KT_H; ++kt) {
+              if (kt + 2 < KT_H) fetch(kt + 2);
+#pragma unroll
+              for (int tt = 0; tt < MT_H; ++tt) { pin_agpr(W2r[tt][kt]); acc[tt] = mfma16(W2r[tt][kt], bh[kt % 3], acc[tt]); }
+#pragma unroll
+              for (int r = 0; r < PS; ++r) {
+                const int j = kt * PS + r;
+                if (j < NT2) {
+                  const int ka = KA1 + j / MTE, tt = j % MTE;
+                  if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) {
+                    if (ka < KTAR) accE[tt] = mfma16(Ar[tt][ka < KTAR ? ka : 0], bx2[ka - KA1], accE[tt]);
+                    else accE[tt] = mfma16(at[(kt % 3) * PS + r], bx2[ka - KA1], accE[tt]);
+                  }
+                }
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+          PSTAMP(4);
+          {
+            // h2 of this wavefront's 64 units stays in registers: lane (g, 4q + c) holds units 4g..4g+3 of tile q for copy c
+            const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
+            const u32x2 hp = pack_bf16x4(h.x, h.y, h.z, h.w);
+            // the lanes of the four real columns (n < 4) collect the other three tiles of their copy from the lanes to their right
+            const uint32_t s4x = dpp_shl_u<0x104>(hp.x), s4y = dpp_shl_u<0x104>(hp.y);
+            const uint32_t s8x = dpp_shl_u<0x108>(hp.x), s8y = dpp_shl_u<0x108>(hp.y);
+            const uint32_t scx = dpp_shl_u<0x10C>(hp.x), scy = dpp_shl_u<0x10C>(hp.y);
+            const bf16x8 bk0 = __builtin_bit_cast(bf16x8, u32x4{hp.x, hp.y, s4x, s4y});     // K tile of the wavefront's tiles 0, 1
+            const bf16x8 bk1 = __builtin_bit_cast(bf16x8, u32x4{s8x, s8y, scx, scy});       // ... and of tiles 2, 3
+#pragma unroll
+            for (int mt = 0; mt < MT3; ++mt) {
+              f32x4 p3 = mfma16(W3k[mt][0], bk0, f32x4{0.f, 0.f, 0.f, 0.f});
+              p3 = mfma16(W3k[mt][1], bk1, p3);
+              if (n < NC) *reinterpret_cast<f32x4*>(p3s + (w * NC + n) * 32 + 16 * mt + 4 * g) = p3;
+            }
+          }
+#pragma unroll
+          for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
+          PSTAMP(5);
+          __syncthreads();
+          PSTAMP(6);
+          // ---- phase D: a = tanh(sum of the partials + b3); s' = tanh(A x + B a); norms for the reward and the termination test ----
+          bf16x8 ba;
+          {
+            f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (arow_ok) {
+              const int r0 = 8 * g + 4 * qq;
+              v = *reinterpret_cast<const f32x4*>(b3s + r0);
+#pragma unroll
+              for (int ww = 0; ww < NW; ++ww) v += *reinterpret_cast<const f32x4*>(p3s + (ww * NC + col) * 32 + r0);
+              if (a.out_tanh) v = tanh4(v);
+            }
+            float part = v.x * v.x;
+            part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+            part = part + dpp_shl<0x104>(part);          // rows 8g..8g+7 of the column (lanes n < 12; the books read lanes n < 4)
+            aa_prev = rows_sum(part);                    // |a_t|^2 of column col
+            const u32x2 ap = pack_bf16x4(v.x, v.y, v.z, v.w);
+            const uint32_t a4x = dpp_shl_u<0x104>(ap.x), a4y = dpp_shl_u<0x104>(ap.y);
+            ba = __builtin_bit_cast(bf16x8, u32x4{ap.x, ap.y, a4x, a4y});      // action rows 8g..8g+7 of column n (n < 4)
+          }
+#pragma unroll
+          for (int tt = 0; tt < MTE; ++tt) accE[tt] = mfma16(Br[tt][0], ba, accE[tt]);
+          PSTAMP(7);
+          float ssp = 0.0f;
+          unsigned mxp = 0u;
+          {
+            const int tile = w * MTE + q;
+            const bool valid = q < MTE && (ENV_ALL || 16 * tile < V::NOP);
+            const f32x4 sn = tanh4(compact4<MTE>(accE));
+            if (valid) {
+              ssp = sn.x * sn.x;
+              ssp = __fmaf_rn(sn.y, sn.y, ssp); ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
+              mxp = umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w)));
+              *reinterpret_cast<u32x2*>(lds + off_xn + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
+              if (NORM) {
+                const f32x4 xn = (sn - *reinterpret_cast<const f32x4*>(mus + 16 * tile + 4 * g)) * *reinterpret_cast<const f32x4*>(ivs + 16 * tile + 4 * g);
+                *reinterpret_cast<u32x2*>(lds + V::OFF_XP + 2 * (col * PX + 16 * tile + 4 * g)) = pack_bf16x4(xn.x, xn.y, xn.z, xn.w);
+              }
+            }
+            ssp = row_bank_sum(ssp);
+            mxp = row_bank_umax(mxp);
+          }
+          ssp = rows_sum(ssp);
+          mxp = rows_umax(mxp);
+          if (g == 0 && n < NC) {
+            reinterpret_cast<float*>(lds + V::OFF_SSP)[col * NW + w] = ssp;
+            reinterpret_cast<unsigned*>(lds + V::OFF_MXP)[col * NW + w] = mxp;
+          }
+          PSTAMP(9);
+          __syncthreads();
+          PSTAMP(10);
+        }
+        } else {
         for (uint32_t t = 0; t <= a.T; ++t) {
           // ---- phase A: h1 = tanh(W1 x + b1); first half of A x; books of the previous step ----
           // partial norms of the previous step, one per wavefront (consumed after the MFMA stream below)
@@ -538,6 +774,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             }
             __builtin_amdgcn_sched_barrier(0);
           }
+          PSTAMP(0);
           // every lane combines the four wavefronts' partials of its column in the same fixed order
           float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
           unsigned mxb = umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w));
@@ -557,6 +794,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           first = false;
           ss_cur = ss_new;
           if (t == a.T || __ballot(alive) == 0ull) break;       // identical in all four wavefronts
+          PSTAMP(1);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int tt = 0; tt < MTE; ++tt) accE[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -587,10 +825,12 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x002, NC == 4 ? 4 : 8, 0);
           }
           // ---- phase B: h2 = tanh(W2 h1 + b2); second half of A x ----
+          PSTAMP(2);
           if constexpr (ME >= 0) {
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
             __syncthreads();
+            PSTAMP(3);
             constexpr int NT2 = (KT1 - KA1) * MTE;      // MFMAs of the second half of A x; j = (kt - KA1) * MTE + tt
             constexpr int PS = (NT2 + KT_H - 1) / KT_H; // ... of which this many ride in each stage of the W2 stream
             bf16x8 bh[3], at[3 * (PS > 0 ? PS : 1)], bx2[KT1 - KA1 > 0 ? KT1 - KA1 : 1];
@@ -628,6 +868,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               }
               __builtin_amdgcn_sched_barrier(0);
             }
+            PSTAMP(4);
             if (NC == 4) {
               const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
               if (q < MT_H)
@@ -682,7 +923,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             for (int kt = 0; kt < W3PRE; ++kt) w3t[kt] = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
             p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
           }
+          PSTAMP(5);
           __syncthreads();
+          PSTAMP(6);
           // ---- phase C: a = tanh(W3 h2 + b3), weights from LDS ----
           unsigned char* qaw = lds + V::OFF_QA + (V::ACT_SPLIT ? 0 : w * (2 * NC * PA));   // action buffer read below
           if (V::ACT_SPLIT) {
@@ -705,7 +948,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
                 if (g == 0) reinterpret_cast<float*>(lds + V::OFF_AAP)[col * 2 + w] = part;
               }
             }
+            PSTAMP(7);
             __syncthreads();
+            PSTAMP(8);
           } else {
             // every wavefront computes the single action tile itself: no exchange before the environment step
             f32x4 p[MT3][2];
@@ -792,8 +1037,15 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           }
 #pragma unroll
           for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 16 * (w * MT_H + tt) + 4 * g);
+          PSTAMP(9);
           __syncthreads();
+          PSTAMP(10);
         }
+        }
+#ifdef ES_PHASE_PROF
+        if (blockIdx.x == 0 && lane == 0 && a.prof)
+          for (int k = 0; k < 12; ++k) a.prof[w * 16 + k] += prof_acc[k];
+#endif
         __syncthreads();   // all reads of the rollout buffers are done before anything is restaged
 
         // ---------------- outputs of this block of environment copies ----------------
@@ -866,7 +1118,7 @@ static int launch_variant(es_ctx* ctx, const MfmaArgs& a, uint32_t units, hipStr
 }
 
 int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,
-                        const float* B, float* returns, int32_t* ep_len, float* fitness, void* /*ws*/,
+                        const float* B, float* returns, int32_t* ep_len, float* fitness, void* ws,
                         hipStream_t st) {
   const Shape& s = ctx->shp;
   const es_config& c = ctx->cfg;
@@ -878,10 +1130,18 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
+  a.prof = static_cast<unsigned long long*>(ws);
   if ((int)V256<16, 4>::LDS_BYTES > ctx->lds_limit)
     return fail(ctx, ES_EUNSUPPORTED, "es_rollout: this device's LDS is too small for the register-resident kernel");
   const uint32_t units = s.N;      // one work item per individual
   const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
+#ifdef ES_DEV_FAST   // tuning builds only: one variant, seconds to compile
+  if (ctx->mfma_variant == 3 && narrow && s.m == 2 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
+    return launch_variant_act<V256<4, 4>, false, false>(ctx, a, units, st);
+  if (ctx->mfma_variant == 0 && !narrow && s.m == 2 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
+    return launch_variant_act<V32<16, 4>, false, false>(ctx, a, units, st);
+  return fail(ctx, ES_EUNSUPPORTED, "tuning build: variant not compiled");
+#else
   if (s.m == 1) {
     if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32S<4, 4>>(ctx, a, units, st) : launch_variant<V32S<16, 4>>(ctx, a, units, st);
     if (ctx->mfma_variant == 1) return narrow ? launch_variant<V64S<4, 4>>(ctx, a, units, st) : launch_variant<V64S<16, 4>>(ctx, a, units, st);
@@ -900,6 +1160,7 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
     case 3: return narrow ? launch_variant<V256<4, 4>>(ctx, a, units, st) : launch_variant<V256<16, 4>>(ctx, a, units, st);
     default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident variant for this shape");
   }
+#endif
 }
 
 }  // namespace es
