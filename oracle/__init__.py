@@ -29,7 +29,7 @@ class OrcConfig(C.Structure):
         ("adam_eps", C.c_float), ("weight_decay", C.c_float),
         ("done_thresh", C.c_float), ("act_cost", C.c_float),
         ("seed", C.c_uint64),
-        ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32), ("episodes", C.c_uint32),
+        ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32), ("episodes", C.c_uint32), ("env_dtype", C.c_uint32),
     ]
 
 
@@ -77,7 +77,7 @@ def config(w) -> OrcConfig:
     """Build the checker's config from a workload description (any object with these fields)."""
     c = OrcConfig()
     for name, _ in OrcConfig._fields_:
-        setattr(c, name, getattr(w, name, 0) if name in ("hidden_act", "num_hidden", "episodes") else getattr(w, name))
+        setattr(c, name, getattr(w, name, 0) if name in ("hidden_act", "num_hidden", "episodes", "env_dtype") else getattr(w, name))
     return c
 
 

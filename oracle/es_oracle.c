@@ -57,6 +57,10 @@ typedef struct orc_config {
   uint32_t num_hidden;   /* m hidden layers of width hid (paper Sec. 5.1 varies m; the base case is 2); 0 means 2 */
   uint32_t episodes;     /* episodes run one after the other in every environment copy, the environment resetting
                             itself in between (paper Sec. 3.1: the auto-reset wrapper); 0 means 1 */
+  uint32_t env_dtype;    /* only with dtype = 1.  0: the environment's products use bf16 operands too (A, B, the state and
+                            the action as operands of A s + B a are rounded to bf16); 1: the environment stays in
+                            binary32 - only the POLICY has "bf16 weights and activations", the simulator it acts on
+                            is not part of the policy's precision */
 } orc_config;
 
 enum { STREAM_NOISE = 1, STREAM_RESET = 2, STREAM_TABLE = 3, STREAM_OFFSET = 4 };
@@ -266,6 +270,11 @@ void orc_reset(const orc_config *cfg, uint64_t gen, uint32_t e, float *s0) {
 static double q_operand(const orc_config *cfg, double x) {
   return cfg->dtype == 1 ? (double)orc_bf16_round((float)x) : x;
 }
+/* ... an operand of the ENVIRONMENT's products A s + B a: rounded like the policy's unless env_dtype keeps it binary32 */
+static int env_rounds(const orc_config *cfg) { return cfg->dtype == 1 && cfg->env_dtype == 0; }
+static double q_env_operand(const orc_config *cfg, double x) {
+  return env_rounds(cfg) ? (double)orc_bf16_round((float)x) : x;
+}
 
 #define REAL double
 #define REAL_TANH tanh
@@ -308,8 +317,8 @@ void orc_rollout_norm(const orc_config *cfg, uint64_t gen, const float *theta, c
   /* environment matrices as the rollout sees them */
   float *Ae = (float *)malloc(sizeof(float) * no * no);
   float *Be = (float *)malloc(sizeof(float) * no * na);
-  for (uint32_t k = 0; k < no * no; ++k) Ae[k] = cfg->dtype == 1 ? orc_bf16_round(A[k]) : A[k];
-  for (uint32_t k = 0; k < no * na; ++k) Be[k] = cfg->dtype == 1 ? orc_bf16_round(B[k]) : B[k];
+  for (uint32_t k = 0; k < no * no; ++k) Ae[k] = env_rounds(cfg) ? orc_bf16_round(A[k]) : A[k];
+  for (uint32_t k = 0; k < no * na; ++k) Be[k] = env_rounds(cfg) ? orc_bf16_round(B[k]) : B[k];
 #pragma omp parallel for schedule(dynamic, 1)
   for (uint32_t i = i0; i < i1; ++i) {
     float *theta_i = (float *)malloc(sizeof(float) * D);

@@ -48,6 +48,7 @@ class Workload:
     num_hidden: int = 2 # m hidden layers of width hid (paper Sec. 5.1 varies m; base case 2)
     noise_table_len: int = 0  # entries of the shared noise table (noise_dtype 4, 5; paper Sec. 5.1)
     episodes: int = 1   # episodes run back to back in every environment copy (auto-reset; paper Sec. 3.1)
+    env_dtype: int = 0  # with dtype 1: 0 = the environment's products use bf16 operands too ; 1 = the environment stays binary32
     # input recipe only (seen by make_inputs, not by the library or the checker):
     a_radius: float = 0.9       # spectral radius the environment matrix A is rescaled to
     b_var: float = 1.0 / 3.0    # variance of the entries of B

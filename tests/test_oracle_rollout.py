@@ -178,9 +178,12 @@ def test_two_individual_enumeration_pure_python(hidden_act):
 
 
 @pytest.mark.parametrize("hidden_act", [0, 1])
-def test_bf16_mode_one_step_against_library_rounding(hidden_act):
+@pytest.mark.parametrize("env_dtype", [0, 1])
+def test_bf16_mode_one_step_against_library_rounding(hidden_act, env_dtype):
+    """bf16 mode with the library's own rounding at every operand; env_dtype = 1 keeps the environment's
+    products (A, B, the state and the action as their operands) in binary32 while the policy still rounds."""
     hid = (lambda z: np.maximum(z, 0.0)) if hidden_act else np.tanh
-    w = replace(W, dtype=1, noise_dtype=1, horizon=2, done_thresh=math.inf, hidden_act=hidden_act)
+    w = replace(W, dtype=1, noise_dtype=1, horizon=3, done_thresh=math.inf, hidden_act=hidden_act, env_dtype=env_dtype)
     a_mat, b_mat, theta = make_inputs(w)
     eps = oracle.sample_population(w, 0)
     ret, _, _, _ = oracle.rollout(w, 0, theta, eps, a_mat, b_mat)
@@ -188,7 +191,10 @@ def test_bf16_mode_one_step_against_library_rounding(hidden_act):
     def q(x):   # value -> binary32 -> bf16, by the library's own conversion
         return torch.from_numpy(np.asarray(x, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
 
-    aq, bq = q(a_mat), q(b_mat)
+    qe = q if env_dtype == 0 else (lambda x: np.asarray(x, dtype=np.float64))      # the environment's operands
+    aq, bq = qe(a_mat), qe(b_mat)
+    other = oracle.rollout(replace(w, env_dtype=1 - env_dtype), 0, theta, eps, a_mat, b_mat)[0]
+    assert not np.array_equal(other, ret)           # the switch does change the arithmetic
     for i in (0, 5):
         th = oracle.perturb(w, theta, eps, i)          # already bf16 values
         assert np.array_equal(th, q(th).astype(np.float32))
@@ -202,7 +208,7 @@ def test_bf16_mode_one_step_against_library_rounding(hidden_act):
                 h2 = q(hid(w2 @ h1 + b2))
                 act = np.tanh(w3 @ h2 + b3)
                 total += 1.0 - np.dot(s, s) / w.obs - float(np.float32(w.act_cost)) * np.dot(act, act)
-                s = np.tanh(aq @ x + bq @ q(act))
+                s = np.tanh(aq @ qe(s) + bq @ qe(act))
             assert abs(ret[i, e] - total) < 1e-6
 
 
