@@ -189,6 +189,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-full", action="store_true",
                     help="run the CPU checker once over the WHOLE population instead of a bounded sample (about two minutes at configs[4])")
+    ap.add_argument("--env-f32", action="store_true",
+                    help="bf16 workloads: keep the environment's products A s + B a in binary32 (env_dtype = 1; obs <= 64)")
     ap.add_argument("--no-antithetic", action="store_true",
                     help="independent noise rows for every individual (antithetic = 0): at configs[4] es_update then streams the literal "
                          "4096 x 132k bf16 matrix, 1.09 GB")
@@ -246,6 +248,8 @@ def main() -> int:
         base = replace(base, name=base.name + "-vanilla", algorithm=2, num_elites=max(1, base.pop // 8), antithetic=0)
     if args.no_antithetic:
         base = replace(base, name=base.name + "-noanti", antithetic=0)
+    if args.env_f32:
+        base = replace(base, name=base.name + "-envf32", env_dtype=1)
     if args.num_hidden != 2:
         base = replace(base, name=base.name + f"-m{args.num_hidden}", num_hidden=args.num_hidden)
     if args.episodes_per_env != 1:
@@ -304,7 +308,7 @@ def main() -> int:
         roofline["frac_of_column_ceiling"] = (ach / peak) / (cols / 16.0)
     plain = (args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm
              and args.episodes_per_env == 1 and args.num_hidden == 2 and not args.paper_base and args.pop is None
-             and not args.no_antithetic)
+             and not args.no_antithetic and not args.env_f32)
     traffic = (measured_traffic(w.name) if plain else None) or {}
     roofline["traffic"] = traffic.get("rollout_bytes_per_launch")
     if traffic:

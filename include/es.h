@@ -107,6 +107,11 @@ typedef struct es_config {
                             The episodes of one copy do not depend on each other, so the kernels run all E
                             side by side (with few copies this also fills matrix-core columns that would
                             otherwise idle) and the results equal the sequential schedule's exactly         */
+  uint32_t env_dtype;    /* only with dtype = 1.  0: the environment's products A s + B a use bf16 operands too
+                            (A, B, the state and the action rounded; configs[4] needs that to hold A on chip).
+                            1: the environment stays binary32 - "bf16 weights and activations" is a property of the
+                            policy, not of the simulator it acts on; built for two hidden layers with obs_dim <= 64
+                            (any width on the LDS kernel if the individual fits), else ES_EUNSUPPORTED from es_rollout */
 } es_config;
 
 /*

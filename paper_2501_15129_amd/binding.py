@@ -29,7 +29,7 @@ class EsConfig(C.Structure):
         ("seed", C.c_uint64),
         ("algorithm", C.c_uint32), ("num_elites", C.c_uint32), ("hidden_act", C.c_uint32), ("num_hidden", C.c_uint32),
         ("noise_table_len", C.c_uint64),
-        ("episodes_per_env", C.c_uint32),
+        ("episodes_per_env", C.c_uint32), ("env_dtype", C.c_uint32),
     ]
 
 
@@ -84,7 +84,7 @@ def make_config(w) -> EsConfig:
                     algorithm=getattr(w, "algorithm", 0), num_elites=getattr(w, "num_elites", 0),
                     hidden_act=getattr(w, "hidden_act", 0), num_hidden=getattr(w, "num_hidden", 2),
                     noise_table_len=getattr(w, "noise_table_len", 0),
-                    episodes_per_env=getattr(w, "episodes", 1))
+                    episodes_per_env=getattr(w, "episodes", 1), env_dtype=getattr(w, "env_dtype", 0))
 
 
 def _stream() -> int:

@@ -84,6 +84,7 @@ int es_create(const es_config* cfg, es_ctx** out) {
   if (c.antithetic > 1 || c.out_tanh > 1) return bad("antithetic and out_tanh must be 0 or 1");
   if (c.antithetic && (c.pop & 1u)) return bad("pop must be even with mirrored sampling");
   if (c.hidden_act > 1) return bad("hidden_act must be 0 (tanh) or 1 (ReLU)");
+  if (c.env_dtype > 1) return bad("env_dtype must be 0 or 1");
   if (c.algorithm > ES_VANILLA) return bad("algorithm must be ES_OPENES, ES_ARS or ES_VANILLA");
   if (c.algorithm == ES_ARS && (!c.antithetic || c.num_elites < 1 || c.num_elites > c.pop / 2))
     return bad("ES_ARS needs mirrored sampling and 1 <= num_elites <= pop / 2");

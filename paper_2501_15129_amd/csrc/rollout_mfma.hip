@@ -65,8 +65,10 @@ constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activ
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
-template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_, int NW_, int OCC_ = 1, int ME_ = 0>
+template <int KT1_, int MT3_, int MTE_, int KTAR_, int NC_, int NW_, int OCC_ = 1, int ME_ = 0, bool ENVF_ = false>
 struct Variant {
+  static constexpr bool ENVF = ENVF_;          // the environment's products A s + B a stay binary32 (fp32 16x16x4 MFMAs, its own
+                                              // binary32 copy of the state in LDS); the policy keeps its bf16 operands
   static constexpr int ME = ME_;              // hidden layers beyond the second (depth m = 2 + ME), each 256 x 256 in registers;
                                               // -1: a single hidden layer (the second layer's phase is skipped)
   static constexpr int OCC = OCC_;            // workgroups per CU the register budget is sized for (1 or 2)
@@ -122,7 +124,14 @@ struct Variant {
   static constexpr bool FUSE3 = NC_ == 4 && ME_ == 0 && NW_ == 4;
   static constexpr int OFF_X1 = OFF_IV + 4 * NOP;
   static constexpr int OFF_P3 = OFF_X1 + (FUSE3 ? 2 * NC * PX : 0);
-  static constexpr int LDS_BYTES = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : 0);
+  // binary32 environment: the state as binary32 [copy][state index] (pitch PXF floats: 16-byte reads of 16 lanes hit
+  // distinct banks), working buffer and cached initial value
+  static constexpr int KPL = NOP / 4;          // state elements per lane group of the fp32 MFMA's K dimension
+  static constexpr int PXF = NOP + 4;
+  static constexpr int OFF_XF = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : 0);
+  static constexpr int OFF_X0F = OFF_XF + (ENVF ? 4 * NC * PXF : 0);
+  static constexpr int LDS_BYTES = OFF_X0F + (ENVF ? 4 * NC * PXF : 0);
+  static_assert(!ENVF || (NC == 16 && ME == 0 && MT3 == 1 && KT1 <= 2), "binary32 environment: passes of 16 copies, two hidden layers, obs <= 64, act <= 16");
   static_assert(ENV_ROWS >= NOP, "the wavefronts must cover the padded state");
   static_assert(ENV_ROWS <= 256, "staging window rows");
   static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
@@ -149,6 +158,11 @@ __device__ __forceinline__ void pin_vgpr(f32x4& v) { asm volatile("" : "+v"(v));
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// binary32 16x16x4: lane (g, n) supplies A[row n][k = g] and B[k = g][column n]
+__device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -341,9 +355,26 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   }
   // ---------------- environment matrices -> registers / LDS (once per workgroup) ----------------
   constexpr int KTAR = V::KTAR, KTAL = V::KTAL, PAL = V::PAL;
+  constexpr bool ENVF = V::ENVF;
+  constexpr int KPL = V::KPL, PXF = V::PXF;
   bf16x8 Ar[MTE][KTAR > 0 ? KTAR : 1], Br[MTE][KTA];
+  // binary32 environment: A and B as fp32 MFMA A operands.  K slot (kk, g) of the state product stands for state
+  // element KPL g + kk (so a lane's KPL operands are contiguous in the binary32 state buffer), K slot (kk, g) of the
+  // action product for action row 4 g + kk (what the lane holds after the action layer): Af[tt][kk] = A[row][KPL g + kk],
+  // Bf[tt][kk] = B[row][4 g + kk], row = 16 (w MTE + tt) + n.
+  float Af[ENVF ? MTE : 1][ENVF ? KPL : 1], Bf[ENVF ? MTE : 1][4];
+  if constexpr (ENVF) {
 #pragma unroll
-  for (int kr = 0; kr < (KTAR + KC - 1) / KC; ++kr) {
+    for (int t = 0; t < MTE; ++t) {
+      const int row = 16 * (w * MTE + t) + n;
+#pragma unroll
+      for (int kk = 0; kk < KPL; ++kk) { const int k = KPL * g + kk; Af[t][kk] = (row < no && k < no) ? a.A[row * no + k] : 0.0f; }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) { const int c = 4 * g + kk; Bf[t][kk] = (row < no && c < na) ? a.B[row * na + c] : 0.0f; }
+    }
+  }
+#pragma unroll
+  for (int kr = 0; kr < (ENVF ? 0 : (KTAR + KC - 1) / KC); ++kr) {
     stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, no, 32 * KC * kr, a.A, NoiseRow{}, 0.0f, 0u);
     __syncthreads();
 #pragma unroll
@@ -357,14 +388,16 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   if (KTAL > 0)
     stage_cols<32 * (KTAL > 0 ? KTAL : 1), false>(reinterpret_cast<uint16_t*>(lds + V::OFF_AL), PAL, V::ENV_ROWS, no, no,
                                                     32 * KTAR, a.A, NoiseRow{}, 0.0f, 0u);
-  stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, na, 0, a.B, NoiseRow{}, 0.0f, 0u);
-  __syncthreads();
+  if constexpr (!ENVF) {
+    stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, na, 0, a.B, NoiseRow{}, 0.0f, 0u);
+    __syncthreads();
 #pragma unroll
-  for (int t = 0; t < MTE; ++t)
+    for (int t = 0; t < MTE; ++t)
 #pragma unroll
-    for (int kt = 0; kt < KTA; ++kt)
-      Br[t][kt] = lds_tile(lds, 2 * ((16 * (w * MTE + t) + n) * PW + 32 * kt + 8 * g));
-  __syncthreads();
+      for (int kt = 0; kt < KTA; ++kt)
+        Br[t][kt] = lds_tile(lds, 2 * ((16 * (w * MTE + t) + n) * PW + 32 * kt + 8 * g));
+    __syncthreads();
+  }
 
   const uint32_t per_unit = a.antithetic ? 2u : 1u;
   const uint32_t nblk = (a.E + (uint32_t)NC - 1u) / (uint32_t)NC;
@@ -485,6 +518,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             if (k < no && e0 < a.E) v = reset_value((uint32_t)k, e0, a.gen, a.k0, a.k1);
             part = __fmaf_rn(v, v, part);
             x0s[n0 * PX + k] = (uint16_t)bf16_bits(v);
+            if (ENVF) reinterpret_cast<float*>(lds + V::OFF_X0F)[n0 * PXF + k] = v;
             if (NORM) x0ps[n0 * PX + k] = (uint16_t)bf16_bits((v - mus[k]) * ivs[k]);
           }
           float* scratch = reinterpret_cast<float*>(lds + V::OFF_SCR);   // KG x NC partial norms
@@ -503,6 +537,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           const uint32_t* src = reinterpret_cast<const uint32_t*>(x0s);
           uint32_t* dst = reinterpret_cast<uint32_t*>(lds + V::OFF_X);
           for (int r = tid; r < NC * PX / 2; r += NT) dst[r] = src[r];
+          if (ENVF) {
+            const float* srcf = reinterpret_cast<const float*>(lds + V::OFF_X0F);
+            float* dstf = reinterpret_cast<float*>(lds + V::OFF_XF);
+            for (int r = tid; r < NC * PXF; r += NT) dstf[r] = srcf[r];
+          }
           if (NORM) {
             const uint32_t* srcp = reinterpret_cast<const uint32_t*>(x0ps);
             uint32_t* dstp = reinterpret_cast<uint32_t*>(lds + V::OFF_XP);
@@ -518,7 +557,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         float Rn = 0.0f;
         int32_t Ln = 0;
         const float inv_no = 1.0f / (float)no;
-        constexpr int KA1 = ME < 0 ? KT1 : (KT1 + 1) / 2;       // K tiles of A x done beside layer 1; the rest beside layer 2
+        constexpr int KA1 = ENVF ? 0 : (ME < 0 ? KT1 : (KT1 + 1) / 2);       // K tiles of A x done beside layer 1; the rest beside layer 2
+        f32x4 av = f32x4{0.f, 0.f, 0.f, 0.f};     // binary32 environment: the action (rows 4g..4g+3 of column n), kept in registers
 
         f32x4 acc[MT_H], accE[MTE];
 #pragma unroll
@@ -747,6 +787,14 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           const f32x4 sp8 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col + (NW > 4 ? 16 : 0));
           const u32x4 mp8 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col + (NW > 4 ? 16 : 0));
           const f32x2 ap2 = *reinterpret_cast<const f32x2*>(lds + V::OFF_AAP + 8 * col);
+          float xf[ENVF ? KPL : 1];                 // binary32 environment: this lane's state operands, elements KPL g .. of column n
+          if constexpr (ENVF) {
+#pragma unroll
+            for (int j = 0; j < KPL / 4; ++j) {
+              const f32x4 v4 = *reinterpret_cast<const f32x4*>(lds + V::OFF_XF + 4 * (n * PXF + KPL * g + 4 * j));
+              xf[4 * j] = v4.x; xf[4 * j + 1] = v4.y; xf[4 * j + 2] = v4.z; xf[4 * j + 3] = v4.w;
+            }
+          }
           // W1 stream: the B operand (state tiles) runs two stages ahead of the MFMAs
           bf16x8 bx[KA1 > 0 ? KA1 : 1], bxr[3];     // tiles < KA1 are kept for A x below; the rest pass through a ring
           auto xload = [&](int kt) { return lds_tile(lds, V::OFF_X + 2 * (col * PX + 32 * kt + 8 * g)); };
@@ -808,6 +856,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
                 else accE[tt] = mfma16(lds_tile(lds, V::OFF_AL + 2 * ((16 * (w * MTE + tt) + n) * PAL + 32 * (kt - KTAR) + 8 * g)), bx[kt], accE[tt]);
               }
           }
+          if constexpr (ENVF) {          // A s in binary32, under the layer-1 epilogue like the bf16 tiles above
+#pragma unroll
+            for (int kk = 0; kk < KPL; ++kk)
+#pragma unroll
+              for (int tt = 0; tt < MTE; ++tt)
+                if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) accE[tt] = mfma4(Af[tt][kk], xf[kk], accE[tt]);
+          }
           if (NC == 4) {
             const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
             if (q < MT_H)
@@ -820,7 +875,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             }
           }
 #pragma unroll
-          for (int r = 0; r < KA1 * MTE; ++r) {
+          for (int r = 0; r < (ENVF ? KPL * MTE : KA1 * MTE); ++r) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, NC == 4 ? 4 : 8, 0);
           }
@@ -831,7 +886,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             for (int tt = 0; tt < MT_H; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 16 * (w * MT_H + tt) + 4 * g);
             __syncthreads();
             PSTAMP(3);
-            constexpr int NT2 = (KT1 - KA1) * MTE;      // MFMAs of the second half of A x; j = (kt - KA1) * MTE + tt
+            constexpr int NT2 = ENVF ? 0 : (KT1 - KA1) * MTE;      // MFMAs of the second half of A x; j = (kt - KA1) * MTE + tt
             constexpr int PS = (NT2 + KT_H - 1) / KT_H; // ... of which this many ride in each stage of the W2 stream
             bf16x8 bh[3], at[3 * (PS > 0 ? PS : 1)], bx2[KT1 - KA1 > 0 ? KT1 - KA1 : 1];
             // operands of stage kt are fetched two stages ahead: h1 tile, LDS-resident A tiles, state tiles
@@ -975,7 +1030,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               if (a.out_tanh) v = tanh4(v);
               part = __fmaf_rn(v.x, v.x, part); part = __fmaf_rn(v.y, v.y, part);
               part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
-              if (n < NC)     // with 4-column passes the lanes of columns 4..15 hold copies
+              if (ENVF) av = v;                // one action tile (asserted): the environment reads it from these registers
+              else if (n < NC)     // with 4-column passes the lanes of columns 4..15 hold copies
                 *reinterpret_cast<u32x2*>(qaw + 2 * (col * PA + 16 * mt + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
             }
             aa_prev = rows_sum(part);      // |a_t|^2 of column `col` (lanes of columns >= NC hold copies)
@@ -1006,12 +1062,20 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             ssp = row_bank_sum(ssp);
             mxp = row_bank_umax(mxp);
           } else {
+            if constexpr (ENVF) {
 #pragma unroll
-            for (int kt = 0; kt < KTA; ++kt) {
-              const bf16x8 b = lds_tile(qaw, 2 * (n * PA + 32 * kt + 8 * g));
+              for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-              for (int tt = 0; tt < MTE; ++tt)
-                if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
+                for (int tt = 0; tt < MTE; ++tt)
+                  if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) accE[tt] = mfma4(Bf[tt][kk], av[kk], accE[tt]);
+            } else {
+#pragma unroll
+              for (int kt = 0; kt < KTA; ++kt) {
+                const bf16x8 b = lds_tile(qaw, 2 * (n * PA + 32 * kt + 8 * g));
+#pragma unroll
+                for (int tt = 0; tt < MTE; ++tt)
+                  if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
+              }
             }
 #pragma unroll
             for (int tt = 0; tt < MTE; ++tt) {
@@ -1021,6 +1085,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
                 ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
                 mxp = umax(mxp, umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w))));
                 *reinterpret_cast<u32x2*>(lds + V::OFF_X + 2 * (n * PX + 16 * (w * MTE + tt) + 4 * g)) = pack_bf16x4(sn.x, sn.y, sn.z, sn.w);
+                if (ENVF) *reinterpret_cast<f32x4*>(lds + V::OFF_XF + 4 * (n * PXF + 16 * (w * MTE + tt) + 4 * g)) = sn;
                 if (NORM) {
                   const int r0 = 16 * (w * MTE + tt) + 4 * g;
                   const f32x4 xn = (sn - *reinterpret_cast<const f32x4*>(mus + r0)) * *reinterpret_cast<const f32x4*>(ivs + r0);
@@ -1068,6 +1133,9 @@ constexpr int env_tiles(int nop, int nw) { return (nop / 16 + nw - 1) / nw > 0 ?
 // individuals) share a CU and hide each other's LDS round trips and barriers (1.5x at obs 27).
 template <int NC, int NW> using V32 = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2>;   // obs <= 32,  act <= 16
 template <int NC, int NW> using V64 = Variant<2, 1, env_tiles(64, NW), 2, NC, NW>;      // obs <= 64,  act <= 16
+// the same two shapes with the environment's products in binary32 (es_config.env_dtype = 1)
+template <int NC, int NW> using V32F = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2, 0, true>;
+template <int NC, int NW> using V64F = Variant<2, 1, env_tiles(64, NW), 2, NC, NW, 1, 0, true>;
 template <int NC, int NW> using V128 = Variant<4, 2, env_tiles(128, NW), 4, NC, NW>;    // obs <= 128, act <= 32
 // Deeper policies (m = 3, 4 hidden layers) of the two narrow-observation shapes: one workgroup per CU, the
 // extra 256 x 256 layers take the registers the second workgroup would have used.
@@ -1089,6 +1157,8 @@ static const VariantInfo kVariants[] = {
 int mfma_variant_for(const es_config& c) {
   const uint32_t m = c.num_hidden ? c.num_hidden : 2;
   if (c.dtype != 1 || c.hid_dim > (uint32_t)NHP || m < 1 || m > 4) return -1;
+  // a binary32 environment is built for the two narrow-observation shapes with two hidden layers
+  if (c.env_dtype == 1 && (m != 2 || c.obs_dim > 64 || c.act_dim > 16)) return -1;
   // narrow policies are served better by the one-wavefront-per-episode kernel when it fits
   if (c.hid_dim < 128 && wave_rollout_lds_bytes(c) <= 160 * 1024) return -1;
   for (int v = 0; v < 4; ++v)
@@ -1136,12 +1206,19 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   const uint32_t units = s.N;      // one work item per individual
   const bool narrow = s.E <= 4;     // passes of 4 environment copies with column compaction
 #ifdef ES_DEV_FAST   // tuning builds only: one variant, seconds to compile
+  if (c.env_dtype == 1 && ctx->mfma_variant == 0 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
+    return launch_variant_act<V32F<16, 4>, false, false>(ctx, a, units, st);
   if (ctx->mfma_variant == 3 && narrow && s.m == 2 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
     return launch_variant_act<V256<4, 4>, false, false>(ctx, a, units, st);
   if (ctx->mfma_variant == 0 && !narrow && s.m == 2 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
     return launch_variant_act<V32<16, 4>, false, false>(ctx, a, units, st);
   return fail(ctx, ES_EUNSUPPORTED, "tuning build: variant not compiled");
 #else
+  if (c.env_dtype == 1) {          // binary32 environment: passes of 16 copies whatever E is
+    if (ctx->mfma_variant == 0) return launch_variant<V32F<16, 4>>(ctx, a, units, st);
+    if (ctx->mfma_variant == 1) return launch_variant<V64F<16, 4>>(ctx, a, units, st);
+    return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident variant with a binary32 environment for this shape");
+  }
   if (s.m == 1) {
     if (ctx->mfma_variant == 0) return narrow ? launch_variant<V32S<4, 4>>(ctx, a, units, st) : launch_variant<V32S<16, 4>>(ctx, a, units, st);
     if (ctx->mfma_variant == 1) return narrow ? launch_variant<V64S<4, 4>>(ctx, a, units, st) : launch_variant<V64S<16, 4>>(ctx, a, units, st);

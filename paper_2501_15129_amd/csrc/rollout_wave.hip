@@ -31,6 +31,7 @@ struct WaveArgs {
   uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
   uint32_t antithetic, out_tanh, noise_mode, hidden_relu;
+  uint32_t env_f32;          // bf16 operands: the environment's products stay binary32 (its matrices then live among the floats)
   float sigma, done_thresh, act_cost;
 };
 
@@ -57,17 +58,25 @@ struct WaveLayout {
   size_t w1, w2, w3, at, bt, wcount;        // matrix offsets (weight elements)
   size_t b1, b2, b3, s, x, xp, mu, iv, h1, h2, a, qa, fcount;   // float offsets
 };
-__host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint32_t na, uint32_t m) {
+// env_floats: the environment matrices are kept as binary32 among the floats (bf16 policy, binary32 environment)
+// instead of among the weight elements.
+__host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint32_t na, uint32_t m, bool env_floats) {
   WaveLayout L;
   L.p_h = odd_pitch(nh); L.p_a = odd_pitch(na); L.p_o = odd_pitch(no);
   size_t o = 0;
   L.w1 = o; o += (size_t)no * L.p_h;
   L.w2 = o; o += (size_t)(m - 1) * nh * L.p_h;        // the m - 1 hidden-to-hidden matrices, one after the other
   L.w3 = o; o += (size_t)nh * L.p_a;
-  L.at = o; o += (size_t)no * L.p_o;
-  L.bt = o; o += (size_t)na * L.p_o;
+  if (!env_floats) {
+    L.at = o; o += (size_t)no * L.p_o;
+    L.bt = o; o += (size_t)na * L.p_o;
+  }
   L.wcount = (o + 1) & ~(size_t)1;
   size_t f = 0;
+  if (env_floats) {
+    L.at = f; f += (size_t)no * L.p_o;
+    L.bt = f; f += (size_t)na * L.p_o;
+  }
   L.b1 = f; f += nh; L.b2 = f; f += (size_t)(m - 1) * nh; L.b3 = f; f += na;
   L.s = f; f += no; L.x = f; f += no; L.xp = f; f += no; L.mu = f; f += no; L.iv = f; f += no; L.h1 = f; f += nh; L.h2 = f; f += nh;
   L.a = f; f += na; L.qa = f; f += na;
@@ -76,7 +85,7 @@ __host__ __device__ inline WaveLayout wave_layout(uint32_t no, uint32_t nh, uint
 }
 
 size_t wave_rollout_lds_bytes(const es_config& c) {
-  const WaveLayout L = wave_layout(c.obs_dim, c.hid_dim, c.act_dim, c.num_hidden ? c.num_hidden : 2);
+  const WaveLayout L = wave_layout(c.obs_dim, c.hid_dim, c.act_dim, c.num_hidden ? c.num_hidden : 2, c.dtype == 1 && c.env_dtype == 1);
   return L.fcount * 4 + L.wcount * (c.dtype == 1 ? 2 : 4);
 }
 
@@ -85,9 +94,14 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
   using WS = WStore<BF16>;
   using WT = typename WS::T;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const WaveLayout L = wave_layout(a.no, a.nh, a.na, a.m);
+  const bool envf = BF16 && a.env_f32 != 0u;
+  const WaveLayout L = wave_layout(a.no, a.nh, a.na, a.m, envf);
   float* fl = reinterpret_cast<float*>(lds_raw);
   WT* wt = reinterpret_cast<WT*>(lds_raw + L.fcount * 4);
+  // the environment's matrices and operands: bf16-rounded like the policy's, or binary32
+  auto env_put = [&](size_t off, float v) { if (envf) fl[off] = v; else wt[off] = WS::put(BF16 ? bf16_round(v) : v); };
+  auto env_get = [&](size_t off) { return envf ? fl[off] : WS::get(wt[off]); };
+  auto env_opnd = [&](float v) { return (BF16 && !envf) ? bf16_round(v) : v; };
 
   const uint32_t lane = threadIdx.x;
   const uint32_t i = blockIdx.x / a.E, e = blockIdx.x % a.E;
@@ -125,15 +139,11 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
   }
   for (uint32_t q = lane; q < no * no; q += 64u) {
     const uint32_t k = q / no, j = q - k * no;
-    float v = a.A[q];
-    if (BF16) v = bf16_round(v);
-    wt[L.at + (size_t)j * L.p_o + k] = WS::put(v);
+    env_put(L.at + (size_t)j * L.p_o + k, a.A[q]);
   }
   for (uint32_t q = lane; q < no * na; q += 64u) {
     const uint32_t k = q / na, c = q - k * na;
-    float v = a.B[q];
-    if (BF16) v = bf16_round(v);
-    wt[L.bt + (size_t)c * L.p_o + k] = WS::put(v);
+    env_put(L.bt + (size_t)c * L.p_o + k, a.B[q]);
   }
   for (uint32_t k = lane; k < no; k += 64u) {
     fl[L.s + k] = reset_value(k, e, a.gen, a.k0, a.k1);
@@ -150,7 +160,7 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     for (uint32_t k = lane; k < no; k += 64u) {
       const float sv = fl[L.s + k];
       ss = __fmaf_rn(sv, sv, ss);
-      fl[L.x + k] = BF16 ? bf16_round(sv) : sv;
+      fl[L.x + k] = env_opnd(sv);             // the environment's operand
       const float pv = (sv - fl[L.mu + k]) * fl[L.iv + k];   // the policy's input (paper App. B: fixed statistics)
       fl[L.xp + k] = BF16 ? bf16_round(pv) : pv;
     }
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
       for (uint32_t k = 0; k < nh; ++k) acc = __fmaf_rn(WS::get(wt[L.w3 + (size_t)k * L.p_a + c]), fl[hin + k], acc);
       const float av = a.out_tanh ? tanh_accurate(acc) : acc;
       aa = __fmaf_rn(av, av, aa);
-      fl[L.qa + c] = BF16 ? bf16_round(av) : av;
+      fl[L.qa + c] = env_opnd(av);
     }
     __syncthreads();
     ss = wave_sum(ss);
@@ -189,8 +199,8 @@ __global__ __launch_bounds__(64) void rollout_wave_kernel(const WaveArgs a) {
     float mx = 0.0f;
     for (uint32_t k = lane; k < no; k += 64u) {
       float acc = 0.0f;
-      for (uint32_t j = 0; j < no; ++j) acc = __fmaf_rn(WS::get(wt[L.at + (size_t)j * L.p_o + k]), fl[L.x + j], acc);
-      for (uint32_t c = 0; c < na; ++c) acc = __fmaf_rn(WS::get(wt[L.bt + (size_t)c * L.p_o + k]), fl[L.qa + c], acc);
+      for (uint32_t j = 0; j < no; ++j) acc = __fmaf_rn(env_get(L.at + (size_t)j * L.p_o + k), fl[L.x + j], acc);
+      for (uint32_t c = 0; c < na; ++c) acc = __fmaf_rn(env_get(L.bt + (size_t)c * L.p_o + k), fl[L.qa + c], acc);
       const float sn = tanh_accurate(acc);
       mx = fmaxf(mx, fabsf(sn));
       fl[L.s + k] = sn;
@@ -233,6 +243,7 @@ int launch_rollout_wave(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode; a.hidden_relu = c.hidden_act == 1;
+  a.env_f32 = (c.dtype == 1 && c.env_dtype == 1) ? 1u : 0u;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const size_t lds = ctx->lds_bytes_wave;
   hipError_t err;

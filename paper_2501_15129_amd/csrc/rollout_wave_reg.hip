@@ -43,6 +43,7 @@ struct RegArgs {
   uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
   uint32_t gen, k0, k1;
   uint32_t antithetic, noise_mode, hidden_relu, out_tanh;
+  uint32_t env_f32;          // bf16 operands: keep the environment's products binary32
   float sigma, done_thresh, act_cost;
 };
 
@@ -105,6 +106,11 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
   const int hu = NQ == 1 ? lc : u;               // the hidden unit of this lane
   const bool hid = hu < nh;
   auto opnd = [](float v) { return BF16 ? bf16_round(v) : v; };      // a value as an operand of a product
+  // ... of one of the ENVIRONMENT's products: rounded like the policy's unless the environment stays binary32 (a select,
+  // not a branch: the flag is read into a vector register the compiler cannot prove uniform)
+  uint32_t envf_l = a.env_f32;
+  if (BF16) asm volatile("" : "+v"(envf_l));
+  auto opnd_env = [&](float v) { return BF16 ? (envf_l ? v : bf16_round(v)) : v; };
 
   // ---- perturbed parameters -> LDS (coalesced, binary32, one rounding each) ----
   {
@@ -159,10 +165,10 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
 #pragma unroll
     for (int j = 0; j < CJ; ++j) {
       const int el = 4 * lc + r, k = 4 * j + lr;
-      ar[CJ * r + j] = (lc < CJ && el < no && k < no) ? opnd(a.A[el * no + k]) : 0.f;
+      ar[CJ * r + j] = (lc < CJ && el < no && k < no) ? opnd_env(a.A[el * no + k]) : 0.f;
     }
 #pragma unroll
-  for (int c = 0; c < NAR; ++c) br[c] = (sval && c < na) ? opnd(a.B[ks * na + c]) : 0.f;
+  for (int c = 0; c < NAR; ++c) br[c] = (sval && c < na) ? opnd_env(a.B[ks * na + c]) : 0.f;
 
   // frozen observation statistics of this lane's state element (identity when none are set: (s - 0) * 1 = s exactly)
   const bool stats = a.obs_mean != nullptr;
@@ -213,9 +219,9 @@ __global__ __launch_bounds__(64) void rollout_reg_kernel(const RegArgs a) {
     // s' = tanh(A s + B a): partial sums of the four elements of this column over the inputs of this row, rows added
     // and moved to their element's lane; the action term straight from the row's action vector
     float ev[4];
-    row_bcast_dot<4, CJ>(ev, opnd(s), ar);
+    row_bcast_dot<4, CJ>(ev, opnd_env(s), ar);
     float pre = rows_transpose_add(ev[0], ev[1], ev[2], ev[3]);
-    pre = row_bcast_mac<NAR>(pre, opnd(tv), br);
+    pre = row_bcast_mac<NAR>(pre, opnd_env(tv), br);
     s = tanh_fast(pre);                                  // lanes without a state element: zero weights, tanh(0) = 0
     if (__ballot(fabsf(s) > a.done_thresh) != 0ull) break;       // max |s| > threshold: some lane exceeds it
   }
@@ -298,6 +304,7 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
   a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.noise_mode = nv.mode; a.hidden_relu = c.hidden_act == 1; a.out_tanh = c.out_tanh != 0;
+  a.env_f32 = (c.dtype == 1 && c.env_dtype == 1) ? 1u : 0u;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
   const dim3 grid(s.N * s.E);
   const size_t lds = (size_t)s.D * sizeof(float);      // at most 65*64 + 65*64 + 65*16 values: 37 KB
