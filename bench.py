@@ -182,6 +182,8 @@ def main() -> int:
                     help="the base configuration of the paper's OpenES timing experiment (Sec. 5.1: m = 2 hidden layers of 256, "
                          "population n = 128, k = 1 episode, T = 1000) on the synthetic environment at Swimmer's widths (obs 8, act 2), "
                          "bf16 operands; vary it with --num-hidden (m), --pop (n), --episodes-per-env (k)")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16",
+                    help="with --paper-base: bf16 operands (default) or binary32 throughout (fp32 matrix-core kernel)")
     ap.add_argument("--pop", type=int, default=None, help="population size override (with --paper-base: n)")
     ap.add_argument("--num-hidden", type=int, default=2, help="m hidden layers (paper Sec. 5.1 varies m); not the default workload")
     ap.add_argument("--episodes-per-env", type=int, default=1,
@@ -236,6 +238,8 @@ def main() -> int:
     base = CONFIGS[args.config]
     if args.paper_base:
         base = Workload("paper-base", pop=128, envs=1, horizon=1000, obs=8, hid=256, act=2, dtype=1, noise_dtype=1, seed=5)
+        if args.dtype == "f32":
+            base = replace(base, name="paper-base-f32", dtype=0, noise_dtype=0)
     if args.pop is not None:
         base = replace(base, name=base.name + f"-n{args.pop}", pop=args.pop)
     if args.noise_dtype is not None:
@@ -295,12 +299,13 @@ def main() -> int:
     upd_ms = mean(stage["update"])
     flops = flop_per_env_step(w) * executed
     bf16 = w.dtype == 1
+    f32_mfma = (not bf16) and "mfma" in ctx.rollout_kernel        # binary32 on the matrix cores: priced against the fp32 MFMA peak
     peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VALU_PEAK_TFLOPS
     ach = flops / (roll_ms * 1e-3) / 1e12
-    roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if bf16 else "alu", "achieved": ach, "peak": peak,
+    roofline = {"kernel": ctx.rollout_kernel, "bound": "mfma" if (bf16 or f32_mfma) else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                 "flop_per_launch": flops, "avg_launch_ms": roll_ms}
-    if bf16 and "mfma" in ctx.rollout_kernel:
+    if "mfma" in ctx.rollout_kernel:
         # the environment copies are the 16 columns of the matrix-core tile: with fewer episodes per individual only
         # that share of every MFMA is algorithmic work, whatever the kernel does
         cols = min(16, ctx.episodes) if ctx.episodes <= 16 else ctx.episodes / (16 * ((ctx.episodes + 15) // 16)) * 16

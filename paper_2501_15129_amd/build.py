@@ -12,7 +12,7 @@ CSRC = HERE / "csrc"
 LIB = HERE / "libes_hip.so"
 MICRO_LIB = HERE / "libes_microbench.so"
 SOURCES = ["api.hip", "sample.hip", "rank.hip", "update.hip", "rollout_wave.hip", "rollout_wave_reg.hip",
-           "rollout_mfma.hip"]
+           "rollout_mfma.hip", "rollout_mfma_f32.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

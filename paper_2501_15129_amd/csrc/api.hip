@@ -135,6 +135,9 @@ int es_create(const es_config* cfg, es_ctx** out) {
   if (ctx->reg_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_WAVE_REG;
     ctx->kernel_name = reg_variant_name(ctx->reg_variant, c.dtype == 1);
+  } else if (mfma_f32_fits(c)) {
+    ctx->rollout_kind = ROLLOUT_MFMA_F32;
+    ctx->kernel_name = c.obs_dim <= 32 ? "rollout_mfma_reg_f32<obs32,hid256,act16>" : "rollout_mfma_reg_f32<obs64,hid256,act16>";
   } else if (ctx->mfma_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_MFMA_REG;
     ctx->kernel_name = mfma_variant_name(ctx->mfma_variant);
@@ -261,6 +264,8 @@ static int enqueue_rollout(es_ctx* ctx, uint32_t generation, const float* theta_
                            hipStream_t st) {
   if (ctx->rollout_kind == ROLLOUT_WAVE_REG)
     return launch_rollout_reg(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);
+  if (ctx->rollout_kind == ROLLOUT_MFMA_F32)
+    return launch_rollout_mfma_f32(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);
   if (ctx->rollout_kind == ROLLOUT_MFMA_REG)
     return launch_rollout_mfma(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);
   return launch_rollout_wave(ctx, generation, theta_d, noise_d, A_d, B_d, returns_d, ep_len_d, fitness_d, workspace_d, st);

@@ -13,6 +13,7 @@ enum RolloutKind : int {
   ROLLOUT_WAVE_LDS = 0,   // one wavefront per (individual, env); weights in LDS
   ROLLOUT_MFMA_REG = 1,   // one workgroup per individual; bf16 weights resident in registers, MFMA
   ROLLOUT_WAVE_REG = 2,   // one wavefront per (individual, env); binary32 weights resident in registers
+  ROLLOUT_MFMA_F32 = 3,   // one workgroup per individual; binary32 weights resident in registers, fp32 MFMA
 };
 
 struct Shape {
@@ -92,6 +93,10 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
 int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
                        const float* A, const float* B, float* returns, int32_t* ep_len,
                        float* fitness, void* ws, hipStream_t st);
+int launch_rollout_mfma_f32(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
+                            const float* A, const float* B, float* returns, int32_t* ep_len,
+                            float* fitness, void* ws, hipStream_t st);
+bool mfma_f32_fits(const es_config& cfg);         // binary32, 65..256 hidden units, two hidden layers, obs <= 64, act <= 16
 int launch_fitness(es_ctx* ctx, const float* returns, float* fitness, hipStream_t st);
 int reg_variant_for(const es_config& cfg);        // -1 when no one-wavefront register-resident kernel is built for the shape
 std::string reg_variant_name(int variant, bool bf16);

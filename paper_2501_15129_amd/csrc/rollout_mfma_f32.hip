@@ -1,0 +1,384 @@
+// es_rollout, register-resident matrix-core variant for BINARY32 policies with a wide hidden layer.
+//
+// Paper Sec. 5.1 times OpenES on policies with m hidden layers of 256 units in the framework's default
+// precision; Sec. 3.2 / 5.2 define the evaluation (population x environment copies, fitness = mean
+// undiscounted return).  A 256-wide two-layer policy is 272-300 KB in binary32: more than the LDS, less than
+// the 512 KB register file of a CU.  One workgroup of four wavefronts evaluates one individual on up to 16
+// environment copies per pass, every product on the fp32 16x16x4 MFMA (lane (g, n) supplies A[row n][k = g]
+// and B[k = g][column n]; the 16 columns are the environment copies):
+//
+//   * each wavefront owns 64 units (four 16-row tiles) of both hidden layers; its rows of W1 and W2 sit in
+//     registers as MFMA A operands for all T steps (W2: 256 registers per lane, in the accumulation half of
+//     the file), the perturbation fused into the load;
+//   * the K order of a product is free as long as both operands agree, so it is chosen per layer such that a
+//     lane's operands are contiguous where they come from: layer 1 and A s read the lane's KPL consecutive
+//     state elements of its column from the binary32 state buffer; layer 2 reads 64 consecutive units of h1;
+//     the action layer is split along K - every wavefront multiplies the h2 units it has just produced, still
+//     in its registers, with its slice of W3, and only the partial sums cross the LDS; B a takes the action
+//     from the registers the reduction leaves it in;
+//   * three workgroup barriers per step (h1, action partials, new state); the norms for the reward and the
+//     termination test are reduced inside a wavefront with the row-swap instructions and across wavefronts
+//     through one LDS partial per wavefront, added by every lane in the same order: reruns are bit-identical.
+// Bound: the fp32 MFMA pipe (32 cycles per 16x16x4 instruction, 4 (KPL + 64 + 4) + KPL + 4 of them per step).
+#include <algorithm>
+
+#include "es_device.hpp"
+#include "es_internal.hpp"
+
+namespace es {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct F32Args {
+  const float* theta;
+  const void* noise;
+  const uint32_t* noise_offs;   // shared noise table: start of every row, else null
+  const float* A;
+  const float* B;
+  const float* obs_mean;        // frozen observation statistics (paper App. B), or null
+  const float* obs_inv;
+  float* returns;
+  int32_t* ep_len;
+  float* fitness;
+  uint32_t N, E, T, no, nh, na, ld;
+  uint32_t oW1, ob1, oW2, ob2, oW3, ob3;
+  uint32_t gen, k0, k1;
+  uint32_t antithetic, out_tanh, noise_mode;
+  float sigma, done_thresh, act_cost;
+};
+
+constexpr int NHP = 256;       // padded hidden width
+constexpr int NCOL = 16;       // environment copies per pass
+constexpr int PH = NHP + 4;    // LDS pitch (floats) of an h1 row: 16-byte reads of 16 lanes hit distinct banks
+
+__device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ void pin_agpr(float& v) { asm volatile("" : "+a"(v)); }
+__device__ __forceinline__ void pin_vgpr(float& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ unsigned umax(unsigned a, unsigned b) { return a > b ? a : b; }
+__device__ __forceinline__ unsigned abs_bits(float v) { return __builtin_bit_cast(unsigned, v) & 0x7FFFFFFFu; }
+// sum / max over the four 16-lane rows of the wavefront (lanes l, l+16, l+32, l+48), result in every row
+__device__ __forceinline__ float rows_sum(float v) {
+  const unsigned b = __builtin_bit_cast(unsigned, v);
+  const auto p = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+  const float t = __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
+  const unsigned c = __builtin_bit_cast(unsigned, t);
+  const auto r = __builtin_amdgcn_permlane32_swap(c, c, false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+__device__ __forceinline__ unsigned rows_umax(unsigned b) {
+  const auto p = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+  const unsigned c = umax((unsigned)p[0], (unsigned)p[1]);
+  const auto r = __builtin_amdgcn_permlane32_swap(c, c, false, false);
+  return umax((unsigned)r[0], (unsigned)r[1]);
+}
+__device__ __forceinline__ f32x4 tanh4(f32x4 v) { return f32x4{tanh_fast(v.x), tanh_fast(v.y), tanh_fast(v.z), tanh_fast(v.w)}; }
+template <bool RELU>
+__device__ __forceinline__ f32x4 hidden4(f32x4 v) {
+  if (RELU) return f32x4{fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)};
+  return tanh4(v);
+}
+
+// KPL: state elements per lane group of the K dimension (padded observation width NOP = 4 KPL: 32 or 64)
+template <int KPL>
+struct Lds {
+  static constexpr int NOP = 4 * KPL;
+  static constexpr int PXF = NOP + 4;                      // pitch of a state row (floats)
+  static constexpr int OFF_H1 = 0;                         // [copy][PH] f32
+  static constexpr int OFF_XF = OFF_H1 + 4 * NCOL * PH;    // [copy][PXF] f32
+  static constexpr int OFF_P3 = OFF_XF + 4 * NCOL * PXF;   // action partials [wavefront][copy][16 rows] f32
+  static constexpr int OFF_SSP = OFF_P3 + 4 * 4 * NCOL * 16;   // |s'|^2 partials [copy][wavefront]
+  static constexpr int OFF_MXP = OFF_SSP + 4 * NCOL * 4;       // max|s'| partials, same layout
+  static constexpr int OFF_B1 = OFF_MXP + 4 * NCOL * 4;
+  static constexpr int OFF_B2 = OFF_B1 + 4 * NHP;
+  static constexpr int OFF_B3 = OFF_B2 + 4 * NHP;
+  static constexpr int OFF_MU = OFF_B3 + 4 * 16;
+  static constexpr int OFF_IV = OFF_MU + 4 * NOP;
+  static constexpr int OFF_SCR = OFF_IV + 4 * NOP;         // scratch for the initial-state norms [16][16]
+  static constexpr int OFF_WIN = OFF_SCR + 4 * 256;        // staging window [256][65] f32
+  static constexpr int BYTES = OFF_WIN + 4 * NHP * 65;
+};
+
+template <int KPL, bool RELU, bool NORM>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void rollout_mfma_f32_kernel(const F32Args a) {
+  using L = Lds<KPL>;
+  constexpr int NOP = L::NOP, PXF = L::PXF;
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, n = lane & 15;
+  const int no = (int)a.no, nh = (int)a.nh, na = (int)a.na;
+  float* h1s = reinterpret_cast<float*>(lds + L::OFF_H1);
+  float* xfs = reinterpret_cast<float*>(lds + L::OFF_XF);
+  float* p3s = reinterpret_cast<float*>(lds + L::OFF_P3);
+  float* ssps = reinterpret_cast<float*>(lds + L::OFF_SSP);
+  unsigned* mxps = reinterpret_cast<unsigned*>(lds + L::OFF_MXP);
+  float* b1s = reinterpret_cast<float*>(lds + L::OFF_B1);
+  float* b2s = reinterpret_cast<float*>(lds + L::OFF_B2);
+  float* b3s = reinterpret_cast<float*>(lds + L::OFF_B3);
+  float* mus = reinterpret_cast<float*>(lds + L::OFF_MU);
+  float* ivs = reinterpret_cast<float*>(lds + L::OFF_IV);
+  const bool env_wave = 16 * w < NOP;                     // this wavefront owns state rows 16w..16w+15
+
+  // ---- environment matrices -> registers (once per workgroup): Af[kk] = A[16w + n][KPL g + kk], Bf[kk] = B[16w + n][4g + kk]
+  float Af[KPL], Bf[4];
+  {
+    const int row = 16 * w + n;
+#pragma unroll
+    for (int kk = 0; kk < KPL; ++kk) { const int k = KPL * g + kk; Af[kk] = (row < no && k < no) ? a.A[row * no + k] : 0.0f; }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { const int c = 4 * g + kk; Bf[kk] = (row < no && c < na) ? a.B[row * na + c] : 0.0f; }
+  }
+  if (NORM) {
+    for (int k = tid; k < NOP; k += 256) {
+      mus[k] = k < no ? a.obs_mean[k] : 0.0f;
+      ivs[k] = k < no ? a.obs_inv[k] : 0.0f;
+    }
+  }
+  const uint32_t per_unit = a.antithetic ? 2u : 1u;
+  const uint32_t nblk = (a.E + (uint32_t)NCOL - 1u) / (uint32_t)NCOL;
+  const float inv_no = 1.0f / (float)no;
+
+  for (uint32_t i = blockIdx.x; i < a.N; i += gridDim.x) {
+    const uint32_t unit = i / per_unit, sub = i - unit * per_unit;
+    const float scale = sub ? -a.sigma : a.sigma;
+    const void* nbase = a.noise;
+    uint32_t nrow = unit;
+    if (a.noise_offs) { nbase = table_row_base(a.noise_mode, a.noise, a.noise_offs, unit); nrow = 0u; }
+    auto param = [&](uint32_t idx) {
+      return __fmaf_rn(scale, noise_value(a.noise_mode, nbase, a.ld, nrow, idx, a.gen, a.k0, a.k1), a.theta[idx]);
+    };
+    __syncthreads();          // the previous individual's last reads of the bias arrays are done
+    // ---- perturbed parameters -> LDS window (coalesced) -> registers, a slab at a time ----
+    // The window holds 256 rows x 64 columns (pitch 65).  W2 goes through it in four slabs: slab c = columns
+    // 64g + 16c .. + 15 of every lane group g, so that a lane picks its K slots 16c .. 16c + 15 of all four tiles.
+    float W1r[4][KPL], W2r[4][64], W3k[16];
+    float* win = reinterpret_cast<float*>(lds + L::OFF_WIN);
+    constexpr int PWIN = 65;
+    for (int q = tid; q < NHP * NOP; q += 256) {
+      const int row = q / NOP, k = q - row * NOP;
+      win[row * PWIN + k] = (row < nh && k < no) ? param(a.oW1 + (uint32_t)(row * no + k)) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int kk = 0; kk < KPL; ++kk) W1r[tt][kk] = win[(64 * w + 16 * tt + n) * PWIN + KPL * g + kk];
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      for (int q = tid; q < NHP * 64; q += 256) {
+        const int row = q >> 6, cc = q & 63, k = 64 * (cc >> 4) + 16 * c + (cc & 15);
+        win[row * PWIN + cc] = (row < nh && k < nh) ? param(a.oW2 + (uint32_t)(row * nh + k)) : 0.0f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) W2r[tt][16 * c + q] = win[(64 * w + 16 * tt + n) * PWIN + 16 * g + q];
+      __syncthreads();
+    }
+    // action layer: K slot (j, g) = unit 64w + 16 (j / 4) + 4g + (j % 4), the order of h2 in the registers
+    for (int q = tid; q < 16 * NHP; q += 256) {
+      const int row = q >> 8, u = q & 255;
+      win[row * (NHP + 1) + u] = (row < na && u < nh) ? param(a.oW3 + (uint32_t)(row * nh + u)) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; ++j) W3k[j] = win[n * (NHP + 1) + 64 * w + 16 * (j >> 2) + 4 * g + (j & 3)];
+    for (int u = tid; u < NHP; u += 256) {
+      b1s[u] = u < nh ? param(a.ob1 + (uint32_t)u) : 0.0f;
+      b2s[u] = u < nh ? param(a.ob2 + (uint32_t)u) : 0.0f;
+    }
+    if (tid < 16) b3s[tid] = tid < na ? param(a.ob3 + (uint32_t)tid) : 0.0f;
+
+    float fit_sum = 0.0f;
+    for (uint32_t cb = 0; cb < nblk; ++cb) {
+      // ---- initial states of this block of copies, their norms as the partials of "step -1" ----
+      __syncthreads();
+      {
+        const int n0 = tid & 15, kq = tid >> 4;
+        const uint32_t e0 = cb * (uint32_t)NCOL + (uint32_t)n0;
+        float part = 0.0f;
+        for (int k = kq; k < NOP; k += 16) {
+          float v = 0.0f;
+          if (k < no && e0 < a.E) v = reset_value((uint32_t)k, e0, a.gen, a.k0, a.k1);
+          part = __fmaf_rn(v, v, part);
+          xfs[n0 * PXF + k] = v;
+        }
+        float* scratch = reinterpret_cast<float*>(lds + L::OFF_SCR);
+        scratch[kq * 16 + n0] = part;
+        __syncthreads();
+        if (tid < 16) {
+          float s = 0.0f;
+          for (int r = 0; r < 16; ++r) s += scratch[r * 16 + tid];
+          ssps[tid * 4] = s; ssps[tid * 4 + 1] = 0.0f; ssps[tid * 4 + 2] = 0.0f; ssps[tid * 4 + 3] = 0.0f;
+          mxps[tid * 4] = 0u; mxps[tid * 4 + 1] = 0u; mxps[tid * 4 + 2] = 0u; mxps[tid * 4 + 3] = 0u;
+        }
+        __syncthreads();
+      }
+      const uint32_t e = cb * (uint32_t)NCOL + (uint32_t)n;
+      bool alive = e < a.E;
+      float Rn = 0.0f, aa_prev = 0.0f, ss_cur = 0.0f;
+      int32_t Ln = 0;
+      bool first = true;
+
+      for (uint32_t t = 0; t <= a.T; ++t) {
+        // ---- phase A: books of the previous step; h1 = act(W1 x + b1); A s ----
+        const f32x4 sp4 = *reinterpret_cast<const f32x4*>(ssps + 4 * n);
+        const u32x4 mp4 = *reinterpret_cast<const u32x4*>(mxps + 4 * n);
+        float xf[KPL], xp[KPL];
+#pragma unroll
+        for (int j = 0; j < KPL / 4; ++j) {
+          const f32x4 v4 = *reinterpret_cast<const f32x4*>(xfs + n * PXF + KPL * g + 4 * j);
+          xf[4 * j] = v4.x; xf[4 * j + 1] = v4.y; xf[4 * j + 2] = v4.z; xf[4 * j + 3] = v4.w;
+        }
+#pragma unroll
+        for (int kk = 0; kk < KPL; ++kk) xp[kk] = NORM ? (xf[kk] - mus[KPL * g + kk]) * ivs[KPL * g + kk] : xf[kk];
+        f32x4 acc[4];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b1s + 64 * w + 16 * tt + 4 * g);
+#pragma unroll
+        for (int kk = 0; kk < KPL; ++kk)
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) {
+            if (KPL > 8 && tt < 2) pin_agpr(W1r[tt][kk]);      // the wider observation: half of W1 joins W2 in the accumulation half
+            acc[tt] = mfma4(W1r[tt][kk], xp[kk], acc[tt]);
+          }
+        {
+          const float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
+          const float mx = __builtin_bit_cast(float, umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w)));
+          const bool book = !first, add = book && alive;
+          const float r = __fmaf_rn(-ss_cur, inv_no, 1.0f) - a.act_cost * aa_prev;
+          Rn += add ? r : 0.0f;
+          Ln += add ? 1 : 0;
+          alive = alive && !(book && mx > a.done_thresh);
+          ss_cur = ss_new;
+          first = false;
+        }
+        if (t == a.T || __ballot(alive) == 0ull) break;       // identical in all four wavefronts
+        f32x4 accE = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (env_wave) {
+#pragma unroll
+          for (int kk = 0; kk < KPL; ++kk) accE = mfma4(Af[kk], xf[kk], accE);
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          const f32x4 h = hidden4<RELU>(acc[tt]);
+          *reinterpret_cast<f32x4*>(h1s + n * PH + 64 * w + 16 * tt + 4 * g) = h;
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) acc[tt] = *reinterpret_cast<const f32x4*>(b2s + 64 * w + 16 * tt + 4 * g);
+        __syncthreads();
+        // ---- phase B: h2 = act(W2 h1 + b2); K slot (kk, g) = unit 64g + kk: 64 consecutive values of the lane's column ----
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const f32x4 hb = *reinterpret_cast<const f32x4*>(h1s + n * PH + 64 * g + 4 * j);
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+              // three of the four tiles of W2 live in the accumulation half of the register file (192 of its 256
+              // registers; the rest is left to the compiler), the fourth beside everything else in the architectural half
+              if (tt < 3) pin_agpr(W2r[tt][4 * j + r]); else pin_vgpr(W2r[tt][4 * j + r]);
+              acc[tt] = mfma4(W2r[tt][4 * j + r], hb[r], acc[tt]);
+            }
+        }
+        // this wavefront's K slice of the action layer, from the registers that hold its h2
+        f32x4 p3 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          const f32x4 h = hidden4<RELU>(acc[tt]);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) p3 = mfma4(W3k[4 * tt + r], h[r], p3);
+        }
+        *reinterpret_cast<f32x4*>(p3s + (w * NCOL + n) * 16 + 4 * g) = p3;
+        __syncthreads();
+        // ---- phase D: a = tanh(sum of the partials + b3); s' = tanh(A s + B a); norms ----
+        f32x4 v = *reinterpret_cast<const f32x4*>(b3s + 4 * g);
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) v += *reinterpret_cast<const f32x4*>(p3s + (ww * NCOL + n) * 16 + 4 * g);
+        {
+          const f32x4 tv = tanh4(v);
+          const bool squash = a.out_tanh != 0u;
+          v = f32x4{squash ? tv.x : v.x, squash ? tv.y : v.y, squash ? tv.z : v.z, squash ? tv.w : v.w};
+        }
+        float part = v.x * v.x;
+        part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+        aa_prev = rows_sum(part);                  // |a_t|^2 of column n (rows past the action width are exactly zero)
+        float ssp = 0.0f;
+        unsigned mxp = 0u;
+        if (env_wave) {
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) accE = mfma4(Bf[kk], v[kk], accE);       // K slot (kk, g) = action row 4g + kk
+          const f32x4 sn = tanh4(accE);
+          ssp = sn.x * sn.x;
+          ssp = __fmaf_rn(sn.y, sn.y, ssp); ssp = __fmaf_rn(sn.z, sn.z, ssp); ssp = __fmaf_rn(sn.w, sn.w, ssp);
+          mxp = umax(umax(abs_bits(sn.x), abs_bits(sn.y)), umax(abs_bits(sn.z), abs_bits(sn.w)));
+          *reinterpret_cast<f32x4*>(xfs + n * PXF + 16 * w + 4 * g) = sn;
+        }
+        ssp = rows_sum(ssp);
+        mxp = rows_umax(mxp);
+        if (g == 0) { ssps[n * 4 + w] = ssp; mxps[n * 4 + w] = mxp; }
+        __syncthreads();
+      }
+      // ---- outputs of this block of copies ----
+      if (w == 0) {
+        const uint32_t cnt = min((uint32_t)NCOL, a.E - cb * (uint32_t)NCOL);
+        if (g == 0 && (uint32_t)n < cnt) {
+          a.returns[(size_t)i * a.E + e] = Rn;
+          a.ep_len[(size_t)i * a.E + e] = Ln;
+        }
+        for (uint32_t r = 0; r < cnt; ++r) fit_sum += __shfl(Rn, (int)r, 64);
+      }
+    }
+    if (tid == 0) a.fitness[i] = fit_sum / (float)a.E;
+  }
+}
+
+template <int KPL, bool RELU, bool NORM>
+int launch_one(es_ctx* ctx, const F32Args& a, hipStream_t st) {
+  const void* fn = reinterpret_cast<const void*>(rollout_mfma_f32_kernel<KPL, RELU, NORM>);
+  hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<KPL>::BYTES);
+  if (err != hipSuccess) return fail(ctx, ES_EHIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(err));
+  const uint32_t grid = std::min<uint32_t>(a.N, (uint32_t)std::max(1, ctx->num_cus));      // persistent: one workgroup per CU
+  hipLaunchKernelGGL((rollout_mfma_f32_kernel<KPL, RELU, NORM>), dim3(grid), dim3(256), Lds<KPL>::BYTES, st, a);
+  return check_launch(ctx, "es_rollout (fp32 MFMA)");
+}
+template <int KPL>
+int launch_kpl(es_ctx* ctx, const F32Args& a, hipStream_t st) {
+  const bool relu = ctx->cfg.hidden_act == 1, norm = ctx->obs_mean != nullptr;
+  if (relu) return norm ? launch_one<KPL, true, true>(ctx, a, st) : launch_one<KPL, true, false>(ctx, a, st);
+  return norm ? launch_one<KPL, false, true>(ctx, a, st) : launch_one<KPL, false, false>(ctx, a, st);
+}
+
+}  // namespace
+
+// Binary32 policies with 65..256 hidden units, two hidden layers, obs <= 64, act <= 16.
+bool mfma_f32_fits(const es_config& c) {
+  const uint32_t m = c.num_hidden ? c.num_hidden : 2;
+  return c.dtype == 0 && m == 2 && c.hid_dim > 64 && c.hid_dim <= (uint32_t)NHP && c.obs_dim <= 64 && c.act_dim <= 16;
+}
+
+int launch_rollout_mfma_f32(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise, const float* A,
+                            const float* B, float* returns, int32_t* ep_len, float* fitness, void* /*ws*/,
+                            hipStream_t st) {
+  const Shape& s = ctx->shp;
+  const es_config& c = ctx->cfg;
+  if (!mfma_f32_fits(c)) return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no binary32 matrix-core variant for this shape");
+  F32Args a;
+  const NoiseView nv = noise_view(ctx, noise);
+  a.theta = theta; a.noise = nv.base; a.noise_offs = nv.offs; a.A = A; a.B = B; a.obs_mean = ctx->obs_mean; a.obs_inv = ctx->obs_inv_std;
+  a.returns = returns; a.ep_len = ep_len; a.fitness = fitness;
+  a.N = s.N; a.E = s.E; a.T = s.T; a.no = s.no; a.nh = s.nh; a.na = s.na; a.ld = s.ld;
+  a.oW1 = s.oW1; a.ob1 = s.ob1; a.oW2 = s.oW2; a.ob2 = s.ob2; a.oW3 = s.oW3; a.ob3 = s.ob3;
+  a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
+  a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode;
+  a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
+  return s.no <= 32 ? launch_kpl<8>(ctx, a, st) : launch_kpl<16>(ctx, a, st);
+}
+
+}  // namespace es
