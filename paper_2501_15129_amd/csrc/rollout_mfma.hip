@@ -58,10 +58,6 @@ constexpr int NHP = 256;          // padded hidden width handled by this kernel
 constexpr int KT_H = NHP / 32;    // 32-deep K tiles over the hidden width
 constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activation row
 
-#ifndef ES_V256_KTAR
-#define ES_V256_KTAR 4
-#endif
-
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
@@ -1144,7 +1140,12 @@ template <int NC, int NW, int ME> using V64D = Variant<2, 1, env_tiles(64, NW), 
 // A single hidden layer (m = 1) of the same two shapes: the second layer's phase and weights drop out.
 template <int NC, int NW> using V32S = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2, -1>;
 template <int NC, int NW> using V64S = Variant<2, 1, env_tiles(64, NW), 2, NC, NW, 1, -1>;
-template <int NC, int NW> using V256 = Variant<8, 2, env_tiles(256, NW), ES_V256_KTAR, NC, NW>;   // obs <= 256, act <= 32; part of A lives in LDS
+// obs <= 256, act <= 32.  KTAR of the eight K tiles of the environment matrix A sit in registers, the rest in LDS.  Measured at
+// configs[4] (ms per rollout): passes of four copies with tanh 27.5 (all eight in registers) against 28.6 (four); with ReLU the
+// register allocation of the epilogue differs and four is better (27.6 against 29.5); passes of sixteen copies have the larger
+// working set and four is as fast (37.9 with four episodes per copy either way).
+template <int NC, int NW, int KTAR> using V256K = Variant<8, 2, env_tiles(256, NW), KTAR, NC, NW>;
+template <int NC, int NW> using V256 = V256K<NC, NW, 4>;
 
 struct VariantInfo { int max_obs, max_act; const char* name; };
 static const VariantInfo kVariants[] = {
@@ -1209,7 +1210,7 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
   if (c.env_dtype == 1 && ctx->mfma_variant == 0 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
     return launch_variant_act<V32F<16, 4>, false, false>(ctx, a, units, st);
   if (ctx->mfma_variant == 3 && narrow && s.m == 2 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
-    return launch_variant_act<V256<4, 4>, false, false>(ctx, a, units, st);
+    return launch_variant_act<V256K<4, 4, 8>, false, false>(ctx, a, units, st);
   if (ctx->mfma_variant == 0 && !narrow && s.m == 2 && ctx->cfg.hidden_act == 0 && !ctx->obs_mean)
     return launch_variant_act<V32<16, 4>, false, false>(ctx, a, units, st);
   return fail(ctx, ES_EUNSUPPORTED, "tuning build: variant not compiled");
@@ -1234,7 +1235,12 @@ int launch_rollout_mfma(es_ctx* ctx, uint32_t gen, const float* theta, const voi
     case 0: return narrow ? launch_variant<V32<4, 4>>(ctx, a, units, st) : launch_variant<V32<16, 4>>(ctx, a, units, st);
     case 1: return narrow ? launch_variant<V64<4, 4>>(ctx, a, units, st) : launch_variant<V64<16, 4>>(ctx, a, units, st);
     case 2: return narrow ? launch_variant<V128<4, 4>>(ctx, a, units, st) : launch_variant<V128<16, 4>>(ctx, a, units, st);
-    case 3: return narrow ? launch_variant<V256<4, 4>>(ctx, a, units, st) : launch_variant<V256<16, 4>>(ctx, a, units, st);
+    case 3: {
+      if (!narrow) return launch_variant<V256<16, 4>>(ctx, a, units, st);
+      const bool norm = ctx->obs_mean != nullptr;
+      if (ctx->cfg.hidden_act == 1) return norm ? launch_variant_act<V256K<4, 4, 4>, true, true>(ctx, a, units, st) : launch_variant_act<V256K<4, 4, 4>, true, false>(ctx, a, units, st);
+      return norm ? launch_variant_act<V256K<4, 4, 8>, false, true>(ctx, a, units, st) : launch_variant_act<V256K<4, 4, 8>, false, false>(ctx, a, units, st);
+    }
     default: return fail(ctx, ES_EUNSUPPORTED, "es_rollout: no register-resident variant for this shape");
   }
 #endif
