@@ -46,6 +46,19 @@ struct MfmaArgs {
   unsigned long long* prof;     // phase-timing build only (ES_PHASE_PROF): cycle totals per wavefront and phase
 };
 
+// A kernel argument read afresh from the kernel-argument segment (the one by-value argument starts at its offset 0),
+// through a pointer the compiler cannot see through.  The staging code takes its arguments this way once per
+// individual: read from the by-value copy they would be loaded once and then held in scalar registers across the
+// step loop, which already spills scalar registers to vector lanes and reloads them every step.
+template <class T>
+__device__ __forceinline__ T kernarg_field(size_t byte_off) {
+  const __attribute__((address_space(4))) char* p =
+      (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(p));
+  return *reinterpret_cast<const __attribute__((address_space(4))) T*>(p + byte_off);
+}
+#define KARG(field) kernarg_field<decltype(MfmaArgs::field)>(offsetof(MfmaArgs, field))
+
 // Phase timing for tuning (compiled in with -DES_PHASE_PROF only): shader-clock cycles between consecutive stamps,
 // summed over all steps of the individuals of workgroup 0, one row of 16 slots per wavefront.
 #ifdef ES_PHASE_PROF
@@ -58,6 +71,9 @@ constexpr int NHP = 256;          // padded hidden width handled by this kernel
 constexpr int KT_H = NHP / 32;    // 32-deep K tiles over the hidden width
 constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activation row
 
+#ifndef ES_STAGE_UNROLL
+#define ES_STAGE_UNROLL 8     // staging iterations whose loads are in flight together
+#endif
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
@@ -126,7 +142,11 @@ struct Variant {
   static constexpr int PXF = NOP + 4;
   static constexpr int OFF_XF = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : 0);
   static constexpr int OFF_X0F = OFF_XF + (ENVF ? 4 * NC * PXF : 0);
-  static constexpr int LDS_BYTES = OFF_X0F + (ENVF ? 4 * NC * PXF : 0);
+  // With all of A in registers the step loop has under a hundred working registers left: B and this wavefront's slice
+  // of the action-layer weights then stay in LDS and are fetched where they are used (a dozen reads per step).
+  static constexpr bool SMALL_LDS = FUSE3 && KTAR_ >= KT1_ && KT1_ >= 8;
+  static constexpr int OFF_BL = OFF_X0F + (ENVF ? 4 * NC * PXF : 0);      // B [ENV_ROWS][PA] bf16
+  static constexpr int LDS_BYTES = OFF_BL + (SMALL_LDS ? 2 * ENV_ROWS * PA : 0);
   static_assert(!ENVF || (NC == 16 && ME == 0 && MT3 == 1 && KT1 <= 2), "binary32 environment: passes of 16 copies, two hidden layers, obs <= 64, act <= 16");
   static_assert(ENV_ROWS >= NOP, "the wavefronts must cover the padded state");
   static_assert(ENV_ROWS <= 256, "staging window rows");
@@ -252,6 +272,14 @@ __device__ __forceinline__ float row_noise(const NoiseRow& nz, uint32_t idx) {
   return nz.mode == 1u ? bf16_to_f32(static_cast<const uint16_t*>(nz.ptr)[idx]) : static_cast<const float*>(nz.ptr)[idx];
 }
 
+// Four stored noise values as binary32: binary32 as they are, bf16 pairs widened (an int stands for "no noise").
+__device__ __forceinline__ f32x4 widen4(f32x4 e) { return e; }
+__device__ __forceinline__ f32x4 widen4(u32x2 raw) {
+  return f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
+               __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
+}
+__device__ __forceinline__ f32x4 widen4(int) { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+
 // Fill dst[r * pitch + c] (bf16) for r < rows_p, c < COLS with the bf16-rounded source value of
 // matrix element (r, kbase + c) when r < rows and kbase + c < cols, and zero elsewhere.
 // PERTURB: value = fma(scale, noise[idx], theta[idx]) with idx = off + r * cols + (kbase + c).
@@ -259,44 +287,66 @@ template <int COLS, bool PERTURB>
 __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p, int rows, int cols, int kbase,
                                            const float* __restrict__ src, const NoiseRow nz, float scale, uint32_t off) {
   if (((cols | (int)off | kbase) & 3) == 0) {
-    // four consecutive columns per thread: 16-byte parameter loads, 8/16-byte noise loads, 8-byte LDS stores
+    // four consecutive columns per thread: 16-byte parameter loads, 8/16-byte noise loads, 8-byte LDS stores.
+    // The loads of U iterations are issued together and unconditionally (a masked-out element reads the
+    // matrix's first four entries instead, which are always there), and only then consumed: a load inside the
+    // bounds test would be waited for in its own iteration, and the round would cost U memory latencies, not one.
     constexpr int C4 = COLS / 4;
     const int total = rows_p * C4;
-    auto body = [&](int q, auto fetch) {
-      const int r = q / C4, c = (q % C4) * 4, k = kbase + c;
-      f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (r < rows && k < cols) {
-        const uint32_t idx = off + (uint32_t)r * (uint32_t)cols + (uint32_t)k;
-        v = *reinterpret_cast<const f32x4*>(src + idx);
-        if (PERTURB) {
-          const f32x4 e = fetch(idx);
-          v = f32x4{__fmaf_rn(scale, e.x, v.x), __fmaf_rn(scale, e.y, v.y), __fmaf_rn(scale, e.z, v.z), __fmaf_rn(scale, e.w, v.w)};
+    const int step = (int)blockDim.x;
+    auto batch = [&](auto fetch) {
+      constexpr int U = ES_STAGE_UNROLL;
+      for (int q0 = threadIdx.x; q0 < total; q0 += U * step) {
+        f32x4 tv[U];
+        decltype(fetch(0u)) ev[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int q = q0 + u * step;
+          const int r = q / C4, k = kbase + (q % C4) * 4;
+          ok[u] = q < total && r < rows && k < cols;
+          const uint32_t idx = ok[u] ? off + (uint32_t)r * (uint32_t)cols + (uint32_t)k : off;
+          tv[u] = *reinterpret_cast<const f32x4*>(src + idx);
+          ev[u] = fetch(idx);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int q = q0 + u * step;
+          if (q < total) {
+            const int r = q / C4, c = (q % C4) * 4;
+            f32x4 v = tv[u];
+            if (PERTURB) {
+              const f32x4 e = widen4(ev[u]);
+              v = f32x4{__fmaf_rn(scale, e.x, v.x), __fmaf_rn(scale, e.y, v.y), __fmaf_rn(scale, e.z, v.z), __fmaf_rn(scale, e.w, v.w)};
+            }
+            if (!ok[u]) v = f32x4{0.f, 0.f, 0.f, 0.f};
+            *reinterpret_cast<u32x2*>(dst + r * pitch + c) = pack_bf16x4(v.x, v.y, v.z, v.w);
+          }
         }
       }
-      *reinterpret_cast<u32x2*>(dst + r * pitch + c) = pack_bf16x4(v.x, v.y, v.z, v.w);
     };
     // one loop per storage mode, chosen outside it (the mode is uniform); the regenerating loop is not
     // unrolled: its body is two hundred instructions, and the staging code should stay in the instruction cache
     if (PERTURB && nz.mode >= 2u) {
 #pragma unroll 1
-      for (int q = threadIdx.x; q < total; q += (int)blockDim.x)
-        body(q, [&](uint32_t idx) {
+      for (int q = threadIdx.x; q < total; q += step) {
+        const int r = q / C4, c = (q % C4) * 4, k = kbase + c;
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (r < rows && k < cols) {
+          const uint32_t idx = off + (uint32_t)r * (uint32_t)cols + (uint32_t)k;
+          v = *reinterpret_cast<const f32x4*>(src + idx);
           float z[4];
           noise_regen4(nz.row, idx, nz.gen, nz.k0, nz.k1, nz.mode == 3u, z);
-          return f32x4{z[0], z[1], z[2], z[3]};
-        });
+          v = f32x4{__fmaf_rn(scale, z[0], v.x), __fmaf_rn(scale, z[1], v.y), __fmaf_rn(scale, z[2], v.z), __fmaf_rn(scale, z[3], v.w)};
+        }
+        *reinterpret_cast<u32x2*>(dst + r * pitch + c) = pack_bf16x4(v.x, v.y, v.z, v.w);
+      }
     } else if (PERTURB && nz.mode == 1u) {
-#pragma unroll 4
-      for (int q = threadIdx.x; q < total; q += (int)blockDim.x)
-        body(q, [&](uint32_t idx) {
-          const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(nz.ptr) + idx);
-          return f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
-                       __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u)};
-        });
+      batch([&](uint32_t idx) { return *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(nz.ptr) + idx); });
+    } else if (PERTURB) {
+      batch([&](uint32_t idx) { return *reinterpret_cast<const f32x4*>(static_cast<const float*>(nz.ptr) + idx); });
     } else {
-#pragma unroll 4
-      for (int q = threadIdx.x; q < total; q += (int)blockDim.x)
-        body(q, [&](uint32_t idx) { return PERTURB ? *reinterpret_cast<const f32x4*>(static_cast<const float*>(nz.ptr) + idx) : f32x4{0.f, 0.f, 0.f, 0.f}; });
+      batch([&](uint32_t) { return 0; });
     }
     return;
   }
@@ -384,7 +434,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   if (KTAL > 0)
     stage_cols<32 * (KTAL > 0 ? KTAL : 1), false>(reinterpret_cast<uint16_t*>(lds + V::OFF_AL), PAL, V::ENV_ROWS, no, no,
                                                     32 * KTAR, a.A, NoiseRow{}, 0.0f, 0u);
-  if constexpr (!ENVF) {
+  if constexpr (V::SMALL_LDS) {
+    stage_cols<V::NAP, false>(reinterpret_cast<uint16_t*>(lds + V::OFF_BL), V::PA, V::ENV_ROWS, no, na, 0, a.B, NoiseRow{}, 0.0f, 0u);
+  } else if constexpr (!ENVF) {
     stage_cols<32 * KC, false>(stage, PW, V::ENV_ROWS, no, na, 0, a.B, NoiseRow{}, 0.0f, 0u);
     __syncthreads();
 #pragma unroll
@@ -403,23 +455,28 @@ void rollout_mfma_kernel(const MfmaArgs a) {
   // the noise row is fetched once per individual either way)
   for (uint32_t i = blockIdx.x; i < a.N; i += gridDim.x) {
     {
+      struct { const float* theta; const void* noise; const uint32_t* noise_offs;
+               uint32_t ld, oW1, ob1, oW2, ob2, oW3, ob3, gen, k0, k1, noise_mode; float sigma; } sa;
+      sa.theta = KARG(theta); sa.noise = KARG(noise); sa.noise_offs = KARG(noise_offs); sa.ld = KARG(ld);
+      sa.oW1 = KARG(oW1); sa.ob1 = KARG(ob1); sa.oW2 = KARG(oW2); sa.ob2 = KARG(ob2); sa.oW3 = KARG(oW3); sa.ob3 = KARG(ob3);
+      sa.gen = KARG(gen); sa.k0 = KARG(k0); sa.k1 = KARG(k1); sa.noise_mode = KARG(noise_mode); sa.sigma = KARG(sigma);
       const uint32_t unit = i / per_unit, sub = i - unit * per_unit;
-      const float scale = sub ? -a.sigma : a.sigma;
+      const float scale = sub ? -sa.sigma : sa.sigma;
       NoiseRow nz;
-      nz.mode = a.noise_mode; nz.row = unit; nz.gen = a.gen; nz.k0 = a.k0; nz.k1 = a.k1;
+      nz.mode = sa.noise_mode; nz.row = unit; nz.gen = sa.gen; nz.k0 = sa.k0; nz.k1 = sa.k1;
       nz.ptr = nullptr;           // regenerated noise has no buffer
-      if (a.noise_offs) nz.ptr = table_row_base(a.noise_mode, a.noise, a.noise_offs, unit);
-      else if (a.noise_mode == 1u) nz.ptr = static_cast<const uint16_t*>(a.noise) + (size_t)unit * a.ld;
-      else if (a.noise_mode == 0u) nz.ptr = static_cast<const float*>(a.noise) + (size_t)unit * a.ld;
+      if (sa.noise_offs) nz.ptr = table_row_base(sa.noise_mode, sa.noise, sa.noise_offs, unit);
+      else if (sa.noise_mode == 1u) nz.ptr = static_cast<const uint16_t*>(sa.noise) + (size_t)unit * sa.ld;
+      else if (sa.noise_mode == 0u) nz.ptr = static_cast<const float*>(sa.noise) + (size_t)unit * sa.ld;
 
       // ---------------- perturbed policy weights -> registers ----------------
       bf16x8 W1r[MT_H][KT1], W2r[MT_H][KT_H], Wxr[ME > 0 ? ME : 1][MT_H][KT_H];
       for (int u = tid; u < NHP; u += NT) {     // biases: perturbed, bf16-rounded, kept as binary32
         float v1 = 0.0f, v2 = 0.0f;
         if (u < nh) {
-          const uint32_t i1 = a.ob1 + u, i2 = a.ob2 + u;
-          v1 = bf16_round(__fmaf_rn(scale, row_noise(nz, i1), a.theta[i1]));
-          if (ME >= 0) v2 = bf16_round(__fmaf_rn(scale, row_noise(nz, i2), a.theta[i2]));      // a single hidden layer has no second one
+          const uint32_t i1 = sa.ob1 + u, i2 = sa.ob2 + u;
+          v1 = bf16_round(__fmaf_rn(scale, row_noise(nz, i1), sa.theta[i1]));
+          if (ME >= 0) v2 = bf16_round(__fmaf_rn(scale, row_noise(nz, i2), sa.theta[i2]));      // a single hidden layer has no second one
         }
         b1s[u] = v1;
         b2s[u] = v2;
@@ -427,8 +484,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         for (int j = 0; j < ME; ++j) {          // hidden layer 3 + j: matrix, then bias, after layer 2's
           float vx = 0.0f;
           if (u < nh) {
-            const uint32_t ix = a.ob2 + (uint32_t)(j + 1) * (uint32_t)(nh * nh + nh) + u;
-            vx = bf16_round(__fmaf_rn(scale, row_noise(nz, ix), a.theta[ix]));
+            const uint32_t ix = sa.ob2 + (uint32_t)(j + 1) * (uint32_t)(nh * nh + nh) + u;
+            vx = bf16_round(__fmaf_rn(scale, row_noise(nz, ix), sa.theta[ix]));
           }
           bxs[j * NHP + u] = vx;
         }
@@ -436,17 +493,17 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       for (int c = tid; c < 16 * MT3; c += NT) {
         float v3 = 0.0f;
         if (c < na) {
-          const uint32_t i3 = a.ob3 + c;
+          const uint32_t i3 = sa.ob3 + c;
           const float e3 = row_noise(nz, i3);
-          v3 = bf16_round(__fmaf_rn(scale, e3, a.theta[i3]));
+          v3 = bf16_round(__fmaf_rn(scale, e3, sa.theta[i3]));
         }
         b3s[c] = v3;
       }
       // action-layer weights stay in LDS (read by one wavefront per tile each step)
-      stage_cols<NHP, true>(reinterpret_cast<uint16_t*>(lds + V::OFF_W3), PH, 16 * MT3, na, nh, 0, a.theta, nz, scale, a.oW3);
+      stage_cols<NHP, true>(reinterpret_cast<uint16_t*>(lds + V::OFF_W3), PH, 16 * MT3, na, nh, 0, sa.theta, nz, scale, sa.oW3);
 #pragma unroll
       for (int kr = 0; kr < (KT1 + KC - 1) / KC; ++kr) {
-        stage_cols<32 * KC, true>(stage, PW, NHP, nh, no, 32 * KC * kr, a.theta, nz, scale, a.oW1);
+        stage_cols<32 * KC, true>(stage, PW, NHP, nh, no, 32 * KC * kr, sa.theta, nz, scale, sa.oW1);
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < MT_H; ++t)
@@ -458,7 +515,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       }
 #pragma unroll
       for (int kr = 0; kr < (ME >= 0 ? KT_H / KC : 0); ++kr) {
-        stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, a.theta, nz, scale, a.oW2);
+        stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, sa.theta, nz, scale, sa.oW2);
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < MT_H; ++t)
@@ -472,8 +529,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       for (int j = 0; j < ME; ++j) {
 #pragma unroll
         for (int kr = 0; kr < KT_H / KC; ++kr) {
-          stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, a.theta, nz, scale,
-                                    a.oW2 + (uint32_t)(j + 1) * (uint32_t)(nh * nh + nh));
+          stage_cols<32 * KC, true>(stage, PW, NHP, nh, nh, 32 * KC * kr, sa.theta, nz, scale,
+                                    sa.oW2 + (uint32_t)(j + 1) * (uint32_t)(nh * nh + nh));
           __syncthreads();
 #pragma unroll
           for (int t = 0; t < MT_H; ++t)
@@ -489,15 +546,16 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       // 4g..4g+3 of the even 16-unit tile, slots 4..7 = the same rows of the odd tile (any K order is as good as another
       // as long as both operands agree), so h2 goes from the epilogue's registers into the MFMA with no exchange.
       bf16x8 W3k[V::FUSE3 ? MT3 : 1][2];
-      if constexpr (V::FUSE3) {
+      auto w3k_tile = [&](int mt, int kk) {
+        const unsigned char* src = lds + V::OFF_W3 + 2 * ((16 * mt + n) * PH + 64 * w + 32 * kk + 4 * g);
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 2 * 16);
+        return __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
+      };
+      if constexpr (V::FUSE3 && !V::SMALL_LDS) {
 #pragma unroll
         for (int mt = 0; mt < MT3; ++mt)
 #pragma unroll
-          for (int kk = 0; kk < 2; ++kk) {
-            const unsigned char* src = lds + V::OFF_W3 + 2 * ((16 * mt + n) * PH + 64 * w + 32 * kk + 4 * g);
-            const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 2 * 16);
-            W3k[mt][kk] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
-          }
+          for (int kk = 0; kk < 2; ++kk) W3k[mt][kk] = w3k_tile(mt, kk);
       }
 
       float fit_sum = 0.0f;
@@ -507,11 +565,12 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           // thread -> (column n0, row group kq): s0[k] for k = kq, kq + 16, ...
           constexpr int KG = NT / NC;                // row groups
           const int n0 = tid % NC, kq = tid / NC;
+          const uint32_t x_gen = KARG(gen), x_k0 = KARG(k0), x_k1 = KARG(k1);
           const uint32_t e0 = cb * (uint32_t)NC + (uint32_t)n0;
           float part = 0.0f;
           for (int k = kq; k < V::NOP; k += KG) {
             float v = 0.0f;
-            if (k < no && e0 < a.E) v = reset_value((uint32_t)k, e0, a.gen, a.k0, a.k1);
+            if (k < no && e0 < a.E) v = reset_value((uint32_t)k, e0, x_gen, x_k0, x_k1);
             part = __fmaf_rn(v, v, part);
             x0s[n0 * PX + k] = (uint16_t)bf16_bits(v);
             if (ENVF) reinterpret_cast<float*>(lds + V::OFF_X0F)[n0 * PXF + k] = v;
@@ -702,6 +761,12 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           }
           PSTAMP(4);
           {
+            if constexpr (V::SMALL_LDS) {      // fetched here, ahead of the activation that hides the latency
+#pragma unroll
+              for (int mt = 0; mt < MT3; ++mt)
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) W3k[mt][kk] = w3k_tile(mt, kk);
+            }
             // h2 of this wavefront's 64 units stays in registers: lane (g, 4q + c) holds units 4g..4g+3 of tile q for copy c
             const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
             const u32x2 hp = pack_bf16x4(h.x, h.y, h.z, h.w);
@@ -724,7 +789,14 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           __syncthreads();
           PSTAMP(6);
           // ---- phase D: a = tanh(sum of the partials + b3); s' = tanh(A x + B a); norms for the reward and the termination test ----
-          bf16x8 ba;
+          bf16x8 ba, brt[MTE];
+          if constexpr (V::SMALL_LDS) {
+#pragma unroll
+            for (int tt = 0; tt < MTE; ++tt) brt[tt] = lds_tile(lds, V::OFF_BL + 2 * ((16 * (w * MTE + tt) + n) * V::PA + 8 * g));
+          } else {
+#pragma unroll
+            for (int tt = 0; tt < MTE; ++tt) brt[tt] = Br[tt][0];
+          }
           {
             f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
             if (arow_ok) {
@@ -743,7 +815,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             ba = __builtin_bit_cast(bf16x8, u32x4{ap.x, ap.y, a4x, a4y});      // action rows 8g..8g+7 of column n (n < 4)
           }
 #pragma unroll
-          for (int tt = 0; tt < MTE; ++tt) accE[tt] = mfma16(Br[tt][0], ba, accE[tt]);
+          for (int tt = 0; tt < MTE; ++tt) accE[tt] = mfma16(brt[tt], ba, accE[tt]);
           PSTAMP(7);
           float ssp = 0.0f;
           unsigned mxp = 0u;
@@ -1113,13 +1185,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         if (w == 0) {
           const uint32_t cnt = min((uint32_t)NC, a.E - cb * (uint32_t)NC);
           if (g == 0 && (uint32_t)n < cnt) {
-            a.returns[(size_t)i * a.E + e] = Rn;
-            a.ep_len[(size_t)i * a.E + e] = Ln;
+            KARG(returns)[(size_t)i * a.E + e] = Rn;
+            KARG(ep_len)[(size_t)i * a.E + e] = Ln;
           }
           for (uint32_t r = 0; r < cnt; ++r) fit_sum += __shfl(Rn, (int)r, 64);
         }
       }
-      if (tid == 0) a.fitness[i] = fit_sum / (float)a.E;
+      if (tid == 0) KARG(fitness)[i] = fit_sum / (float)a.E;
     }
   }
 }
