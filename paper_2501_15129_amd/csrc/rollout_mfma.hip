@@ -140,7 +140,11 @@ struct Variant {
   // distinct banks), working buffer and cached initial value
   static constexpr int KPL = NOP / 4;          // state elements per lane group of the fp32 MFMA's K dimension
   static constexpr int PXF = NOP + 4;
-  static constexpr int OFF_XF = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : 0);
+  // passes of sixteen copies, one action tile (KSPLIT16): the same K split of the action layer; every lane keeps its four
+  // hidden tiles of its own column, so h2 feeds the MFMA with no lane exchange at all.  Partials [wavefront][copy][PP3 rows].
+  static constexpr bool KSPLIT16 = NC_ == 16 && ME_ == 0 && NW_ == 4 && MT3_ == 1;
+  static constexpr int PP3 = 20;               // pitch (floats) of a copy's 16 partial rows: 16-byte accesses of 16 lanes spread over the banks
+  static constexpr int OFF_XF = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : KSPLIT16 ? 4 * NW * 16 * PP3 : 0);
   static constexpr int OFF_X0F = OFF_XF + (ENVF ? 4 * NC * PXF : 0);
   // With all of A in registers the step loop has under a hundred working registers left: B and this wavefront's slice
   // of the action-layer weights then stay in LDS and are fetched where they are used (a dozen reads per step).
@@ -444,6 +448,15 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 #pragma unroll
       for (int kt = 0; kt < KTA; ++kt)
         Br[t][kt] = lds_tile(lds, 2 * ((16 * (w * MTE + t) + n) * PW + 32 * kt + 8 * g));
+    if constexpr (V::KSPLIT16) {
+      // K slot j < 4 of lane group g stands for action row 4g + j - the rows whose sums the lane holds after the action
+      // layer - and slots 4..7 are padding: the action goes from those registers into the MFMA
+#pragma unroll
+      for (int t = 0; t < MTE; ++t) {
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(lds + 2 * ((16 * (w * MTE + t) + n) * PW + 4 * g));
+        Br[t][0] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, 0u, 0u});
+      }
+    }
     __syncthreads();
   }
 
@@ -545,13 +558,13 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       // order inside a tile follows the order in which the lane holds h2 after the layer-2 epilogue: slots 0..3 = units
       // 4g..4g+3 of the even 16-unit tile, slots 4..7 = the same rows of the odd tile (any K order is as good as another
       // as long as both operands agree), so h2 goes from the epilogue's registers into the MFMA with no exchange.
-      bf16x8 W3k[V::FUSE3 ? MT3 : 1][2];
+      bf16x8 W3k[(V::FUSE3 || V::KSPLIT16) ? MT3 : 1][2];
       auto w3k_tile = [&](int mt, int kk) {
         const unsigned char* src = lds + V::OFF_W3 + 2 * ((16 * mt + n) * PH + 64 * w + 32 * kk + 4 * g);
         const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 2 * 16);
         return __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
       };
-      if constexpr (V::FUSE3 && !V::SMALL_LDS) {
+      if constexpr ((V::FUSE3 && !V::SMALL_LDS) || V::KSPLIT16) {
 #pragma unroll
         for (int mt = 0; mt < MT3; ++mt)
 #pragma unroll
@@ -996,6 +1009,21 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
               if (q < MT_H)
                 *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            } else if constexpr (V::KSPLIT16) {
+              // h2 stays in registers: the lane's values of tiles 0, 1 and of tiles 2, 3 are the two K tiles of this
+              // wavefront's slice of the action layer; only the binary32 partial sums cross the LDS
+              u32x2 hp[MT_H];
+#pragma unroll
+              for (int tt = 0; tt < MT_H; ++tt) {
+                const f32x4 h = hidden4<RELU>(acc[tt]);
+                hp[tt] = pack_bf16x4(h.x, h.y, h.z, h.w);
+              }
+              static_assert(!V::KSPLIT16 || MT_H == 4, "four hidden tiles per wavefront");
+              const bf16x8 bk0 = __builtin_bit_cast(bf16x8, u32x4{hp[0].x, hp[0].y, hp[1 % MT_H].x, hp[1 % MT_H].y});
+              const bf16x8 bk1 = __builtin_bit_cast(bf16x8, u32x4{hp[2 % MT_H].x, hp[2 % MT_H].y, hp[3 % MT_H].x, hp[3 % MT_H].y});
+              f32x4 p3 = mfma16(W3k[0][0], bk0, f32x4{0.f, 0.f, 0.f, 0.f});
+              p3 = mfma16(W3k[0][1], bk1, p3);
+              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(lds + V::OFF_P3) + (w * 16 + n) * V::PP3 + 4 * g) = p3;
             } else {
 #pragma unroll
               for (int tt = 0; tt < MT_H; ++tt) {
@@ -1051,7 +1079,23 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           PSTAMP(6);
           // ---- phase C: a = tanh(W3 h2 + b3), weights from LDS ----
           unsigned char* qaw = lds + V::OFF_QA + (V::ACT_SPLIT ? 0 : w * (2 * NC * PA));   // action buffer read below
-          if (V::ACT_SPLIT) {
+          bf16x8 ba16 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});   // KSPLIT16: the action as a B operand, from registers
+          if constexpr (V::KSPLIT16) {
+            // every lane adds the four wavefronts' partials of rows 4g..4g+3 of its column, in the same order everywhere
+            const float* p3s = reinterpret_cast<const float*>(lds + V::OFF_P3);
+            f32x4 v = *reinterpret_cast<const f32x4*>(b3s + 4 * g);
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) v += *reinterpret_cast<const f32x4*>(p3s + (ww * 16 + n) * V::PP3 + 4 * g);
+            if (a.out_tanh) v = tanh4(v);
+            float part = v.x * v.x;
+            part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+            aa_prev = rows_sum(part);
+            if (ENVF) av = v;
+            else {
+              const u32x2 ap = pack_bf16x4(v.x, v.y, v.z, v.w);
+              ba16 = __builtin_bit_cast(bf16x8, u32x4{ap.x, ap.y, 0u, 0u});
+            }
+          } else if (V::ACT_SPLIT) {
             if (w < MT3) {     // wavefront mt computes action tile mt
               p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -1139,7 +1183,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             } else {
 #pragma unroll
               for (int kt = 0; kt < KTA; ++kt) {
-                const bf16x8 b = lds_tile(qaw, 2 * (n * PA + 32 * kt + 8 * g));
+                const bf16x8 b = V::KSPLIT16 ? ba16 : lds_tile(qaw, 2 * (n * PA + 32 * kt + 8 * g));
 #pragma unroll
                 for (int tt = 0; tt < MTE; ++tt)
                   if (ENV_ALL || 16 * (w * MTE + tt) < V::NOP) accE[tt] = mfma16(Br[tt][kt], b, accE[tt]);
