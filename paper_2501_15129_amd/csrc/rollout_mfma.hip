@@ -89,10 +89,6 @@ struct Variant {
   static constexpr int MT_H = NHP / (16 * NW);   // 16-row tiles of a wide layer per wavefront
   static constexpr int ENV_ROWS = 16 * NW * MTE_;   // padded rows of the next-state vector covered by the workgroup
   static constexpr int NC = NC_;              // environment copies per pass: 16, or 4 with column compaction
-  // One 16-row action tile: every wavefront computes it (no exchange before the environment
-  // step).  Two tiles: wavefront mt computes tile mt and the action goes through LDS, because
-  // the replicated version quadruples the LDS traffic of the weight tiles, which then dominates.
-  static constexpr bool ACT_SPLIT = MT3_ > 1;
   static constexpr int KT1 = KT1_;            // K tiles over the (padded) observation width
   static constexpr int MT3 = MT3_;            // 16-row tiles of the action layer
   static constexpr int MTE = MTE_;            // 16-row tiles of the next-state vector per wavefront
@@ -111,8 +107,7 @@ struct Variant {
   static constexpr int OFF_QA = OFF_H2 + 2 * NC * PH;
   static constexpr int OFF_SSP = OFF_QA + NW * 2 * NC * PA; // (one action buffer per wavefront) |s'|^2 partials [column][wavefront]
   static constexpr int OFF_MXP = OFF_SSP + 4 * 16 * NW;     // max|s'| partials, same layout
-  static constexpr int OFF_AAP = OFF_MXP + 4 * 16 * NW;     // |a|^2 partials [column][action tile] (split action layer only)
-  static constexpr int OFF_SCR = OFF_AAP + 4 * 16 * 2;     // scratch for the initial-state norms
+  static constexpr int OFF_SCR = OFF_MXP + 4 * 16 * NW;     // scratch for the initial-state norms
   static constexpr int ROLL_END = OFF_SCR + 4 * NT;
   static constexpr int WIN_BYTES = 2 * 256 * PW;
   static constexpr int REGION0 = ROLL_END > WIN_BYTES ? ROLL_END : WIN_BYTES;
@@ -140,10 +135,11 @@ struct Variant {
   // distinct banks), working buffer and cached initial value
   static constexpr int KPL = NOP / 4;          // state elements per lane group of the fp32 MFMA's K dimension
   static constexpr int PXF = NOP + 4;
-  // passes of sixteen copies, one action tile (KSPLIT16): the same K split of the action layer; every lane keeps its four
-  // hidden tiles of its own column, so h2 feeds the MFMA with no lane exchange at all.  Partials [wavefront][copy][PP3 rows].
-  static constexpr bool KSPLIT16 = NC_ == 16 && ME_ == 0 && NW_ == 4 && MT3_ == 1;
-  static constexpr int PP3 = 20;               // pitch (floats) of a copy's 16 partial rows: 16-byte accesses of 16 lanes spread over the banks
+  // passes of sixteen copies (KSPLIT16): the same K split of the action layer, at any depth; every lane keeps its four tiles of
+  // the last hidden layer for its own column, so they feed the MFMA with no lane exchange at all.
+  // Partials [wavefront][copy][PP3 rows].
+  static constexpr bool KSPLIT16 = NC_ == 16 && NW_ == 4;
+  static constexpr int PP3 = 16 * MT3_ + 4;    // pitch (floats) of a copy's partial rows: 16-byte accesses of 16 lanes spread over the banks
   static constexpr int OFF_XF = OFF_P3 + (FUSE3 ? 4 * NW * NC * 32 : KSPLIT16 ? 4 * NW * 16 * PP3 : 0);
   static constexpr int OFF_X0F = OFF_XF + (ENVF ? 4 * NC * PXF : 0);
   // With all of A in registers the step loop has under a hundred working registers left: B and this wavefront's slice
@@ -449,12 +445,16 @@ void rollout_mfma_kernel(const MfmaArgs a) {
       for (int kt = 0; kt < KTA; ++kt)
         Br[t][kt] = lds_tile(lds, 2 * ((16 * (w * MTE + t) + n) * PW + 32 * kt + 8 * g));
     if constexpr (V::KSPLIT16) {
-      // K slot j < 4 of lane group g stands for action row 4g + j - the rows whose sums the lane holds after the action
-      // layer - and slots 4..7 are padding: the action goes from those registers into the MFMA
+      // K slot j < 4 of lane group g stands for action row 4g + j, slot j >= 4 for row 16 + 4g + (j - 4) of the second
+      // action tile (padding when there is one tile) - the rows whose sums the lane holds after the action layer: the
+      // action goes from those registers into the MFMA
 #pragma unroll
       for (int t = 0; t < MTE; ++t) {
-        const u32x2 lo = *reinterpret_cast<const u32x2*>(lds + 2 * ((16 * (w * MTE + t) + n) * PW + 4 * g));
-        Br[t][0] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, 0u, 0u});
+        const unsigned char* src = lds + 2 * ((16 * (w * MTE + t) + n) * PW + 4 * g);
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(src);
+        u32x2 hi = u32x2{0u, 0u};                                   // second action tile: rows 16 + 4g + (j - 4) in slots 4..7
+        if (MT3 > 1) hi = *reinterpret_cast<const u32x2*>(src + 2 * 16);
+        Br[t][0] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
       }
     }
     __syncthreads();
@@ -564,7 +564,10 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         const u32x2 lo = *reinterpret_cast<const u32x2*>(src), hi = *reinterpret_cast<const u32x2*>(src + 2 * 16);
         return __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
       };
-      if constexpr ((V::FUSE3 && !V::SMALL_LDS) || V::KSPLIT16) {
+      // ... held in registers where the file has room for them; fetched from LDS at their use otherwise (all of A in
+      // registers, two workgroups per CU, more than two hidden layers)
+      constexpr bool W3K_REGS = (V::FUSE3 && !V::SMALL_LDS) || V::KSPLIT16;
+      if constexpr (W3K_REGS) {
 #pragma unroll
         for (int mt = 0; mt < MT3; ++mt)
 #pragma unroll
@@ -636,8 +639,6 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           float* sp = reinterpret_cast<float*>(lds + V::OFF_SSP) + tid * NW;
           unsigned* mp = reinterpret_cast<unsigned*>(lds + V::OFF_MXP) + tid * NW;
           for (int r = 0; r < NW; ++r) { sp[r] = 0.0f; mp[r] = 0u; }
-          reinterpret_cast<float*>(lds + V::OFF_AAP)[tid * 2] = 0.0f;
-          reinterpret_cast<float*>(lds + V::OFF_AAP)[tid * 2 + 1] = 0.0f;
           if (tid < NC) sp[0] = ss0s[tid];
         }
         __syncthreads();
@@ -649,6 +650,31 @@ void rollout_mfma_kernel(const MfmaArgs a) {
         unsigned long long prof_acc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         unsigned long long prof_last = __builtin_readcyclecounter();
 #endif
+        // KSPLIT16, after the last hidden layer: it stays in registers - the lane's values of tiles 0, 1 and of tiles 2, 3 are
+        // the two K tiles of this wavefront's slice of the action layer - and only the binary32 partial sums cross the LDS
+        auto last_hidden_ksplit = [&](const f32x4 (&accs)[MT_H]) {
+          static_assert(!V::KSPLIT16 || MT_H == 4, "four hidden tiles per wavefront");
+          if constexpr (!W3K_REGS) {      // requested ahead of the activation, which hides the latency
+#pragma unroll
+            for (int mt = 0; mt < MT3; ++mt)
+#pragma unroll
+              for (int kk = 0; kk < 2; ++kk) W3k[mt][kk] = w3k_tile(mt, kk);
+          }
+          u32x2 hp[MT_H];
+#pragma unroll
+          for (int tt = 0; tt < MT_H; ++tt) {
+            const f32x4 h = hidden4<RELU>(accs[tt]);
+            hp[tt] = pack_bf16x4(h.x, h.y, h.z, h.w);
+          }
+          const bf16x8 bk0 = __builtin_bit_cast(bf16x8, u32x4{hp[0].x, hp[0].y, hp[1 % MT_H].x, hp[1 % MT_H].y});
+          const bf16x8 bk1 = __builtin_bit_cast(bf16x8, u32x4{hp[2 % MT_H].x, hp[2 % MT_H].y, hp[3 % MT_H].x, hp[3 % MT_H].y});
+#pragma unroll
+          for (int mt = 0; mt < MT3; ++mt) {
+            f32x4 p3 = mfma16(W3k[mt][0], bk0, f32x4{0.f, 0.f, 0.f, 0.f});
+            p3 = mfma16(W3k[mt][1], bk1, p3);
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(lds + V::OFF_P3) + (w * 16 + n) * V::PP3 + 16 * mt + 4 * g) = p3;
+          }
+        };
         if constexpr (V::FUSE3) {
         // Passes of four copies, two hidden layers (FUSE3): the action layer is split along K.  Every wavefront multiplies
         // the 64 units of h2 it has just produced - still in its registers - with its slice of the action-layer weights;
@@ -867,7 +893,6 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           const u32x4 mp4 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col);
           const f32x4 sp8 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col + (NW > 4 ? 16 : 0));
           const u32x4 mp8 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col + (NW > 4 ? 16 : 0));
-          const f32x2 ap2 = *reinterpret_cast<const f32x2*>(lds + V::OFF_AAP + 8 * col);
           float xf[ENVF ? KPL : 1];                 // binary32 environment: this lane's state operands, elements KPL g .. of column n
           if constexpr (ENVF) {
 #pragma unroll
@@ -912,7 +937,7 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             mxb = umax(mxb, umax(umax(mp8.x, mp8.y), umax(mp8.z, mp8.w)));
           }
           const float mx = __builtin_bit_cast(float, mxb);
-          const float aa = V::ACT_SPLIT ? ap2.x + ap2.y : aa_prev;
+          const float aa = aa_prev;
           if (!first) {
             if (alive) {
               Rn += __fmaf_rn(-ss_cur, inv_no, 1.0f) - a.act_cost * aa;
@@ -948,6 +973,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
             const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
             if (q < MT_H)
               *reinterpret_cast<u32x2*>(lds + V::OFF_H1 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+          } else if constexpr (V::KSPLIT16 && ME < 0) {
+            last_hidden_ksplit(acc);
           } else {
 #pragma unroll
             for (int tt = 0; tt < MT_H; ++tt) {
@@ -1009,21 +1036,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
               if (q < MT_H)
                 *reinterpret_cast<u32x2*>(lds + V::OFF_H2 + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
-            } else if constexpr (V::KSPLIT16) {
-              // h2 stays in registers: the lane's values of tiles 0, 1 and of tiles 2, 3 are the two K tiles of this
-              // wavefront's slice of the action layer; only the binary32 partial sums cross the LDS
-              u32x2 hp[MT_H];
-#pragma unroll
-              for (int tt = 0; tt < MT_H; ++tt) {
-                const f32x4 h = hidden4<RELU>(acc[tt]);
-                hp[tt] = pack_bf16x4(h.x, h.y, h.z, h.w);
-              }
-              static_assert(!V::KSPLIT16 || MT_H == 4, "four hidden tiles per wavefront");
-              const bf16x8 bk0 = __builtin_bit_cast(bf16x8, u32x4{hp[0].x, hp[0].y, hp[1 % MT_H].x, hp[1 % MT_H].y});
-              const bf16x8 bk1 = __builtin_bit_cast(bf16x8, u32x4{hp[2 % MT_H].x, hp[2 % MT_H].y, hp[3 % MT_H].x, hp[3 % MT_H].y});
-              f32x4 p3 = mfma16(W3k[0][0], bk0, f32x4{0.f, 0.f, 0.f, 0.f});
-              p3 = mfma16(W3k[0][1], bk1, p3);
-              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(lds + V::OFF_P3) + (w * 16 + n) * V::PP3 + 4 * g) = p3;
+            } else if constexpr (V::KSPLIT16 && ME == 0) {
+              last_hidden_ksplit(acc);
             } else {
 #pragma unroll
               for (int tt = 0; tt < MT_H; ++tt) {
@@ -1057,6 +1071,8 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               const f32x4 h = hidden4<RELU>(compact4<MT_H>(acc));
               if (q < MT_H)
                 *reinterpret_cast<u32x2*>(lds + off_out + 2 * (col * PH + 16 * (w * MT_H + q) + 4 * g)) = pack_bf16x4(h.x, h.y, h.z, h.w);
+            } else if (V::KSPLIT16 && j == ME - 1) {
+              last_hidden_ksplit(acc);
             } else {
 #pragma unroll
               for (int tt = 0; tt < MT_H; ++tt) {
@@ -1065,59 +1081,34 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               }
             }
           }
-          // action-layer operands that do not depend on h2 are fetched before the barrier (split mode)
-          constexpr int W3PRE = 4;       // of the KT_H weight tiles; the register file has no room for all of them
-          bf16x8 w3t[V::ACT_SPLIT ? W3PRE : 1];
-          f32x4 p[4];
-          if (V::ACT_SPLIT && w < MT3) {
-#pragma unroll
-            for (int kt = 0; kt < W3PRE; ++kt) w3t[kt] = lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
-            p[0] = *reinterpret_cast<const f32x4*>(b3s + 16 * w + 4 * g);
-          }
           PSTAMP(5);
           __syncthreads();
           PSTAMP(6);
           // ---- phase C: a = tanh(W3 h2 + b3), weights from LDS ----
-          unsigned char* qaw = lds + V::OFF_QA + (V::ACT_SPLIT ? 0 : w * (2 * NC * PA));   // action buffer read below
+          unsigned char* qaw = lds + V::OFF_QA + w * (2 * NC * PA);   // this wavefront's action buffer (four-copy passes of the other depths)
           bf16x8 ba16 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});   // KSPLIT16: the action as a B operand, from registers
           if constexpr (V::KSPLIT16) {
-            // every lane adds the four wavefronts' partials of rows 4g..4g+3 of its column, in the same order everywhere
+            // every lane adds the four wavefronts' partials of rows 4g..4g+3 (of every action tile) of its column, in the same order everywhere
             const float* p3s = reinterpret_cast<const float*>(lds + V::OFF_P3);
-            f32x4 v = *reinterpret_cast<const f32x4*>(b3s + 4 * g);
+            f32x4 v[MT3];
+            float part = 0.0f;
 #pragma unroll
-            for (int ww = 0; ww < NW; ++ww) v += *reinterpret_cast<const f32x4*>(p3s + (ww * 16 + n) * V::PP3 + 4 * g);
-            if (a.out_tanh) v = tanh4(v);
-            float part = v.x * v.x;
-            part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
+            for (int mt = 0; mt < MT3; ++mt) {
+              v[mt] = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
+#pragma unroll
+              for (int ww = 0; ww < NW; ++ww) v[mt] += *reinterpret_cast<const f32x4*>(p3s + (ww * 16 + n) * V::PP3 + 16 * mt + 4 * g);
+              if (a.out_tanh) v[mt] = tanh4(v[mt]);
+              part = __fmaf_rn(v[mt].x, v[mt].x, part); part = __fmaf_rn(v[mt].y, v[mt].y, part);
+              part = __fmaf_rn(v[mt].z, v[mt].z, part); part = __fmaf_rn(v[mt].w, v[mt].w, part);
+            }
             aa_prev = rows_sum(part);
-            if (ENVF) av = v;
+            if (ENVF) av = v[0];
             else {
-              const u32x2 ap = pack_bf16x4(v.x, v.y, v.z, v.w);
-              ba16 = __builtin_bit_cast(bf16x8, u32x4{ap.x, ap.y, 0u, 0u});
+              const u32x2 lo = pack_bf16x4(v[0].x, v[0].y, v[0].z, v[0].w);
+              u32x2 hi = u32x2{0u, 0u};
+              if (MT3 > 1) hi = pack_bf16x4(v[MT3 - 1].x, v[MT3 - 1].y, v[MT3 - 1].z, v[MT3 - 1].w);
+              ba16 = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
             }
-          } else if (V::ACT_SPLIT) {
-            if (w < MT3) {     // wavefront mt computes action tile mt
-              p[1] = p[2] = p[3] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-              for (int kt = 0; kt < KT_H; ++kt) {
-                const bf16x8 b = lds_tile(lds, V::OFF_HL + 2 * (col * PH + 32 * kt + 8 * g));
-                const bf16x8 wt = kt < W3PRE ? w3t[kt < W3PRE ? kt : 0]
-                                             : lds_tile(lds, V::OFF_W3 + 2 * ((16 * w + n) * PH + 32 * kt + 8 * g));
-                p[kt & 3] = mfma16(wt, b, p[kt & 3]);
-              }
-              f32x4 v = (p[0] + p[1]) + (p[2] + p[3]);
-              if (a.out_tanh) v = tanh4(v);
-              float part = v.x * v.x;
-              part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
-              part = rows_sum(part);
-              if (n < NC) {     // with 4-column passes the lanes of columns 4..15 hold copies
-                *reinterpret_cast<u32x2*>(qaw + 2 * (col * PA + 16 * w + 4 * g)) = pack_bf16x4(v.x, v.y, v.z, v.w);
-                if (g == 0) reinterpret_cast<float*>(lds + V::OFF_AAP)[col * 2 + w] = part;
-              }
-            }
-            PSTAMP(7);
-            __syncthreads();
-            PSTAMP(8);
           } else {
             // every wavefront computes the single action tile itself: no exchange before the environment step
             f32x4 p[MT3][2];
@@ -1243,7 +1234,9 @@ void rollout_mfma_kernel(const MfmaArgs a) {
 constexpr int env_tiles(int nop, int nw) { return (nop / 16 + nw - 1) / nw > 0 ? (nop / 16 + nw - 1) / nw : 1; }
 // The smallest-observation variant leaves half of the register file free: two workgroups (two
 // individuals) share a CU and hide each other's LDS round trips and barriers (1.5x at obs 27).
-template <int NC, int NW> using V32 = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2>;   // obs <= 32,  act <= 16
+// (Passes of sixteen copies: A stays in LDS - with two workgroups per CU the register file has no four registers to spare
+// for its tile, and a spilled tile would be reloaded from scratch memory every step.)
+template <int NC, int NW> using V32 = Variant<1, 1, env_tiles(32, NW), NC == 16 ? 0 : 1, NC, NW, 2>;   // obs <= 32,  act <= 16
 template <int NC, int NW> using V64 = Variant<2, 1, env_tiles(64, NW), 2, NC, NW>;      // obs <= 64,  act <= 16
 // the same two shapes with the environment's products in binary32 (es_config.env_dtype = 1)
 template <int NC, int NW> using V32F = Variant<1, 1, env_tiles(32, NW), 1, NC, NW, 2, 0, true>;
