@@ -71,9 +71,7 @@ constexpr int NHP = 256;          // padded hidden width handled by this kernel
 constexpr int KT_H = NHP / 32;    // 32-deep K tiles over the hidden width
 constexpr int PH = NHP + 8;       // LDS pitch (bf16 elements) of a hidden activation row
 
-#ifndef ES_STAGE_UNROLL
-#define ES_STAGE_UNROLL 8     // staging iterations whose loads are in flight together
-#endif
+constexpr int STAGE_BATCH = 8;    // staging iterations whose loads are in flight together (4: 24 % slower staging, 16: spills)
 constexpr int KC = 2;             // K tiles staged per round
 constexpr int PW = 32 * KC + 8;   // LDS pitch of the staging window
 
@@ -84,7 +82,7 @@ struct Variant {
   static constexpr int ME = ME_;              // hidden layers beyond the second (depth m = 2 + ME), each 256 x 256 in registers;
                                               // -1: a single hidden layer (the second layer's phase is skipped)
   static constexpr int OCC = OCC_;            // workgroups per CU the register budget is sized for (1 or 2)
-  static constexpr int NW = NW_;              // wavefronts per workgroup: 4 (one per SIMD) or 8 (two per SIMD)
+  static constexpr int NW = NW_;              // wavefronts per workgroup: one per SIMD
   static constexpr int NT = 64 * NW;          // threads per workgroup
   static constexpr int MT_H = NHP / (16 * NW);   // 16-row tiles of a wide layer per wavefront
   static constexpr int ENV_ROWS = 16 * NW * MTE_;   // padded rows of the next-state vector covered by the workgroup
@@ -150,7 +148,7 @@ struct Variant {
   static_assert(!ENVF || (NC == 16 && ME == 0 && MT3 == 1 && KT1 <= 2), "binary32 environment: passes of 16 copies, two hidden layers, obs <= 64, act <= 16");
   static_assert(ENV_ROWS >= NOP, "the wavefronts must cover the padded state");
   static_assert(ENV_ROWS <= 256, "staging window rows");
-  static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
+  static_assert(NW == 4, "one wavefront per SIMD (two per SIMD, each with half of the rows, measured slower at every shape)");
   static_assert(MT_H >= 1 && MT_H <= 4, "wide-layer tiles per wavefront");
   static_assert(NAP >= 16 * MT3 && KTA <= KC, "action K padding");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -295,7 +293,7 @@ __device__ __forceinline__ void stage_cols(uint16_t* dst, int pitch, int rows_p,
     const int total = rows_p * C4;
     const int step = (int)blockDim.x;
     auto batch = [&](auto fetch) {
-      constexpr int U = ES_STAGE_UNROLL;
+      constexpr int U = STAGE_BATCH;
       for (int q0 = threadIdx.x; q0 < total; q0 += U * step) {
         f32x4 tv[U];
         decltype(fetch(0u)) ev[U];
@@ -891,8 +889,6 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           // partial norms of the previous step, one per wavefront (consumed after the MFMA stream below)
           const f32x4 sp4 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col);
           const u32x4 mp4 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col);
-          const f32x4 sp8 = *reinterpret_cast<const f32x4*>(lds + V::OFF_SSP + 4 * NW * col + (NW > 4 ? 16 : 0));
-          const u32x4 mp8 = *reinterpret_cast<const u32x4*>(lds + V::OFF_MXP + 4 * NW * col + (NW > 4 ? 16 : 0));
           float xf[ENVF ? KPL : 1];                 // binary32 environment: this lane's state operands, elements KPL g .. of column n
           if constexpr (ENVF) {
 #pragma unroll
@@ -932,10 +928,6 @@ void rollout_mfma_kernel(const MfmaArgs a) {
           // every lane combines the four wavefronts' partials of its column in the same fixed order
           float ss_new = (sp4.x + sp4.y) + (sp4.z + sp4.w);
           unsigned mxb = umax(umax(mp4.x, mp4.y), umax(mp4.z, mp4.w));
-          if (NW > 4) {
-            ss_new += (sp8.x + sp8.y) + (sp8.z + sp8.w);
-            mxb = umax(mxb, umax(umax(mp8.x, mp8.y), umax(mp8.z, mp8.w)));
-          }
           const float mx = __builtin_bit_cast(float, mxb);
           const float aa = aa_prev;
           if (!first) {
