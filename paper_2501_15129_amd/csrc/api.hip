@@ -137,7 +137,7 @@ int es_create(const es_config* cfg, es_ctx** out) {
     ctx->kernel_name = reg_variant_name(ctx->reg_variant, c.dtype == 1);
   } else if (mfma_f32_fits(c)) {
     ctx->rollout_kind = ROLLOUT_MFMA_F32;
-    ctx->kernel_name = c.obs_dim <= 32 ? "rollout_mfma_reg_f32<obs32,hid256,act16>" : "rollout_mfma_reg_f32<obs64,hid256,act16>";
+    ctx->kernel_name = mfma_f32_variant_name(c, ctx->shp.E);
   } else if (ctx->mfma_variant >= 0) {
     ctx->rollout_kind = ROLLOUT_MFMA_REG;
     ctx->kernel_name = mfma_variant_name(ctx->mfma_variant);

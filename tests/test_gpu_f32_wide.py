@@ -33,12 +33,12 @@ def _case(es, w, gen=1, obs_norm=None):
     if obs_norm is not None:
         keep = (dev(obs_norm[0]), dev(obs_norm[1]))
         ctx.set_obs_norm(*keep)
-    ws = replace(w, noise_dtype=w.noise_dtype & 1) if w.noise_dtype < 4 else replace(w, noise_dtype=0)
+    ws = replace(w, noise_dtype=w.noise_dtype & 1)
     if ctx.noise_table:
         noise = ctx.alloc_noise()
         ctx.build_noise_table(noise)
         ctx.sample_population(gen, noise)
-        eps = oracle.table_rows(w, gen, w.noise_table_len, ctx.noise_ld, False)
+        eps = oracle.table_rows(w, gen, w.noise_table_len, ctx.noise_ld, w.noise_dtype == 5)
     else:
         eps = oracle.sample_population(ws, gen)
         noise = None if ctx.noise_regenerated else noise_to_device(ctx, eps)
@@ -66,13 +66,32 @@ def _case(es, w, gen=1, obs_norm=None):
     replace(BASE, name="f32w-table", noise_dtype=4, noise_table_len=1 << 18, envs=4),
     replace(BASE, name="f32w-k3", envs=3, episodes=3),
     replace(BASE, name="f32w-N300", pop=300, envs=2, horizon=5),
+    # the four-copy variant (4x4x1 matrix-core shape, up to eight copies per individual): every observation width class,
+    # one and two passes, ragged last pass, several episodes per copy, termination inside an episode, bf16 noise
+    replace(BASE, name="f32n-16-256-8-E4", obs=16, envs=4, horizon=50),
+    replace(BASE, name="f32n-17-130-5-E8", obs=17, hid=130, act=5, envs=8),
+    replace(BASE, name="f32n-32-256-16-E7", obs=32, act=16, envs=7),
+    replace(BASE, name="f32n-64-256-16-E6-relu", obs=64, act=16, envs=6, hidden_act=1),
+    replace(BASE, name="f32n-48-255-9-k2", obs=48, hid=255, act=9, envs=3, episodes=2),
+    replace(BASE, name="f32n-len1", envs=4, done_thresh=1e-6),
+    replace(BASE, name="f32n-T1", envs=2, horizon=1),
+    replace(BASE, name="f32n-fixedlen-bf16noise", envs=4, done_thresh=math.inf, horizon=80, noise_dtype=1),
+    replace(BASE, name="f32n-table-bf16", noise_dtype=5, noise_table_len=1 << 18, envs=3),
+    replace(BASE, name="f32n-regen-rounded", noise_dtype=3, envs=5),
 ], ids=lambda w: w.name)
 def test_rollout_f32_wide(es, w):
     _case(es, w)
 
 
+def test_four_copy_variant_is_chosen_up_to_eight_copies(es):
+    for envs, episodes, narrow in ((1, 1, True), (4, 2, True), (8, 1, True), (3, 3, False), (16, 1, False)):
+        ctx = es.EsContext(replace(BASE, envs=envs, episodes=episodes))
+        assert ("copies4" in ctx.rollout_kernel) == narrow, (envs, episodes, ctx.rollout_kernel)
+
+
 def test_rollout_f32_wide_with_observation_statistics(es):
-    for w in (replace(BASE, name="f32w-norm"), replace(BASE, name="f32w-norm-60-relu", obs=60, hid=160, act=5, hidden_act=1)):
+    for w in (replace(BASE, name="f32w-norm"), replace(BASE, name="f32w-norm-60-relu", obs=60, hid=160, act=5, hidden_act=1),
+              replace(BASE, name="f32n-norm", envs=4), replace(BASE, name="f32n-norm-60-relu-E5", obs=60, hid=160, act=5, hidden_act=1, envs=5)):
         rng = np.random.default_rng(w.seed)
         mean = (rng.standard_normal(w.obs) * 0.05).astype(np.float32)
         inv = (1.0 / (0.33 + rng.random(w.obs) * 0.67)).astype(np.float32)
