@@ -308,9 +308,13 @@ def main() -> int:
     if "mfma" in ctx.rollout_kernel:
         # the environment copies are the 16 columns of the matrix-core tile: with fewer episodes per individual only
         # that share of every MFMA is algorithmic work, whatever the kernel does
-        cols = min(16, ctx.episodes) if ctx.episodes <= 16 else ctx.episodes / (16 * ((ctx.episodes + 15) // 16)) * 16
-        roofline["column_ceiling"] = cols / 16.0
-        roofline["frac_of_column_ceiling"] = (ach / peak) / (cols / 16.0)
+        # (the four-copy binary32 kernel uses the 4x4x1 shape: four columns per pass)
+        width = 4 if "copies4" in ctx.rollout_kernel else 16
+        passes = (ctx.episodes + width - 1) // width
+        share = ctx.episodes / (width * passes)
+        roofline["column_ceiling"] = share
+        roofline["frac_of_column_ceiling"] = (ach / peak) / share
+        roofline["columns_per_pass"] = width
     plain = (args.noise_dtype is None and args.algorithm == "openes" and args.hidden_act == "tanh" and not args.obs_norm
              and args.episodes_per_env == 1 and args.num_hidden == 2 and not args.paper_base and args.pop is None
              and not args.no_antithetic and not args.env_f32)
