@@ -12,11 +12,17 @@
 //   * Each wavefront owns 64 output units (four 16-row tiles) of every wide layer; the
 //     environment copies are the 16 columns of the MFMA.  Activations travel between
 //     wavefronts as bf16 through LDS ([column][unit], padded pitch, 16-byte reads).
-//   * The narrow 256 -> act layer is read from LDS and computed by one wavefront per 16-row
-//     tile; reward norms and the termination test are reduced through per-wavefront LDS
-//     partials that every lane adds in the same fixed order, so reruns are bit-identical.
+//   * The narrow 256 -> act layer is split along K: any K order is as good as another as long
+//     as both MFMA operands agree, so every wavefront multiplies the 64 units of the last
+//     hidden layer it has just produced - still in its registers - with its slice of the
+//     action-layer weights, and only the binary32 partial sums cross the LDS (passes of four
+//     copies with two hidden layers, and every pass of sixteen copies; the remaining four-copy
+//     variants exchange the last hidden layer and every wavefront computes the one action tile).
+//     Reward norms and the termination test are reduced through per-wavefront LDS partials;
+//     every lane adds partials in the same fixed order, so reruns are bit-identical.
 //   * The grid is persistent: workgroup b handles individuals b, b + grid, ...
-// Bound: MFMA issue (dense 16x16x32 bf16) plus the tanh epilogue on the vector ALU.
+// Bound: the dependent chain of a step (MFMA streams, activation epilogues on the vector ALU,
+// three LDS hand-overs) in one in-order wavefront per SIMD; two where the register file allows.
 #include "es_device.hpp"
 #include "es_internal.hpp"
 
