@@ -101,14 +101,16 @@ def test_rollout_f32_wide_with_observation_statistics(es):
 def test_rollout_f32_wide_sigma_zero_and_rerun(es):
     got = _case(es, replace(BASE, name="f32w-sigma0", sigma=0.0))
     assert np.all(got[2].view(np.uint32) == got[2].view(np.uint32)[0])
-    w = BASE
-    a_mat, b_mat, theta = make_inputs(w)
-    ctx = es.EsContext(w)
-    nd = noise_to_device(ctx, oracle.sample_population(w, 0))
-    a = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
-    b = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
-    for x, y in zip(a, b):
-        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    for w in (BASE, replace(BASE, name="f32n-rerun", envs=4), replace(BASE, name="f32n-rerun-two-passes", obs=50, envs=7)):
+        a_mat, b_mat, theta = make_inputs(w)
+        ctx = es.EsContext(w)
+        nd = noise_to_device(ctx, oracle.sample_population(w, 0))
+        a = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
+        b = run_rollout(ctx, w, 0, theta, nd, a_mat, b_mat)
+        for x, y in zip(a, b):
+            assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), w.name
+    got = _case(es, replace(BASE, name="f32n-sigma0", sigma=0.0, envs=4))
+    assert np.all(got[2].view(np.uint32) == got[2].view(np.uint32)[0])
 
 
 def test_paper_base_shape_contractive_full_horizon_strict(es):
