@@ -847,7 +847,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               v = *reinterpret_cast<const f32x4*>(b3s + r0);
 #pragma unroll
               for (int ww = 0; ww < NW; ++ww) v += *reinterpret_cast<const f32x4*>(p3s + (ww * NC + col) * 32 + r0);
-              if (a.out_tanh) v = tanh4(v);
+              {      // branch-free: a select costs four instructions, the branch cost six register moves on the chain
+                const f32x4 tv = tanh4(v);
+                const bool squash = a.out_tanh != 0u;
+                v = f32x4{squash ? tv.x : v.x, squash ? tv.y : v.y, squash ? tv.z : v.z, squash ? tv.w : v.w};
+              }
             }
             float part = v.x * v.x;
             part = __fmaf_rn(v.y, v.y, part); part = __fmaf_rn(v.z, v.z, part); part = __fmaf_rn(v.w, v.w, part);
@@ -1095,7 +1099,11 @@ void rollout_mfma_kernel(const MfmaArgs a) {
               v[mt] = *reinterpret_cast<const f32x4*>(b3s + 16 * mt + 4 * g);
 #pragma unroll
               for (int ww = 0; ww < NW; ++ww) v[mt] += *reinterpret_cast<const f32x4*>(p3s + (ww * 16 + n) * V::PP3 + 16 * mt + 4 * g);
-              if (a.out_tanh) v[mt] = tanh4(v[mt]);
+              {
+                const f32x4 tv = tanh4(v[mt]);
+                const bool squash = a.out_tanh != 0u;
+                v[mt] = f32x4{squash ? tv.x : v[mt].x, squash ? tv.y : v[mt].y, squash ? tv.z : v[mt].z, squash ? tv.w : v[mt].w};
+              }
               part = __fmaf_rn(v[mt].x, v[mt].x, part); part = __fmaf_rn(v[mt].y, v[mt].y, part);
               part = __fmaf_rn(v[mt].z, v[mt].z, part); part = __fmaf_rn(v[mt].w, v[mt].w, part);
             }
