@@ -96,7 +96,7 @@ int launch_rollout_reg(es_ctx* ctx, uint32_t gen, const float* theta, const void
 int launch_rollout_mfma_f32(es_ctx* ctx, uint32_t gen, const float* theta, const void* noise,
                             const float* A, const float* B, float* returns, int32_t* ep_len,
                             float* fitness, void* ws, hipStream_t st);
-bool mfma_f32_fits(const es_config& cfg);         // binary32, 65..256 hidden units, two hidden layers, obs <= 64, act <= 16
+bool mfma_f32_fits(const es_config& cfg);         // binary32, 65..256 hidden units, one or two hidden layers, obs <= 64, act <= 16
 const char* mfma_f32_variant_name(const es_config& cfg, uint32_t copies);   // copies = episodes evaluated per individual
 int launch_fitness(es_ctx* ctx, const float* returns, float* fitness, hipStream_t st);
 int reg_variant_for(const es_config& cfg);        // -1 when no one-wavefront register-resident kernel is built for the shape

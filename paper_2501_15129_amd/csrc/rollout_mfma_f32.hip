@@ -462,8 +462,9 @@ struct LdsN {
   static constexpr int BYTES = OFF_WIN + 4 * WIN_FLOATS;
 };
 
-// KO: padded observation width (16, 32 or 64): the K extent of layer 1 and of A s
-template <int KO, bool RELU, bool NORM>
+// KO: padded observation width (16, 32 or 64): the K extent of layer 1 and of A s.  TWO: two hidden layers; with one
+// (the paper's depth sweep, Sec. 5.1) layer 1 feeds the action layer directly and a step has a single barrier.
+template <int KO, bool RELU, bool NORM, bool TWO>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void rollout_mfma_f32_narrow_kernel(const F32Args a) {
   using L = LdsN<KO>;
@@ -511,7 +512,7 @@ void rollout_mfma_f32_narrow_kernel(const F32Args a) {
     const ParamSrc ps{a.theta, nbase, a.noise_mode, a.ld, nrow, a.gen, a.k0, a.k1, scale};
     __syncthreads();          // the previous individual's last reads of the bias arrays are done
     // ---- perturbed parameters -> LDS window (coalesced) -> registers ----
-    float W1s[KO], W2k[4][64], W3k[16];
+    float W1s[KO], W2k[TWO ? 4 : 1][TWO ? 64 : 1], W3k[16];
     stage_params(win, NHP * KO, tid, ps, [&](int q) {
       const int row = q / KO, k = q - row * KO;
       return Slot{row * (KO + 1) + k, a.oW1 + (uint32_t)(row * no + k), row < nh && k < no};
@@ -520,16 +521,18 @@ void rollout_mfma_f32_narrow_kernel(const F32Args a) {
 #pragma unroll
     for (int k = 0; k < KO; ++k) W1s[k] = win[unit * (KO + 1) + k];           // W1[unit][k]
     __syncthreads();
+    if constexpr (TWO) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {      // rows 64 t .. 64 t + 63 of W2: the lane keeps row 64 t + lane, columns of its wavefront's K slice
-      stage_params(win, 64 * NHP, tid, ps, [&](int q) {
-        const int r = q >> 8, c = q & 255, row = 64 * t + r;
-        return Slot{r * PWN + c, a.oW2 + (uint32_t)(row * nh + c), row < nh && c < nh};
-      });
-      __syncthreads();
+      for (int t = 0; t < 4; ++t) {    // rows 64 t .. 64 t + 63 of W2: the lane keeps row 64 t + lane, columns of its wavefront's K slice
+        stage_params(win, 64 * NHP, tid, ps, [&](int q) {
+          const int r = q >> 8, c = q & 255, row = 64 * t + r;
+          return Slot{r * PWN + c, a.oW2 + (uint32_t)(row * nh + c), row < nh && c < nh};
+        });
+        __syncthreads();
 #pragma unroll
-      for (int kk = 0; kk < 64; ++kk) W2k[t][kk] = win[lane * PWN + 64 * w + kk];
-      __syncthreads();
+        for (int kk = 0; kk < 64; ++kk) W2k[t][kk] = win[lane * PWN + 64 * w + kk];
+        __syncthreads();
+      }
     }
     // action layer: lane (group g = blk / 4, ag = blk % 4, x) serves action row 4 ag + x; its K value number 4 a' + j'
     // is unit 64 w + 16 g + 4 a' + j' (block 4 g + a' of the transposed h2, register j')
@@ -541,10 +544,10 @@ void rollout_mfma_f32_narrow_kernel(const F32Args a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) W3k[r] = win[(4 * (blk & 3) + x) * PWN + 64 * w + 16 * (blk >> 2) + r];
     stage_params(b1s, NHP, tid, ps, [&](int u) { return Slot{u, a.ob1 + (uint32_t)u, u < nh}; });
-    stage_params(b2s, NHP, tid, ps, [&](int u) { return Slot{u, a.ob2 + (uint32_t)u, u < nh}; });
+    if constexpr (TWO) stage_params(b2s, NHP, tid, ps, [&](int u) { return Slot{u, a.ob2 + (uint32_t)u, u < nh}; });
     stage_params(b3s, 16, tid, ps, [&](int c) { return Slot{c, a.ob3 + (uint32_t)c, c < na}; });
     __syncthreads();
-    const float b1u = b1s[unit], b2u = b2s[unit];
+    const float b1u = b1s[unit], b2u = TWO ? b2s[unit] : 0.0f;
     f32x4 b3q = f32x4{0.f, 0.f, 0.f, 0.f};          // biases of action rows 4 blk .. 4 blk + 3 (blocks 0..3 hold the action)
     if (blk < 4) b3q = *reinterpret_cast<const f32x4*>(b3s + 4 * blk);
 
@@ -583,23 +586,26 @@ void rollout_mfma_f32_narrow_kernel(const F32Args a) {
           accE[r % 2] = mfma1_all<r / 4>(ts[r % 4], Ae[r], r < 2 ? zero4 : accE[r % 2]);
         });
         const f32x4 th1 = quad_transpose(hidden4<RELU>(acc1[0] + acc1[1]), xp0, xp1);
-        // ---- layer 2, this wavefront's K slice: partial sums of all 256 units ----
-        f32x4 acc2[4][2];
-        static_for<0, 64>([&](auto kc) {
-          constexpr int kk = decltype(kc)::value;
+        f32x4 th2 = th1;          // one hidden layer: layer 1 is the last
+        if constexpr (TWO) {
+          // ---- layer 2, this wavefront's K slice: partial sums of all 256 units ----
+          f32x4 acc2[4][2];
+          static_for<0, 64>([&](auto kc) {
+            constexpr int kk = decltype(kc)::value;
 #pragma unroll
-          for (int tt = 0; tt < 4; ++tt) {
-            pin_agpr(W2k[tt][kk]);
-            acc2[tt][kk % 2] = mfma1_all<kk / 4>(th1[kk % 4], W2k[tt][kk], kk < 2 ? zero4 : acc2[tt][kk % 2]);
-          }
-        });
+            for (int tt = 0; tt < 4; ++tt) {
+              pin_agpr(W2k[tt][kk]);
+              acc2[tt][kk % 2] = mfma1_all<kk / 4>(th1[kk % 4], W2k[tt][kk], kk < 2 ? zero4 : acc2[tt][kk % 2]);
+            }
+          });
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) *reinterpret_cast<f32x4*>(p2s + ((w * NHP + 64 * tt + lane) * NCN)) = acc2[tt][0] + acc2[tt][1];
-        __syncthreads();
-        f32x4 v2 = f32x4{b2u, b2u, b2u, b2u};
+          for (int tt = 0; tt < 4; ++tt) *reinterpret_cast<f32x4*>(p2s + ((w * NHP + 64 * tt + lane) * NCN)) = acc2[tt][0] + acc2[tt][1];
+          __syncthreads();
+          f32x4 v2 = f32x4{b2u, b2u, b2u, b2u};
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) v2 += *reinterpret_cast<const f32x4*>(p2s + ((ww * NHP + unit) * NCN));
-        const f32x4 th2 = quad_transpose(hidden4<RELU>(v2), xp0, xp1);
+          for (int ww = 0; ww < 4; ++ww) v2 += *reinterpret_cast<const f32x4*>(p2s + ((ww * NHP + unit) * NCN));
+          th2 = quad_transpose(hidden4<RELU>(v2), xp0, xp1);
+        }
         // ---- action layer, K slice of this wavefront: four K values per instruction ----
         f32x4 acc3p[4];
         static_for<0, 16>([&](auto rc) {
@@ -658,20 +664,24 @@ void rollout_mfma_f32_narrow_kernel(const F32Args a) {
   }
 }
 
-template <int KO, bool RELU, bool NORM>
+template <int KO, bool RELU, bool NORM, bool TWO>
 int launch_narrow_one(es_ctx* ctx, const F32Args& a, hipStream_t st) {
-  const void* fn = reinterpret_cast<const void*>(rollout_mfma_f32_narrow_kernel<KO, RELU, NORM>);
+  const void* fn = reinterpret_cast<const void*>(rollout_mfma_f32_narrow_kernel<KO, RELU, NORM, TWO>);
   hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LdsN<KO>::BYTES);
   if (err != hipSuccess) return fail(ctx, ES_EHIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(err));
   const uint32_t grid = std::min<uint32_t>(a.N, (uint32_t)std::max(1, ctx->num_cus));      // persistent: one workgroup per CU
-  hipLaunchKernelGGL((rollout_mfma_f32_narrow_kernel<KO, RELU, NORM>), dim3(grid), dim3(256), LdsN<KO>::BYTES, st, a);
+  hipLaunchKernelGGL((rollout_mfma_f32_narrow_kernel<KO, RELU, NORM, TWO>), dim3(grid), dim3(256), LdsN<KO>::BYTES, st, a);
   return check_launch(ctx, "es_rollout (fp32 MFMA, four copies)");
+}
+template <int KO, bool TWO>
+int launch_narrow_depth(es_ctx* ctx, const F32Args& a, hipStream_t st) {
+  const bool relu = ctx->cfg.hidden_act == 1, norm = ctx->obs_mean != nullptr;
+  if (relu) return norm ? launch_narrow_one<KO, true, true, TWO>(ctx, a, st) : launch_narrow_one<KO, true, false, TWO>(ctx, a, st);
+  return norm ? launch_narrow_one<KO, false, true, TWO>(ctx, a, st) : launch_narrow_one<KO, false, false, TWO>(ctx, a, st);
 }
 template <int KO>
 int launch_narrow(es_ctx* ctx, const F32Args& a, hipStream_t st) {
-  const bool relu = ctx->cfg.hidden_act == 1, norm = ctx->obs_mean != nullptr;
-  if (relu) return norm ? launch_narrow_one<KO, true, true>(ctx, a, st) : launch_narrow_one<KO, true, false>(ctx, a, st);
-  return norm ? launch_narrow_one<KO, false, true>(ctx, a, st) : launch_narrow_one<KO, false, false>(ctx, a, st);
+  return ctx->shp.m == 1 ? launch_narrow_depth<KO, false>(ctx, a, st) : launch_narrow_depth<KO, true>(ctx, a, st);
 }
 
 template <int KPL, bool RELU, bool NORM>
@@ -692,17 +702,21 @@ int launch_kpl(es_ctx* ctx, const F32Args& a, hipStream_t st) {
 
 }  // namespace
 
-// Binary32 policies with 65..256 hidden units, two hidden layers, obs <= 64, act <= 16.
+// Binary32 policies with 65..256 hidden units, one or two hidden layers, obs <= 64, act <= 16.
 bool mfma_f32_fits(const es_config& c) {
   const uint32_t m = c.num_hidden ? c.num_hidden : 2;
-  return c.dtype == 0 && m == 2 && c.hid_dim > 64 && c.hid_dim <= (uint32_t)NHP && c.obs_dim <= 64 && c.act_dim <= 16;
+  return c.dtype == 0 && (m == 1 || m == 2) && c.hid_dim > 64 && c.hid_dim <= (uint32_t)NHP && c.obs_dim <= 64 && c.act_dim <= 16;
 }
 
-// up to eight copies per individual: two passes of the four-copy kernel cost less than one pass of sixteen columns
-static bool narrow_pays(uint32_t copies) { return copies <= 2u * (uint32_t)NCN; }
+// up to eight copies per individual: two passes of the four-copy kernel cost less than one pass of sixteen columns;
+// a single hidden layer is served by the four-copy kernel whatever the number of copies
+static bool narrow_pays(const es_config& c, uint32_t copies) { return copies <= 2u * (uint32_t)NCN || c.num_hidden == 1; }
 
 const char* mfma_f32_variant_name(const es_config& c, uint32_t copies) {
-  if (narrow_pays(copies))
+  if (c.num_hidden == 1)
+    return c.obs_dim <= 16 ? "rollout_mfma_reg_f32<obs16,hid256,act16,copies4>,depth1"
+         : c.obs_dim <= 32 ? "rollout_mfma_reg_f32<obs32,hid256,act16,copies4>,depth1" : "rollout_mfma_reg_f32<obs64,hid256,act16,copies4>,depth1";
+  if (narrow_pays(c, copies))
     return c.obs_dim <= 16 ? "rollout_mfma_reg_f32<obs16,hid256,act16,copies4>"
          : c.obs_dim <= 32 ? "rollout_mfma_reg_f32<obs32,hid256,act16,copies4>" : "rollout_mfma_reg_f32<obs64,hid256,act16,copies4>";
   return c.obs_dim <= 32 ? "rollout_mfma_reg_f32<obs32,hid256,act16>" : "rollout_mfma_reg_f32<obs64,hid256,act16>";
@@ -723,7 +737,7 @@ int launch_rollout_mfma_f32(es_ctx* ctx, uint32_t gen, const float* theta, const
   a.gen = gen; a.k0 = (uint32_t)c.seed; a.k1 = (uint32_t)(c.seed >> 32);
   a.antithetic = c.antithetic; a.out_tanh = c.out_tanh; a.noise_mode = nv.mode;
   a.sigma = c.sigma; a.done_thresh = c.done_thresh; a.act_cost = c.act_cost;
-  if (narrow_pays(s.E)) {
+  if (narrow_pays(c, s.E)) {
     if (s.no <= 16) return launch_narrow<16>(ctx, a, st);
     return s.no <= 32 ? launch_narrow<32>(ctx, a, st) : launch_narrow<64>(ctx, a, st);
   }

@@ -78,6 +78,10 @@ def _case(es, w, gen=1, obs_norm=None):
     replace(BASE, name="f32n-fixedlen-bf16noise", envs=4, done_thresh=math.inf, horizon=80, noise_dtype=1),
     replace(BASE, name="f32n-table-bf16", noise_dtype=5, noise_table_len=1 << 18, envs=3),
     replace(BASE, name="f32n-regen-rounded", noise_dtype=3, envs=5),
+    # one hidden layer (the paper's depth sweep): the four-copy kernel whatever the number of copies
+    replace(BASE, name="f32n-depth1-paper-8-256-2-E1", obs=8, act=2, envs=1, horizon=60, num_hidden=1),
+    replace(BASE, name="f32n-depth1-40-200-11-E16-relu", obs=40, hid=200, act=11, num_hidden=1, hidden_act=1),
+    replace(BASE, name="f32n-depth1-64-129-16-E6-fixedlen", obs=64, hid=129, act=16, envs=6, num_hidden=1, done_thresh=math.inf),
 ], ids=lambda w: w.name)
 def test_rollout_f32_wide(es, w):
     _case(es, w)
@@ -87,6 +91,8 @@ def test_four_copy_variant_is_chosen_up_to_eight_copies(es):
     for envs, episodes, narrow in ((1, 1, True), (4, 2, True), (8, 1, True), (3, 3, False), (16, 1, False)):
         ctx = es.EsContext(replace(BASE, envs=envs, episodes=episodes))
         assert ("copies4" in ctx.rollout_kernel) == narrow, (envs, episodes, ctx.rollout_kernel)
+    ctx = es.EsContext(replace(BASE, num_hidden=1))
+    assert "copies4" in ctx.rollout_kernel and "depth1" in ctx.rollout_kernel, ctx.rollout_kernel
 
 
 def test_rollout_f32_wide_with_observation_statistics(es):
