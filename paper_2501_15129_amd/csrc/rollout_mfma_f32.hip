@@ -20,6 +20,9 @@
 //     termination test are reduced inside a wavefront with the row-swap instructions and across wavefronts
 //     through one LDS partial per wavefront, added by every lane in the same order: reruns are bit-identical.
 // Bound: the fp32 MFMA pipe (32 cycles per 16x16x4 instruction, 4 (KPL + 64 + 4) + KPL + 4 of them per step).
+//
+// Up to eight copies per individual (and policies with ONE hidden layer) run on a second kernel further down, built on the
+// 4x4x1 shape with four copies per pass: a quarter of the matrix-pipe time when only one to four columns carry episodes.
 #include <algorithm>
 #include <type_traits>
 
