@@ -224,6 +224,15 @@ def test_rollout_contractive_twins_full_size(es, idx):
     assert float(np.std(got[2])) > 1e-3 * abs(float(np.mean(got[2])))
 
 
+def test_rollout_contractive_twin_sixteen_copies_two_action_tiles(es):
+    """configs[4]'s shapes with four episodes per environment copy - sixteen columns per pass, the K-split action layer with
+    two action tiles - on the contractive twin at the full horizon: strict 2e-2 per episode on 16 mirrored pairs."""
+    w = replace(CONFIGS[4].contractive(), name="cfg4-contractive-k4-n256", pop=256, episodes=4)
+    got, chaotic = _full_size_sampled(es, w, gen=0, n_blocks=2, probes=1)
+    assert np.all(got[1] == w.horizon) and not chaotic
+    assert compare_rollout.last_excused == 0 and compare_rollout.last_sensitive == 0
+
+
 @pytest.mark.parametrize("idx", [1, 2])
 def test_rollout_contractive_twins_fp32(es, idx):
     """configs[1] / [2]'s twins, every episode, strict 1e-4 at T = 1000, none sensitive, none excused."""
