@@ -233,6 +233,16 @@ def test_rollout_contractive_twin_sixteen_copies_two_action_tiles(es):
     assert compare_rollout.last_excused == 0 and compare_rollout.last_sensitive == 0
 
 
+@pytest.mark.parametrize("m", [1, 3, 4])
+def test_rollout_contractive_twin_other_depths_full_horizon(es, m):
+    """configs[3]'s shapes with one, three and four hidden layers (the paper's depth sweep, Sec. 5.1) on the contractive twin,
+    sixteen copies, T = 1000: every episode of a small population strictly within 2e-2."""
+    w = replace(CONFIGS[3].contractive(), name=f"cfg3-contractive-m{m}-n8", pop=8, num_hidden=m)
+    got, _ = _case(es, w, gen=0)
+    assert np.all(got[1] == w.horizon)
+    assert compare_rollout.last_excused == 0
+
+
 @pytest.mark.parametrize("idx", [1, 2])
 def test_rollout_contractive_twins_fp32(es, idx):
     """configs[1] / [2]'s twins, every episode, strict 1e-4 at T = 1000, none sensitive, none excused."""
