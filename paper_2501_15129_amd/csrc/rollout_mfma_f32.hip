@@ -339,14 +339,15 @@ void rollout_mfma_f32_kernel(const F32Args a) {
             }
         }
         // this wavefront's K slice of the action layer, from the registers that hold its h2
-        f32x4 p3 = f32x4{0.f, 0.f, 0.f, 0.f};
+        // (four partial accumulators: a dependent 16x16x4 MFMA waits out the previous one's eight passes)
+        f32x4 p3q[4];
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
           const f32x4 h = hidden4<RELU>(acc[tt]);
 #pragma unroll
-          for (int r = 0; r < 4; ++r) p3 = mfma4(W3k[4 * tt + r], h[r], p3);
+          for (int r = 0; r < 4; ++r) p3q[r] = mfma4(W3k[4 * tt + r], h[r], tt == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : p3q[r]);
         }
-        *reinterpret_cast<f32x4*>(p3s + (w * NCOL + n) * 16 + 4 * g) = p3;
+        *reinterpret_cast<f32x4*>(p3s + (w * NCOL + n) * 16 + 4 * g) = (p3q[0] + p3q[1]) + (p3q[2] + p3q[3]);
         __syncthreads();
         // ---- phase D: a = tanh(sum of the partials + b3); s' = tanh(A s + B a); norms ----
         f32x4 v = *reinterpret_cast<const f32x4*>(b3s + 4 * g);
